@@ -1,0 +1,254 @@
+/*
+ * demand_layering.h — C ABI of the pipelined Demand Layering library for MI355X (gfx950).
+ *
+ * The library runs a transformer layer stack whose BF16 parameters live in
+ * pinned host memory: each streamed layer is copied host -> device into one of
+ * two device slots on a copy stream while the previous layer computes on the
+ * compute stream, and a chosen subset of layers stays device-resident.
+ *
+ * Conventions
+ *   - Every call returns an int32_t: DL_OK (0) or a negative DL_ERR_* code;
+ *     dl_last_error(ctx) gives a NUL-terminated message owned by the context.
+ *   - A failed call leaves the context unchanged (a residency set that does
+ *     not fit is rejected whole).
+ *   - A context is used from one host thread.  No C++ type crosses the ABI.
+ *   - "host" / "device" in a parameter comment says where the pointer lives.
+ *   - BF16 data is passed as raw 16-bit patterns; matrices are row-major
+ *     [out_features, in_features] (a linear map is y = x * W^T + b).
+ *   - The caller owns: its source tensors (copied by the call that takes
+ *     them), the arena block, the two streams.  The library owns: the pinned
+ *     parameter store, its events, and whatever it carves out of the arena.
+ *   - All device memory the library uses comes out of the arena: the arena
+ *     size IS the device-memory cap.
+ */
+#ifndef DEMAND_LAYERING_H
+#define DEMAND_LAYERING_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dl_ctx dl_ctx;
+
+enum {
+    DL_OK = 0,
+    DL_ERR_INVALID_ARG = -1,
+    DL_ERR_BUDGET_EXCEEDED = -2,
+    DL_ERR_HOST_ALLOC = -3,
+    DL_ERR_DEVICE = -4,
+    DL_ERR_BAD_STATE = -5
+};
+
+enum { DL_NORM_RMS = 0, DL_NORM_LN = 1 };
+enum { DL_ACT_SWIGLU = 0, DL_ACT_GELU = 1 };
+/* Sec. IV-B (sequential: copy, then compute, never overlapped) and Sec. IV-C (pipelined) */
+enum { DL_MODE_PIPELINED = 0, DL_MODE_SEQUENTIAL = 1 };
+
+/* per-layer parameter tensors */
+enum {
+    DL_T_NORM1_G = 0, DL_T_NORM1_B = 1,
+    DL_T_WQ = 2, DL_T_WK = 3, DL_T_WV = 4, DL_T_BQ = 5, DL_T_BK = 6, DL_T_BV = 7,
+    DL_T_WO = 8, DL_T_BO = 9,
+    DL_T_NORM2_G = 10, DL_T_NORM2_B = 11,
+    DL_T_W_GATE = 12, DL_T_W_UP = 13, DL_T_B_UP = 14, DL_T_W_DOWN = 15, DL_T_B_DOWN = 16,
+    DL_T_NORMC_G = 17, DL_T_NORMC_B = 18,
+    DL_T_WQ_C = 19, DL_T_WK_C = 20, DL_T_WV_C = 21, DL_T_BQ_C = 22, DL_T_BK_C = 23, DL_T_BV_C = 24,
+    DL_T_WO_C = 25, DL_T_BO_C = 26,
+    DL_T_COUNT = 27
+};
+
+/* always-resident non-layer parameters (Sec. IV-D: non-layer components stay resident in every configuration) */
+enum { DL_R_EMBED = 0, DL_R_HEAD = 1, DL_R_FINAL_NORM_G = 2, DL_R_FINAL_NORM_B = 3, DL_R_COUNT = 4 };
+
+/*
+ * One layer stack ("module" in the paper: vision encoder, VLM backbone, expert decoder).
+ * Block: h = x + Attn(Norm1 x) [+ CrossAttn(NormC h, ctx) if d_ctx > 0];  y = h + FFN(Norm2 h).
+ */
+typedef struct {
+    int32_t n_layers;
+    int32_t d_model;
+    int32_t n_q_heads, n_kv_heads, d_head;   /* n_q_heads % n_kv_heads == 0; d_head % 8 == 0, <= 128 */
+    int32_t d_ff;                            /* % 32 == 0 for SwiGLU, % 8 == 0 for GELU */
+    int32_t norm;                            /* DL_NORM_* */
+    int32_t act;                             /* DL_ACT_*: SwiGLU (gate, up, down) or GELU-tanh MLP (up, down) */
+    int32_t has_bias;                        /* biases on every linear map */
+    int32_t causal;
+    int32_t d_ctx;                           /* > 0: cross-attention over a [n_ctx, d_ctx] source */
+    int32_t max_seq;                         /* > 0: KV cache with this many positions (forward may then be called with pos0 > 0) */
+    int32_t max_tokens;                      /* largest n_tokens of any forward call; sizes the activation workspace */
+    int32_t max_ctx;                         /* largest n_ctx (cross-attention), 0 if none */
+    int32_t vocab;                           /* > 0: embedding table and output head [vocab, d_model] */
+    float rope_theta;                        /* 0 = no rotary embedding; else pair (i, i + d_head/2), angle pos * theta^(-2i/d_head) */
+    float norm_eps;
+} dl_module_desc;
+
+/* ---- context ---------------------------------------------------------------------------- */
+
+/* device >= 0: HIP device ordinal (made current on every call).  device == -1: host-only
+ * context — nothing touches a GPU: parameters go to ordinary host memory, the arena is pure
+ * accounting, dl_forward only records its schedule (see dl_trace_read).  Used for planning
+ * and for checking the slot protocol without a GPU.  *out is owned by the library. */
+int32_t dl_create(dl_ctx** out, int32_t device);
+int32_t dl_destroy(dl_ctx* ctx);
+const char* dl_last_error(const dl_ctx* ctx);
+
+/* The device-memory budget.  dev_base: device pointer to a block of `bytes` bytes the caller
+ * allocated and keeps alive until dl_destroy; 256-byte aligned.  Must be set once, before any
+ * module is finalized.  Sec. IV-D: residency costs VRAM; here every device byte is counted. */
+int32_t dl_set_arena(dl_ctx* ctx, void* dev_base, uint64_t bytes);
+/* Sub-allocate from the arena for the caller's activations (counted against the cap).
+ * DL_ERR_BUDGET_EXCEEDED if it does not fit. */
+int32_t dl_arena_alloc(dl_ctx* ctx, uint64_t bytes, void** dev_ptr_out);
+int32_t dl_arena_free(dl_ctx* ctx, void* dev_ptr);
+int32_t dl_arena_stats(const dl_ctx* ctx, uint64_t* used, uint64_t* peak, uint64_t* capacity);
+
+/* compute_stream / copy_stream: hipStream_t handles owned by the caller; distinct; default priority.
+ * Sec. IV-C: one queue executes layers, the other prefetches parameters. */
+int32_t dl_set_streams(dl_ctx* ctx, void* compute_stream, void* copy_stream);
+
+/* ---- registering a layer stack (one-time, untimed) ------------------------------------- */
+
+/* Allocates the module's pinned host parameter store (Sec. IV-C(iii)), one contiguous
+ * kernel-ready blob per layer so that a layer is ONE host-to-device copy. */
+int32_t dl_module_create(dl_ctx* ctx, const dl_module_desc* desc, int32_t* module_out);
+/* host_bf16: host pointer, n_elems BF16 values, shape fixed by the descriptor (see DL_T_*).
+ * The data is COPIED into the packed blob (fused / interleaved as the kernels read it). */
+int32_t dl_layer_set_tensor(dl_ctx* ctx, int32_t module, int32_t layer, int32_t tensor_id,
+                            const void* host_bf16, uint64_t n_elems);
+/* host_bf16 -> arena (device-resident for the module's lifetime). Needs the arena. */
+int32_t dl_set_resident_tensor(dl_ctx* ctx, int32_t module, int32_t which, const void* host_bf16, uint64_t n_elems);
+/* All tensors of all layers must have been set.  Sizes the two shared slots to the largest
+ * layer over all finalized modules (Sec. IV-C(i): 2 x M_max) and carves the module's KV
+ * cache and activation workspace out of the arena. */
+int32_t dl_module_finalize(dl_ctx* ctx, int32_t module);
+/* packed_bytes: bytes of one layer's blob (what one copy moves); param_bytes: 2 * parameter count. */
+int32_t dl_module_layer_bytes(const dl_ctx* ctx, int32_t module, uint64_t* packed_bytes, uint64_t* param_bytes);
+
+/* ---- residency (Sec. IV-D) ------------------------------------------------------------- */
+
+/* layer_idx: host array of n distinct layer indices that stay device-resident; the rest stream.
+ * Uploads newly resident layers, releases dropped ones.  n == n_layers for every module
+ * releases the two slots.  Synchronises both streams.  DL_ERR_BUDGET_EXCEEDED: nothing changed. */
+int32_t dl_set_residency(dl_ctx* ctx, int32_t module, const int32_t* layer_idx, int32_t n);
+/* idx_out: host array of capacity n_layers; *n_out = count */
+int32_t dl_get_residency(const dl_ctx* ctx, int32_t module, int32_t* idx_out, int32_t* n_out);
+
+/* mode: DL_MODE_*.  wrap_prefetch != 0: at the end of a forward pass the first streamed layer of the
+ * module is prefetched for the next pass (valid while the next pass uses the same module; another
+ * module's pass simply re-issues its own first copy). */
+int32_t dl_set_mode(dl_ctx* ctx, int32_t mode, int32_t wrap_prefetch);
+
+/* ---- the hot path (Sec. IV-C) ------------------------------------------------------------ */
+
+/* One pass over all layers of `module`; enqueues only, returns before the GPU finishes.
+ * x_dev: device fp32 [n_tokens, d_model] input;  y_dev: device fp32 [n_tokens, d_model] output
+ * (may equal x_dev).  Token t sits at absolute position pos0 + t; with a KV cache the pass appends
+ * its keys/values at those positions and attends over 0 .. pos0+t.  pos0 must be 0 without a cache.
+ * ctx_dev: device fp32 [n_ctx, d_ctx] (cross-attention source) or NULL.
+ * n_tokens <= 4 takes the decode kernels (weight-streaming GEMV), otherwise the MFMA GEMM path. */
+int32_t dl_forward(dl_ctx* ctx, int32_t module, const void* x_dev, void* y_dev, int32_t n_tokens,
+                   int32_t pos0, const void* ctx_dev, int32_t n_ctx);
+/* x_dev[d_model] (fp32) = embedding row `token`, on the compute stream. */
+int32_t dl_embed_token(dl_ctx* ctx, int32_t module, int32_t token, void* x_dev);
+/* out_dev fp32 [n_tokens, d_model] = FinalNorm(h_dev), on the compute stream. */
+int32_t dl_final_norm(dl_ctx* ctx, int32_t module, const void* h_dev, void* out_dev, int32_t n_tokens);
+/* Greedy head on one fp32 hidden vector h_dev[d_model]: logits = FinalNorm(h) * W_head^T in fp32,
+ * token = lowest index of the maximum.  Synchronises the compute stream.  token_out: host.
+ * logits_out_host: host fp32 [vocab] or NULL. */
+int32_t dl_logits_argmax(dl_ctx* ctx, int32_t module, const void* h_dev, int32_t* token_out, float* logits_out_host);
+/* As above but leaves the token on the device and feeds it back: x_dev[d_model] = E[token].  No host sync.
+ * token_dev: device int32[1]. */
+int32_t dl_greedy_step(dl_ctx* ctx, int32_t module, const void* h_dev, int32_t* token_dev, void* x_dev);
+int32_t dl_sync(dl_ctx* ctx);
+
+/* ---- measurement ------------------------------------------------------------------------ */
+
+typedef struct {
+    double c_dma_ms;      /* un-overlapped host-to-device copy time of the layer */
+    double c_exe_ms;      /* un-overlapped execution time of the layer */
+    uint64_t bytes;       /* bytes one copy moves */
+} dl_layer_profile;
+
+/* Sec. II-C / Table III: runs the module in sequential mode `iters` times at (n_tokens, pos0),
+ * discards the first iteration, writes per-layer means.  Every layer is copied (into a slot)
+ * and timed regardless of residency.  out: host array [n_layers].  Restores the KV-cache
+ * contents it touches only in the sense that positions pos0.. are rewritten by the next real pass. */
+int32_t dl_profile(dl_ctx* ctx, int32_t module, int32_t n_tokens, int32_t pos0, const void* x_dev,
+                   const void* ctx_dev, int32_t n_ctx, int32_t iters, dl_layer_profile* out);
+
+typedef struct {
+    double total_ms;          /* first op start to last op end, over the recorded passes */
+    double dma_ms;            /* summed copy durations */
+    double exe_ms;            /* summed layer execution durations */
+    double exposed_ms;        /* summed time the compute stream idled on a DMA-done event */
+    double hidden_frac;       /* 1 - exposed/dma (1 when nothing streamed) */
+    double h2d_gbps;          /* bytes_streamed / dma_ms */
+    uint64_t bytes_streamed;
+    uint64_t arena_peak;
+    int32_t n_layer_records;  /* layer invocations recorded */
+} dl_run_stats;
+
+typedef struct {
+    int32_t module, layer, streamed, slot;
+    float dma_start_ms, dma_end_ms, exe_start_ms, exe_end_ms;   /* relative to the first recorded op */
+} dl_layer_record;
+
+/* on != 0: subsequent forward passes record timing events around every copy and every layer
+ * until dl_collect_stats, which synchronises, fills *stats (and up to cap per-layer records,
+ * may be NULL), and resets the recording. */
+int32_t dl_set_timing(dl_ctx* ctx, int32_t on);
+int32_t dl_collect_stats(dl_ctx* ctx, dl_run_stats* stats, dl_layer_record* records, int32_t cap);
+
+/* The schedule one forward pass enqueues, as data (also recorded by host-only contexts). */
+enum { DL_OP_WAIT = 0, DL_OP_RECORD = 1, DL_OP_COPY = 2, DL_OP_EXEC = 3 };
+enum { DL_EV_DMA_DONE = 0, DL_EV_COMPUTE_DONE = 1, DL_EV_PASS_DONE = 2 };
+typedef struct {
+    int32_t queue;       /* 0 = compute stream, 1 = copy stream */
+    int32_t op;          /* DL_OP_* */
+    int32_t event_kind;  /* DL_EV_* for WAIT / RECORD, else -1 */
+    int32_t slot;        /* slot the event / copy / exec refers to, -1 = resident exec */
+    int32_t module, layer;
+} dl_trace_op;
+int32_t dl_trace_enable(dl_ctx* ctx, int32_t on);
+/* copies up to cap ops, *n_out = number recorded since the last read; then clears the trace */
+int32_t dl_trace_read(dl_ctx* ctx, dl_trace_op* out, int32_t cap, int32_t* n_out);
+
+/* ---- planner and predictor: pure host functions (usable with ctx == NULL semantics: no ctx taken) ---- */
+
+/* Eq. 8 generalised to L layers: idx_out[i] = floor(i * (L-1) / k), i < k, for 1 <= k <= L-1
+ * (first layer in, last layer out); k == 0: nothing; k == L: every layer.  idx_out: host, capacity k. */
+int32_t dl_place_interleaved(int32_t n_layers, int32_t k, int32_t* idx_out);
+
+/* Residency benefit by position, Eq. 4 with Tables IV-VI.  A module is used in n_phases phases per
+ * inference; phase p runs reps[p] passes with per-layer execution time c_exe_ms[p] (e.g. prefill x1,
+ * decode xN).  c_dma_ms, m_mib: per-layer copy time and footprint in MiB.
+ * out3 = {B_first, B_middle, B_last} in ms per MiB. */
+int32_t dl_benefit(double c_dma_ms, double m_mib, int32_t n_phases, const double* c_exe_ms,
+                   const int32_t* reps, double* out3);
+/* floor(c_dma / c_exe): the consecutive residency limit of Sec. IV-D. */
+int32_t dl_consecutive_limit(double c_dma_ms, double c_exe_ms, int32_t* out);
+/* Eq. 9: *out = c_total0 - k * slope, slope = B * M in ms per layer. */
+int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t k, double* out);
+
+/* The two-event protocol of Sec. IV-C(ii) as a recurrence over a flattened sequence of n layer
+ * invocations.  c_dma_ms[j], c_exe_ms[j]: times of invocation j; streamed[j] != 0 if its parameters
+ * are copied; pass_start[j] != 0 marks the first layer of a pass.  overhead_ms is added to every
+ * invocation's execution (fixed host/launch cost).  total_ms, hidden_frac, exposed_ms: outputs
+ * (any may be NULL). */
+int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_t* streamed,
+                    const uint8_t* pass_start, int32_t n, int32_t wrap_prefetch, double overhead_ms,
+                    double* total_ms, double* hidden_frac, double* exposed_ms);
+
+/* Budgeted choice of resident layers over several modules from one profiling run (Sec. IV-D).
+ * Per module m: n_layers[m], layer_bytes[m], b3[3*m..] = {B_first, B_mid, B_last} (ms/MiB).
+ * Greedy by benefit per MiB: a module's first layer, then its middle layers, then its last layer.
+ * k_out[m] = resident count for module m (indices then come from dl_place_interleaved). */
+int32_t dl_plan(int32_t n_modules, const int32_t* n_layers, const uint64_t* layer_bytes,
+                const double* b3, uint64_t budget_bytes, int32_t* k_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEMAND_LAYERING_H */
