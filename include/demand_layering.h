@@ -204,12 +204,14 @@ int32_t dl_collect_stats(dl_ctx* ctx, dl_run_stats* stats, dl_layer_record* reco
 /* The schedule one forward pass enqueues, as data (also recorded by host-only contexts). */
 enum { DL_OP_WAIT = 0, DL_OP_RECORD = 1, DL_OP_COPY = 2, DL_OP_EXEC = 3 };
 enum { DL_EV_DMA_DONE = 0, DL_EV_COMPUTE_DONE = 1, DL_EV_PASS_DONE = 2 };
+enum { DL_OPF_NEXT_PASS = 1 };   /* a copy that prefetches the first streamed layer of the NEXT pass */
 typedef struct {
     int32_t queue;       /* 0 = compute stream, 1 = copy stream */
     int32_t op;          /* DL_OP_* */
     int32_t event_kind;  /* DL_EV_* for WAIT / RECORD, else -1 */
     int32_t slot;        /* slot the event / copy / exec refers to, -1 = resident exec */
     int32_t module, layer;
+    int32_t flags;       /* DL_OPF_* */
 } dl_trace_op;
 int32_t dl_trace_enable(dl_ctx* ctx, int32_t on);
 /* copies up to cap ops, *n_out = number recorded since the last read; then clears the trace */
@@ -232,13 +234,17 @@ int32_t dl_consecutive_limit(double c_dma_ms, double c_exe_ms, int32_t* out);
 /* Eq. 9: *out = c_total0 - k * slope, slope = B * M in ms per layer. */
 int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t k, double* out);
 
-/* The two-event protocol of Sec. IV-C(ii) as a recurrence over a flattened sequence of n layer
- * invocations.  c_dma_ms[j], c_exe_ms[j]: times of invocation j; streamed[j] != 0 if its parameters
- * are copied; pass_start[j] != 0 marks the first layer of a pass.  overhead_ms is added to every
- * invocation's execution (fixed host/launch cost).  total_ms, hidden_frac, exposed_ms: outputs
- * (any may be NULL). */
+/* Predicted time of a sequence of passes: replays the schedule dl_forward enqueues (the two-event
+ * protocol of Sec. IV-C(ii)) on two in-order queues.  Eq. 1, 2, 5, 6, 7 are special cases.
+ * The n layer invocations of all passes are flattened: c_dma_ms[j], c_exe_ms[j] = times of
+ * invocation j; streamed[j] != 0 if its parameters are copied; pass_start[j] != 0 marks the first
+ * layer of a pass; module_id[j] (NULL = all the same) tells passes over different stacks apart.
+ * mode, wrap_prefetch: as dl_set_mode.  overhead_ms is added to every execution (fixed
+ * host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
+ * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
 int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_t* streamed,
-                    const uint8_t* pass_start, int32_t n, int32_t wrap_prefetch, double overhead_ms,
+                    const uint8_t* pass_start, const int32_t* module_id, int32_t n, int32_t mode,
+                    int32_t wrap_prefetch, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms);
 
 /* Budgeted choice of resident layers over several modules from one profiling run (Sec. IV-D).

@@ -1,0 +1,875 @@
+// C ABI of the library: context, pinned parameter store, residency, the pipelined forward pass
+// (Sec. IV-C), profiling (Table III procedure) and run statistics.  HIP backend: one copy stream,
+// one compute stream, event fences between them.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "dl_internal.hpp"
+#include "kernels.hpp"
+
+using dl::PackLayout;
+
+namespace {
+
+struct Module {
+    dl_module_desc d{};
+    PackLayout L;
+    dl::WorkspaceLayout W;
+    dl::KvLayout KV;
+    uint8_t* store = nullptr;            // n_layers blobs, pinned (or plain malloc in a host-only context)
+    std::vector<uint32_t> set_mask;      // per layer: which tensors have been provided
+    bool finalized = false;
+    std::vector<uint8_t> resident;       // per layer
+    std::vector<uint64_t> res_off;       // arena offset of the resident copy
+    uint64_t ws_off = 0, kv_off = 0;
+    uint64_t rt_off[DL_R_COUNT] = {0, 0, 0, 0};
+    bool rt_set[DL_R_COUNT] = {false, false, false, false};
+};
+
+struct TimedOp {
+    hipEvent_t e0, e1;
+    int32_t module, layer, slot;
+    int32_t copy_index;                  // for EXEC of a streamed layer: index into copies, else -1
+};
+
+}  // namespace
+
+struct dl_ctx {
+    int32_t device = -1;
+    std::string err;
+    dl::Arena arena;
+    uint8_t* base = nullptr;
+    hipStream_t s_compute = nullptr, s_copy = nullptr;
+    bool streams_set = false;
+    std::vector<Module> mods;
+    uint64_t slot_bytes = 0;
+    uint64_t slot_off[2] = {0, 0};
+    bool slots_alloc = false;
+    dl::SlotBook book;
+    hipEvent_t ev_dma[2] = {nullptr, nullptr}, ev_comp[2] = {nullptr, nullptr}, ev_pass = nullptr;
+    bool events_made = false;
+    int32_t mode = DL_MODE_PIPELINED, wrap = 0;
+    bool tracing = false;
+    std::vector<dl_trace_op> trace;
+    bool timing = false;
+    std::vector<TimedOp> copies, execs;
+    int32_t last_copy_in_slot[2] = {-1, -1};
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_next = 0;
+};
+
+namespace {
+
+int32_t fail(dl_ctx* c, int32_t code, const std::string& msg) {
+    if (c) c->err = msg;
+    return code;
+}
+
+#define DL_HIP(c, call)                                                                              \
+    do {                                                                                             \
+        hipError_t e_ = (call);                                                                      \
+        if (e_ != hipSuccess)                                                                        \
+            return fail((c), DL_ERR_DEVICE, std::string(#call) + ": " + hipGetErrorString(e_));      \
+    } while (0)
+
+bool on_gpu(const dl_ctx* c) { return c->device >= 0; }
+
+int32_t enter(dl_ctx* c) {
+    if (!c) return DL_ERR_INVALID_ARG;
+    if (on_gpu(c)) DL_HIP(c, hipSetDevice(c->device));
+    return DL_OK;
+}
+
+Module* get_module(dl_ctx* c, int32_t m) {
+    if (m < 0 || size_t(m) >= c->mods.size()) return nullptr;
+    return &c->mods[size_t(m)];
+}
+
+int32_t make_events(dl_ctx* c) {
+    if (c->events_made || !on_gpu(c)) return DL_OK;
+    for (int s = 0; s < 2; ++s) {
+        DL_HIP(c, hipEventCreateWithFlags(&c->ev_dma[s], hipEventDisableTiming));
+        DL_HIP(c, hipEventCreateWithFlags(&c->ev_comp[s], hipEventDisableTiming));
+    }
+    DL_HIP(c, hipEventCreateWithFlags(&c->ev_pass, hipEventDisableTiming));
+    c->events_made = true;
+    return DL_OK;
+}
+
+int32_t timing_event(dl_ctx* c, hipEvent_t* out) {
+    if (c->ev_next == c->ev_pool.size()) {
+        hipEvent_t e;
+        DL_HIP(c, hipEventCreate(&e));
+        c->ev_pool.push_back(e);
+    }
+    *out = c->ev_pool[c->ev_next++];
+    return DL_OK;
+}
+
+int32_t sync_streams(dl_ctx* c) {
+    if (on_gpu(c) && c->streams_set) {
+        DL_HIP(c, hipStreamSynchronize(c->s_copy));
+        DL_HIP(c, hipStreamSynchronize(c->s_compute));
+    }
+    return DL_OK;
+}
+
+// Recomputes slot and resident-copy placement for a proposed residency of module `mi` on a COPY of
+// the arena; commits only if everything fits.  new_res == nullptr: keep residency (used by finalize).
+int32_t rebalance(dl_ctx* c, int32_t mi, const std::vector<uint8_t>* new_res) {
+    dl::Arena A = c->arena;
+    Module& M = c->mods[size_t(mi)];
+    std::vector<uint8_t> res = new_res ? *new_res : M.resident;
+    std::vector<uint64_t> off = M.res_off;
+    // 1. release copies of layers that stop being resident
+    for (int32_t i = 0; i < M.d.n_layers; ++i)
+        if (M.resident[size_t(i)] && !res[size_t(i)]) A.free(off[size_t(i)]);
+    // 2. slots: two buffers of the largest layer over all modules, needed while anything streams
+    uint64_t need_bytes = 0;
+    bool any_streamed = false;
+    for (size_t m = 0; m < c->mods.size(); ++m) {
+        const Module& X = c->mods[m];
+        if (!X.finalized && int32_t(m) != mi) continue;
+        need_bytes = std::max(need_bytes, X.L.bytes);
+        const std::vector<uint8_t>& r = (int32_t(m) == mi) ? res : X.resident;
+        for (uint8_t v : r) any_streamed |= !v;
+    }
+    bool slots_alloc = c->slots_alloc;
+    uint64_t slot_off[2] = {c->slot_off[0], c->slot_off[1]};
+    uint64_t slot_bytes = c->slot_bytes;
+    if (slots_alloc && (!any_streamed || slot_bytes != need_bytes)) {
+        A.free(slot_off[0]);
+        A.free(slot_off[1]);
+        slots_alloc = false;
+    }
+    if (any_streamed && !slots_alloc) {
+        if (!A.alloc(need_bytes, &slot_off[0]) || !A.alloc(need_bytes, &slot_off[1]))
+            return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the two layer slots");
+        slots_alloc = true;
+        slot_bytes = need_bytes;
+    }
+    // 3. copies of newly resident layers
+    std::vector<int32_t> to_upload;
+    for (int32_t i = 0; i < M.d.n_layers; ++i) {
+        if (res[size_t(i)] && !M.resident[size_t(i)]) {
+            if (!A.alloc(M.L.bytes, &off[size_t(i)])) {
+                char buf[160];
+                snprintf(buf, sizeof buf, "arena cannot hold resident layer %d (%llu bytes each, %llu of %llu used)", i,
+                         (unsigned long long)M.L.bytes, (unsigned long long)A.used(), (unsigned long long)A.capacity());
+                return fail(c, DL_ERR_BUDGET_EXCEEDED, buf);
+            }
+            to_upload.push_back(i);
+        }
+    }
+    // commit
+    c->arena = A;
+    c->slots_alloc = slots_alloc;
+    c->slot_off[0] = slot_off[0];
+    c->slot_off[1] = slot_off[1];
+    c->slot_bytes = slot_bytes;
+    M.resident = res;
+    M.res_off = off;
+    c->book = dl::SlotBook();
+    if (on_gpu(c)) {
+        for (int32_t i : to_upload)
+            DL_HIP(c, hipMemcpy(c->base + off[size_t(i)], M.store + size_t(i) * M.L.bytes, M.L.bytes,
+                                hipMemcpyHostToDevice));
+    }
+    return DL_OK;
+}
+
+// ---- one layer on the compute stream -------------------------------------------------------------
+using dlk::bf16_t;
+
+void linear(hipStream_t st, int T, const bf16_t* A, int lda, const bf16_t* B, int K, int N, const bf16_t* bias,
+            int epi, void* out, int ldo, const float* resid, int ldr) {
+    if (T == 1) {
+        dlk::GemvArgs g{A, B, K, bias, out, resid, N, K, epi};
+        dlk::gemv(g, st);
+    } else {
+        dlk::GemmArgs g{A, lda, B, K, bias, out, ldo, resid, ldr, T, N, K, epi};
+        dlk::gemm(g, st);
+    }
+}
+
+void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const float* in, float* out, int32_t T,
+               int32_t pos0, const float* ctx, int32_t n_ctx) {
+    const dl_module_desc& d = M.d;
+    const PackLayout& L = M.L;
+    hipStream_t st = c->s_compute;
+    auto P = [&](uint64_t off) -> const bf16_t* {
+        return off == PackLayout::kNone ? nullptr : reinterpret_cast<const bf16_t*>(w + off);
+    };
+    uint8_t* ws = c->base + M.ws_off;
+    bf16_t* nbuf = reinterpret_cast<bf16_t*>(ws + M.W.nbuf);
+    bf16_t* qkv = reinterpret_cast<bf16_t*>(ws + M.W.qkv);
+    bf16_t* attn = reinterpret_cast<bf16_t*>(ws + M.W.attn);
+    bf16_t* mid = reinterpret_cast<bf16_t*>(ws + M.W.mid);
+    const int dm = d.d_model, dh = d.d_head, Hq = d.n_q_heads, Hkv = d.n_kv_heads;
+    const int dq = Hq * dh, dkv = Hkv * dh;
+    const bool cache = d.max_seq > 0;
+
+    // attention sub-block
+    dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
+    linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
+    bf16_t* kc = nullptr;
+    bf16_t* vt;
+    uint64_t k_hs, v_hs;
+    int ldk, ldv;
+    if (cache) {
+        uint8_t* kvb = c->base + M.kv_off + uint64_t(layer) * (M.KV.k_layer_bytes + M.KV.v_layer_bytes);
+        kc = reinterpret_cast<bf16_t*>(kvb);
+        vt = reinterpret_cast<bf16_t*>(kvb + M.KV.k_layer_bytes);
+        k_hs = uint64_t(d.max_seq) * dh;
+        ldk = dh;
+        ldv = M.KV.v_ld;
+        v_hs = uint64_t(dh) * ldv;
+    } else {
+        vt = reinterpret_cast<bf16_t*>(ws + M.W.vt);
+        k_hs = uint64_t(dh);
+        ldk = L.n_qkv;
+        ldv = M.W.vt_ld;
+        v_hs = uint64_t(dh) * ldv;
+    }
+    dlk::QkvPostArgs qp{qkv, L.n_qkv, T, pos0, Hq, Hkv, dh, d.rope_theta, kc, k_hs, vt, v_hs, ldv, 0, dq, dq + dkv};
+    dlk::qkv_post(qp, st);
+    dlk::AttnArgs aa{qkv, L.n_qkv, cache ? kc : qkv + dq, ldk, k_hs, vt, ldv, v_hs, attn, dq,
+                     T, pos0 + T, pos0, Hq, Hkv, dh, d.causal};
+    dlk::attention(aa, st);
+    linear(st, T, attn, dq, P(L.w_o), dq, dm, P(L.b_o), dlk::EPI_RESID_F32, out, dm, in, dm);
+
+    // cross-attention sub-block
+    if (d.d_ctx > 0) {
+        bf16_t* ctxn = reinterpret_cast<bf16_t*>(ws + M.W.ctxn);
+        bf16_t* kvc = reinterpret_cast<bf16_t*>(ws + M.W.kvc);
+        bf16_t* vtc = reinterpret_cast<bf16_t*>(ws + M.W.vtc);
+        dlk::norm_rows(d.norm, out, P(L.normc_g), P(L.normc_b), nbuf, false, T, dm, d.norm_eps, st);
+        linear(st, T, nbuf, dm, P(L.w_qc), dm, dq, P(L.b_qc), dlk::EPI_BF16, qkv, dq, nullptr, 0);
+        dlk::cast_f32_bf16(ctx, ctxn, uint64_t(n_ctx) * d.d_ctx, st);
+        linear(st, n_ctx, ctxn, d.d_ctx, P(L.w_kvc), d.d_ctx, 2 * dkv, P(L.b_kvc), dlk::EPI_BF16, kvc, 2 * dkv,
+               nullptr, 0);
+        dlk::QkvPostArgs cp{kvc, 2 * dkv, n_ctx, 0, Hq, Hkv, dh, 0.0f, nullptr, 0, vtc,
+                            uint64_t(dh) * M.W.vtc_ld, M.W.vtc_ld, -1, 0, dkv};
+        dlk::qkv_post(cp, st);
+        dlk::AttnArgs ca{qkv, dq, kvc, 2 * dkv, uint64_t(dh), vtc, M.W.vtc_ld, uint64_t(dh) * M.W.vtc_ld, attn, dq,
+                         T, n_ctx, 0, Hq, Hkv, dh, 0};
+        dlk::attention(ca, st);
+        linear(st, T, attn, dq, P(L.w_oc), dq, dm, P(L.b_oc), dlk::EPI_RESID_F32, out, dm, out, dm);
+    }
+
+    // feed-forward sub-block
+    dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
+    if (d.act == DL_ACT_SWIGLU)
+        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, d.d_ff, nullptr, 0);
+    else
+        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, d.d_ff, nullptr, 0);
+    linear(st, T, mid, d.d_ff, P(L.w_down), d.d_ff, dm, P(L.b_down), dlk::EPI_RESID_F32, out, dm, out, dm);
+}
+
+hipEvent_t event_of(dl_ctx* c, const dl_trace_op& o) {
+    if (o.event_kind == DL_EV_DMA_DONE) return c->ev_dma[o.slot];
+    if (o.event_kind == DL_EV_COMPUTE_DONE) return c->ev_comp[o.slot];
+    return c->ev_pass;
+}
+
+// Enqueues one pass.  force_all: every layer goes through a slot (profiling).
+int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int32_t pos0, const float* ctx,
+                 int32_t n_ctx, bool force_all) {
+    Module& M = c->mods[size_t(mi)];
+    std::vector<dl_trace_op> ops;
+    dl::build_pass(mi, M.d.n_layers, M.resident.data(), c->mode, c->wrap, force_all, &c->book, &ops);
+    if (c->tracing || !on_gpu(c)) c->trace.insert(c->trace.end(), ops.begin(), ops.end());
+    if (!on_gpu(c)) return DL_OK;
+    for (const dl_trace_op& o : ops) {
+        hipStream_t st = o.queue == 0 ? c->s_compute : c->s_copy;
+        switch (o.op) {
+            case DL_OP_WAIT:
+                DL_HIP(c, hipStreamWaitEvent(st, event_of(c, o), 0));
+                break;
+            case DL_OP_RECORD:
+                DL_HIP(c, hipEventRecord(event_of(c, o), st));
+                break;
+            case DL_OP_COPY: {
+                TimedOp t{nullptr, nullptr, o.module, o.layer, o.slot, -1};
+                if (c->timing) {
+                    int32_t rc = timing_event(c, &t.e0);
+                    if (rc) return rc;
+                    rc = timing_event(c, &t.e1);
+                    if (rc) return rc;
+                    DL_HIP(c, hipEventRecord(t.e0, st));
+                }
+                DL_HIP(c, hipMemcpyAsync(c->base + c->slot_off[o.slot], M.store + size_t(o.layer) * M.L.bytes,
+                                         M.L.bytes, hipMemcpyHostToDevice, st));
+                if (c->timing) {
+                    DL_HIP(c, hipEventRecord(t.e1, st));
+                    c->last_copy_in_slot[o.slot] = int32_t(c->copies.size());
+                    c->copies.push_back(t);
+                }
+                break;
+            }
+            case DL_OP_EXEC: {
+                const uint8_t* w = o.slot >= 0 ? c->base + c->slot_off[o.slot]
+                                               : c->base + M.res_off[size_t(o.layer)];
+                TimedOp t{nullptr, nullptr, o.module, o.layer, o.slot, o.slot >= 0 ? c->last_copy_in_slot[o.slot] : -1};
+                if (c->timing) {
+                    int32_t rc = timing_event(c, &t.e0);
+                    if (rc) return rc;
+                    rc = timing_event(c, &t.e1);
+                    if (rc) return rc;
+                    DL_HIP(c, hipEventRecord(t.e0, st));
+                }
+                run_layer(c, M, o.layer, w, o.layer == 0 ? x : y, y, T, pos0, ctx, n_ctx);
+                DL_HIP(c, hipGetLastError());
+                if (c->timing) {
+                    DL_HIP(c, hipEventRecord(t.e1, st));
+                    c->execs.push_back(t);
+                }
+                break;
+            }
+            default: break;
+        }
+    }
+    return DL_OK;
+}
+
+int32_t check_forward_args(dl_ctx* c, Module* M, const void* x, void* y, int32_t T, int32_t pos0, const void* ctx,
+                           int32_t n_ctx) {
+    if (!M) return fail(c, DL_ERR_INVALID_ARG, "no such module");
+    if (!M->finalized) return fail(c, DL_ERR_BAD_STATE, "module not finalized");
+    if (on_gpu(c) && !c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
+    if (on_gpu(c) && (!x || !y)) return fail(c, DL_ERR_INVALID_ARG, "null activation pointer");
+    if (T < 1 || T > M->d.max_tokens) return fail(c, DL_ERR_INVALID_ARG, "n_tokens outside [1, max_tokens]");
+    if (pos0 < 0) return fail(c, DL_ERR_INVALID_ARG, "pos0 < 0");
+    if (M->d.max_seq == 0 && pos0 != 0) return fail(c, DL_ERR_INVALID_ARG, "pos0 must be 0 without a KV cache");
+    if (M->d.max_seq > 0 && pos0 + T > M->d.max_seq) return fail(c, DL_ERR_INVALID_ARG, "pos0 + n_tokens exceeds max_seq");
+    if (M->d.d_ctx > 0) {
+        if (n_ctx < 1 || n_ctx > M->d.max_ctx) return fail(c, DL_ERR_INVALID_ARG, "n_ctx outside [1, max_ctx]");
+        if (on_gpu(c) && !ctx) return fail(c, DL_ERR_INVALID_ARG, "cross-attention source missing");
+    }
+    return DL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t dl_create(dl_ctx** out, int32_t device) {
+    if (!out || device < -1) return DL_ERR_INVALID_ARG;
+    if (device >= 0) {
+        int n = 0;
+        if (hipGetDeviceCount(&n) != hipSuccess || device >= n) return DL_ERR_DEVICE;
+        if (hipSetDevice(device) != hipSuccess) return DL_ERR_DEVICE;
+    }
+    dl_ctx* c = new dl_ctx();
+    c->device = device;
+    *out = c;
+    return DL_OK;
+}
+
+int32_t dl_destroy(dl_ctx* c) {
+    if (!c) return DL_ERR_INVALID_ARG;
+    if (on_gpu(c)) {
+        (void)hipSetDevice(c->device);
+        if (c->streams_set) {
+            (void)hipStreamSynchronize(c->s_copy);
+            (void)hipStreamSynchronize(c->s_compute);
+        }
+        if (c->events_made) {
+            for (int s = 0; s < 2; ++s) {
+                (void)hipEventDestroy(c->ev_dma[s]);
+                (void)hipEventDestroy(c->ev_comp[s]);
+            }
+            (void)hipEventDestroy(c->ev_pass);
+        }
+        for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
+    }
+    for (Module& M : c->mods) {
+        if (!M.store) continue;
+        if (on_gpu(c)) (void)hipHostFree(M.store);
+        else free(M.store);
+    }
+    delete c;
+    return DL_OK;
+}
+
+const char* dl_last_error(const dl_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+int32_t dl_set_arena(dl_ctx* c, void* dev_base, uint64_t bytes) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena already set");
+    if (bytes < dl::kAlign) return fail(c, DL_ERR_INVALID_ARG, "arena too small");
+    if (on_gpu(c) && (!dev_base || (reinterpret_cast<uintptr_t>(dev_base) % dl::kAlign)))
+        return fail(c, DL_ERR_INVALID_ARG, "arena base must be a 256-byte aligned device pointer");
+    c->base = static_cast<uint8_t*>(dev_base);
+    c->arena.reset(bytes);
+    return DL_OK;
+}
+
+int32_t dl_arena_alloc(dl_ctx* c, uint64_t bytes, void** out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!out || bytes == 0) return fail(c, DL_ERR_INVALID_ARG, "bad arguments");
+    if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
+    uint64_t off;
+    if (!c->arena.alloc(bytes, &off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the requested block");
+    *out = c->base + off;
+    return DL_OK;
+}
+
+int32_t dl_arena_free(dl_ctx* c, void* p) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
+    const uint64_t off = uint64_t(static_cast<uint8_t*>(p) - c->base);
+    if (!c->arena.free(off)) return fail(c, DL_ERR_INVALID_ARG, "pointer is not a live arena block");
+    return DL_OK;
+}
+
+int32_t dl_arena_stats(const dl_ctx* c, uint64_t* used, uint64_t* peak, uint64_t* cap) {
+    if (!c) return DL_ERR_INVALID_ARG;
+    if (used) *used = c->arena.used();
+    if (peak) *peak = c->arena.peak();
+    if (cap) *cap = c->arena.capacity();
+    return DL_OK;
+}
+
+int32_t dl_set_streams(dl_ctx* c, void* compute_stream, void* copy_stream) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!on_gpu(c)) return DL_OK;
+    if (compute_stream == copy_stream) return fail(c, DL_ERR_INVALID_ARG, "the two streams must be distinct");
+    rc = sync_streams(c);
+    if (rc) return rc;
+    c->s_compute = static_cast<hipStream_t>(compute_stream);
+    c->s_copy = static_cast<hipStream_t>(copy_stream);
+    c->streams_set = true;
+    c->book = dl::SlotBook();
+    return make_events(c);
+}
+
+int32_t dl_module_create(dl_ctx* c, const dl_module_desc* desc, int32_t* module_out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!desc || !module_out) return fail(c, DL_ERR_INVALID_ARG, "null argument");
+    std::string why;
+    if (!dl::validate_desc(*desc, &why)) return fail(c, DL_ERR_INVALID_ARG, why);
+    Module M;
+    M.d = *desc;
+    M.L = dl::make_layout(*desc);
+    M.W = dl::make_workspace(*desc);
+    M.KV = dl::make_kv(*desc);
+    const uint64_t total = uint64_t(desc->n_layers) * M.L.bytes;
+    if (on_gpu(c)) {
+        void* p = nullptr;
+        if (hipHostMalloc(&p, total, hipHostMallocDefault) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return fail(c, DL_ERR_HOST_ALLOC, "pinned host allocation failed");
+        }
+        M.store = static_cast<uint8_t*>(p);
+    } else {
+        M.store = static_cast<uint8_t*>(malloc(total));
+        if (!M.store) return fail(c, DL_ERR_HOST_ALLOC, "host allocation failed");
+    }
+    M.set_mask.assign(size_t(desc->n_layers), 0u);
+    M.resident.assign(size_t(desc->n_layers), 0);
+    M.res_off.assign(size_t(desc->n_layers), 0);
+    c->mods.push_back(M);
+    *module_out = int32_t(c->mods.size() - 1);
+    return DL_OK;
+}
+
+int32_t dl_layer_set_tensor(dl_ctx* c, int32_t module, int32_t layer, int32_t tid, const void* host, uint64_t n) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M) return fail(c, DL_ERR_INVALID_ARG, "no such module");
+    if (M->finalized) return fail(c, DL_ERR_BAD_STATE, "module already finalized");
+    if (layer < 0 || layer >= M->d.n_layers) return fail(c, DL_ERR_INVALID_ARG, "layer out of range");
+    if (tid < 0 || tid >= DL_T_COUNT || !host) return fail(c, DL_ERR_INVALID_ARG, "bad tensor id or null data");
+    const uint64_t want = dl::tensor_elems(M->d, tid);
+    if (want == 0) return fail(c, DL_ERR_INVALID_ARG, "this module has no such tensor");
+    if (want != n) return fail(c, DL_ERR_INVALID_ARG, "tensor has the wrong number of elements");
+    dl::pack_tensor(M->d, M->L, tid, static_cast<const uint16_t*>(host), M->store + size_t(layer) * M->L.bytes);
+    M->set_mask[size_t(layer)] |= 1u << tid;
+    return DL_OK;
+}
+
+int32_t dl_set_resident_tensor(dl_ctx* c, int32_t module, int32_t which, const void* host, uint64_t n) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M) return fail(c, DL_ERR_INVALID_ARG, "no such module");
+    if (which < 0 || which >= DL_R_COUNT || !host) return fail(c, DL_ERR_INVALID_ARG, "bad tensor id or null data");
+    if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
+    uint64_t want = 0;
+    if (which == DL_R_EMBED || which == DL_R_HEAD) want = uint64_t(M->d.vocab) * M->d.d_model;
+    else if (which == DL_R_FINAL_NORM_G) want = M->d.d_model;
+    else want = M->d.norm == DL_NORM_LN ? M->d.d_model : 0;
+    if (want == 0 || want != n) return fail(c, DL_ERR_INVALID_ARG, "resident tensor has the wrong size for this module");
+    if (!M->rt_set[which]) {
+        uint64_t off;
+        if (!c->arena.alloc(2 * n, &off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the resident tensor");
+        M->rt_off[which] = off;
+        M->rt_set[which] = true;
+    }
+    if (on_gpu(c)) {
+        rc = sync_streams(c);
+        if (rc) return rc;
+        DL_HIP(c, hipMemcpy(c->base + M->rt_off[which], host, 2 * n, hipMemcpyHostToDevice));
+    }
+    return DL_OK;
+}
+
+int32_t dl_module_finalize(dl_ctx* c, int32_t module) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M) return fail(c, DL_ERR_INVALID_ARG, "no such module");
+    if (M->finalized) return fail(c, DL_ERR_BAD_STATE, "module already finalized");
+    if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
+    const uint32_t need = dl::required_tensor_mask(M->d);
+    for (int32_t i = 0; i < M->d.n_layers; ++i)
+        if ((M->set_mask[size_t(i)] & need) != need) {
+            char buf[96];
+            snprintf(buf, sizeof buf, "layer %d is missing tensors (have mask 0x%x, need 0x%x)", i,
+                     M->set_mask[size_t(i)], need);
+            return fail(c, DL_ERR_BAD_STATE, buf);
+        }
+    rc = sync_streams(c);
+    if (rc) return rc;
+    // workspace and KV cache first, then the slots; undo on failure
+    uint64_t ws = 0, kv = 0;
+    if (!c->arena.alloc(M->W.bytes, &ws)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the activation workspace");
+    if (M->KV.bytes && !c->arena.alloc(M->KV.bytes, &kv)) {
+        c->arena.free(ws);
+        return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the KV cache");
+    }
+    M->ws_off = ws;
+    M->kv_off = kv;
+    rc = rebalance(c, module, nullptr);
+    if (rc) {
+        c->arena.free(ws);
+        if (M->KV.bytes) c->arena.free(kv);
+        return rc;
+    }
+    if (on_gpu(c)) {
+        // stale bytes in the transposed-V areas must be finite numbers: zero everything once
+        DL_HIP(c, hipMemset(c->base + ws, 0, M->W.bytes));
+        if (M->KV.bytes) DL_HIP(c, hipMemset(c->base + kv, 0, M->KV.bytes));
+    }
+    M->finalized = true;
+    return DL_OK;
+}
+
+int32_t dl_module_layer_bytes(const dl_ctx* c, int32_t module, uint64_t* packed, uint64_t* params) {
+    if (!c || module < 0 || size_t(module) >= c->mods.size()) return DL_ERR_INVALID_ARG;
+    if (packed) *packed = c->mods[size_t(module)].L.bytes;
+    if (params) *params = c->mods[size_t(module)].L.param_bytes;
+    return DL_OK;
+}
+
+int32_t dl_set_residency(dl_ctx* c, int32_t module, const int32_t* idx, int32_t n) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M) return fail(c, DL_ERR_INVALID_ARG, "no such module");
+    if (!M->finalized) return fail(c, DL_ERR_BAD_STATE, "module not finalized");
+    if (n < 0 || n > M->d.n_layers || (n > 0 && !idx)) return fail(c, DL_ERR_INVALID_ARG, "bad resident count");
+    std::vector<uint8_t> res(size_t(M->d.n_layers), 0);
+    for (int32_t i = 0; i < n; ++i) {
+        if (idx[i] < 0 || idx[i] >= M->d.n_layers) return fail(c, DL_ERR_INVALID_ARG, "resident layer index out of range");
+        if (res[size_t(idx[i])]) return fail(c, DL_ERR_INVALID_ARG, "duplicate resident layer index");
+        res[size_t(idx[i])] = 1;
+    }
+    rc = sync_streams(c);
+    if (rc) return rc;
+    return rebalance(c, module, &res);
+}
+
+int32_t dl_get_residency(const dl_ctx* c, int32_t module, int32_t* idx_out, int32_t* n_out) {
+    if (!c || module < 0 || size_t(module) >= c->mods.size() || !n_out) return DL_ERR_INVALID_ARG;
+    const Module& M = c->mods[size_t(module)];
+    int32_t n = 0;
+    for (int32_t i = 0; i < M.d.n_layers; ++i)
+        if (M.resident[size_t(i)]) {
+            if (idx_out) idx_out[n] = i;
+            ++n;
+        }
+    *n_out = n;
+    return DL_OK;
+}
+
+int32_t dl_set_mode(dl_ctx* c, int32_t mode, int32_t wrap) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (mode != DL_MODE_PIPELINED && mode != DL_MODE_SEQUENTIAL) return fail(c, DL_ERR_INVALID_ARG, "unknown mode");
+    c->mode = mode;
+    c->wrap = wrap ? 1 : 0;
+    return DL_OK;
+}
+
+int32_t dl_forward(dl_ctx* c, int32_t module, const void* x, void* y, int32_t T, int32_t pos0, const void* ctx,
+                   int32_t n_ctx) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    rc = check_forward_args(c, M, x, y, T, pos0, ctx, n_ctx);
+    if (rc) return rc;
+    return run_pass(c, module, static_cast<const float*>(x), static_cast<float*>(y), T, pos0,
+                    static_cast<const float*>(ctx), n_ctx, false);
+}
+
+int32_t dl_embed_token(dl_ctx* c, int32_t module, int32_t token, void* x_dev) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M || !M->finalized) return fail(c, DL_ERR_BAD_STATE, "module missing or not finalized");
+    if (!M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
+    if (token < 0 || token >= M->d.vocab) return fail(c, DL_ERR_INVALID_ARG, "token out of range");
+    if (!on_gpu(c)) return DL_OK;
+    if (!x_dev) return fail(c, DL_ERR_INVALID_ARG, "null output");
+    dlk::embed_row(reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_EMBED]), M->d.d_model, nullptr, token,
+                   static_cast<float*>(x_dev), c->s_compute);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_final_norm(dl_ctx* c, int32_t module, const void* h, void* out, int32_t T) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M || !M->finalized) return fail(c, DL_ERR_BAD_STATE, "module missing or not finalized");
+    if (!M->rt_set[DL_R_FINAL_NORM_G] || (M->d.norm == DL_NORM_LN && !M->rt_set[DL_R_FINAL_NORM_B]))
+        return fail(c, DL_ERR_BAD_STATE, "final norm parameters not set");
+    if (T < 1) return fail(c, DL_ERR_INVALID_ARG, "n_tokens < 1");
+    if (!on_gpu(c)) return DL_OK;
+    if (!h || !out) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    dlk::norm_rows(M->d.norm, static_cast<const float*>(h),
+                   reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_G]),
+                   M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr,
+                   out, true, T, M->d.d_model, M->d.norm_eps, c->s_compute);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+static int32_t head_common(dl_ctx* c, Module* M, const void* h) {
+    if (!M || !M->finalized) return fail(c, DL_ERR_BAD_STATE, "module missing or not finalized");
+    if (M->d.vocab <= 0 || !M->rt_set[DL_R_HEAD] || !M->rt_set[DL_R_FINAL_NORM_G])
+        return fail(c, DL_ERR_BAD_STATE, "head or final norm not set");
+    if (!on_gpu(c)) return DL_OK;
+    if (!h) return fail(c, DL_ERR_INVALID_ARG, "null hidden state");
+    uint8_t* ws = c->base + M->ws_off;
+    bf16_t* nbuf = reinterpret_cast<bf16_t*>(ws + M->W.nbuf);
+    float* logits = reinterpret_cast<float*>(ws + M->W.logits);
+    int32_t* tok = reinterpret_cast<int32_t*>(ws + M->W.token);
+    hipStream_t st = c->s_compute;
+    dlk::norm_rows(M->d.norm, static_cast<const float*>(h),
+                   reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_G]),
+                   M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr,
+                   nbuf, false, 1, M->d.d_model, M->d.norm_eps, st);
+    dlk::GemvArgs g{nbuf, reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_HEAD]), M->d.d_model, nullptr,
+                    logits, nullptr, M->d.vocab, M->d.d_model, dlk::EPI_F32};
+    dlk::gemv(g, st);
+    dlk::argmax_f32(logits, M->d.vocab, tok, st);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_logits_argmax(dl_ctx* c, int32_t module, const void* h, int32_t* token_out, float* logits_out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!token_out) return fail(c, DL_ERR_INVALID_ARG, "null token_out");
+    rc = head_common(c, M, h);
+    if (rc) return rc;
+    if (!on_gpu(c)) { *token_out = 0; return DL_OK; }
+    uint8_t* ws = c->base + M->ws_off;
+    DL_HIP(c, hipMemcpyAsync(token_out, ws + M->W.token, 4, hipMemcpyDeviceToHost, c->s_compute));
+    if (logits_out)
+        DL_HIP(c, hipMemcpyAsync(logits_out, ws + M->W.logits, 4 * size_t(M->d.vocab), hipMemcpyDeviceToHost, c->s_compute));
+    DL_HIP(c, hipStreamSynchronize(c->s_compute));
+    return DL_OK;
+}
+
+int32_t dl_greedy_step(dl_ctx* c, int32_t module, const void* h, int32_t* token_dev, void* x_dev) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    rc = head_common(c, M, h);
+    if (rc) return rc;
+    if (!M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
+    if (!on_gpu(c)) return DL_OK;
+    if (!x_dev) return fail(c, DL_ERR_INVALID_ARG, "null x_dev");
+    uint8_t* ws = c->base + M->ws_off;
+    const int32_t* tok = reinterpret_cast<const int32_t*>(ws + M->W.token);
+    if (token_dev) DL_HIP(c, hipMemcpyAsync(token_dev, tok, 4, hipMemcpyDeviceToDevice, c->s_compute));
+    dlk::embed_row(reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_EMBED]), M->d.d_model, tok, 0,
+                   static_cast<float*>(x_dev), c->s_compute);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_sync(dl_ctx* c) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    return sync_streams(c);
+}
+
+int32_t dl_set_timing(dl_ctx* c, int32_t on) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    c->timing = on != 0;
+    return DL_OK;
+}
+
+int32_t dl_collect_stats(dl_ctx* c, dl_run_stats* stats, dl_layer_record* recs, int32_t cap) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!stats) return fail(c, DL_ERR_INVALID_ARG, "null stats");
+    memset(stats, 0, sizeof *stats);
+    stats->hidden_frac = 1.0;
+    stats->arena_peak = c->arena.peak();
+    if (!on_gpu(c)) return DL_OK;
+    rc = sync_streams(c);
+    if (rc) return rc;
+    if (c->execs.empty()) {
+        c->copies.clear();
+        c->ev_next = 0;
+        return DL_OK;
+    }
+    // origin: the earlier of the first copy start and the first exec start
+    hipEvent_t origin = c->execs[0].e0;
+    if (!c->copies.empty()) {
+        float ms = 0;
+        DL_HIP(c, hipEventElapsedTime(&ms, c->copies[0].e0, c->execs[0].e0));
+        if (ms > 0) origin = c->copies[0].e0;
+    }
+    auto rel = [&](hipEvent_t e, float* out) -> hipError_t { return hipEventElapsedTime(out, origin, e); };
+    std::vector<float> c0(c->copies.size()), c1(c->copies.size());
+    for (size_t i = 0; i < c->copies.size(); ++i) {
+        DL_HIP(c, rel(c->copies[i].e0, &c0[i]));
+        DL_HIP(c, rel(c->copies[i].e1, &c1[i]));
+    }
+    double dma = 0, exe = 0, exposed = 0, last_end = 0;
+    uint64_t bytes = 0;
+    float prev_exe_end = 0;
+    for (size_t i = 0; i < c->execs.size(); ++i) {
+        const TimedOp& t = c->execs[i];
+        float e0, e1;
+        DL_HIP(c, rel(t.e0, &e0));
+        DL_HIP(c, rel(t.e1, &e1));
+        exe += double(e1) - e0;
+        dl_layer_record r{t.module, t.layer, t.slot >= 0 ? 1 : 0, t.slot, 0, 0, e0, e1};
+        if (t.copy_index >= 0) {
+            const float d0 = c0[size_t(t.copy_index)], d1 = c1[size_t(t.copy_index)];
+            r.dma_start_ms = d0;
+            r.dma_end_ms = d1;
+            dma += double(d1) - d0;
+            bytes += c->mods[size_t(t.module)].L.bytes;
+            exposed += std::max(0.0, double(d1) - std::max(double(prev_exe_end), double(d0)));
+        }
+        prev_exe_end = e1;
+        last_end = std::max(last_end, double(e1));
+        if (recs && int32_t(i) < cap) recs[i] = r;
+    }
+    stats->total_ms = last_end;
+    stats->dma_ms = dma;
+    stats->exe_ms = exe;
+    stats->exposed_ms = exposed;
+    stats->hidden_frac = dma > 0 ? 1.0 - exposed / dma : 1.0;
+    stats->bytes_streamed = bytes;
+    stats->h2d_gbps = dma > 0 ? double(bytes) / (dma * 1e6) : 0.0;
+    stats->n_layer_records = int32_t(c->execs.size());
+    c->copies.clear();
+    c->execs.clear();
+    c->last_copy_in_slot[0] = c->last_copy_in_slot[1] = -1;
+    c->ev_next = 0;
+    return DL_OK;
+}
+
+int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const void* x, const void* ctx, int32_t n_ctx,
+                   int32_t iters, dl_layer_profile* out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!out || iters < 2) return fail(c, DL_ERR_INVALID_ARG, "need an output array and at least 2 iterations");
+    if (!on_gpu(c)) return fail(c, DL_ERR_BAD_STATE, "profiling needs a device context");
+    float* scratch = nullptr;
+    {
+        // validated against a placeholder output pointer; the real one is carved below
+        rc = check_forward_args(c, M, x, const_cast<void*>(x), T, pos0, ctx, n_ctx);
+        if (rc) return rc;
+    }
+    if (!c->slots_alloc) return fail(c, DL_ERR_BAD_STATE, "no slots: every layer is resident, nothing to profile through");
+    rc = sync_streams(c);
+    if (rc) return rc;
+    if (!c->copies.empty() || !c->execs.empty()) return fail(c, DL_ERR_BAD_STATE, "collect pending statistics first");
+    void* tmp = nullptr;
+    rc = dl_arena_alloc(c, uint64_t(T) * M->d.d_model * 4, &tmp);
+    if (rc) return rc;
+    scratch = static_cast<float*>(tmp);
+    const int32_t mode0 = c->mode, wrap0 = c->wrap;
+    const bool timing0 = c->timing, tracing0 = c->tracing;
+    c->mode = DL_MODE_SEQUENTIAL;
+    c->wrap = 0;
+    c->timing = true;
+    c->tracing = false;
+    c->book = dl::SlotBook();
+    const int32_t Ln = M->d.n_layers;
+    std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0);
+    for (int32_t it = 0; it < iters && rc == DL_OK; ++it) {
+        rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
+        if (rc) break;
+        dl_run_stats st;
+        std::vector<dl_layer_record> recs;
+        recs.resize(size_t(Ln));
+        rc = dl_collect_stats(c, &st, recs.data(), Ln);
+        if (rc) break;
+        if (it == 0) continue;       // the first iteration is discarded
+        for (int32_t i = 0; i < Ln; ++i) {
+            dma[size_t(i)] += double(recs[size_t(i)].dma_end_ms) - recs[size_t(i)].dma_start_ms;
+            exe[size_t(i)] += double(recs[size_t(i)].exe_end_ms) - recs[size_t(i)].exe_start_ms;
+        }
+    }
+    c->mode = mode0;
+    c->wrap = wrap0;
+    c->timing = timing0;
+    c->tracing = tracing0;
+    c->book = dl::SlotBook();
+    sync_streams(c);
+    c->copies.clear();
+    c->execs.clear();
+    c->ev_next = 0;
+    dl_arena_free(c, tmp);
+    if (rc) return rc;
+    for (int32_t i = 0; i < Ln; ++i) {
+        out[i].c_dma_ms = dma[size_t(i)] / (iters - 1);
+        out[i].c_exe_ms = exe[size_t(i)] / (iters - 1);
+        out[i].bytes = M->L.bytes;
+    }
+    return DL_OK;
+}
+
+int32_t dl_trace_enable(dl_ctx* c, int32_t on) {
+    if (!c) return DL_ERR_INVALID_ARG;
+    c->tracing = on != 0;
+    return DL_OK;
+}
+
+int32_t dl_trace_read(dl_ctx* c, dl_trace_op* out, int32_t cap, int32_t* n_out) {
+    if (!c || !n_out || cap < 0 || (cap > 0 && !out)) return DL_ERR_INVALID_ARG;
+    const int32_t n = int32_t(c->trace.size());
+    for (int32_t i = 0; i < n && i < cap; ++i) out[i] = c->trace[size_t(i)];
+    *n_out = n;
+    c->trace.clear();
+    return DL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,520 @@
+// Host core: arena accounting, packed-blob layout, the per-pass schedule (slot protocol),
+// and the planner / predictor.  No HIP call in this file: everything here also runs in a
+// host-only context.
+#include "dl_internal.hpp"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+
+namespace dl {
+
+// ------------------------------------------------------------------------------------------
+// Arena
+// ------------------------------------------------------------------------------------------
+void Arena::reset(uint64_t capacity) {
+    blocks_.clear();
+    cap_ = capacity / kAlign * kAlign;
+    used_ = peak_ = 0;
+    if (cap_) blocks_.push_back({0, cap_, false});
+}
+
+bool Arena::alloc(uint64_t bytes, uint64_t* off_out) {
+    uint64_t need = align_up(bytes ? bytes : 1);
+    for (size_t i = 0; i < blocks_.size(); ++i) {
+        Block& b = blocks_[i];
+        if (b.used || b.size < need) continue;
+        if (b.size > need) {
+            Block rest{b.off + need, b.size - need, false};
+            b.size = need;
+            b.used = true;
+            *off_out = b.off;
+            blocks_.insert(blocks_.begin() + i + 1, rest);
+        } else {
+            b.used = true;
+            *off_out = b.off;
+        }
+        used_ += need;
+        peak_ = std::max(peak_, used_);
+        return true;
+    }
+    return false;
+}
+
+bool Arena::free(uint64_t off) {
+    for (size_t i = 0; i < blocks_.size(); ++i) {
+        if (blocks_[i].off != off || !blocks_[i].used) continue;
+        blocks_[i].used = false;
+        used_ -= blocks_[i].size;
+        if (i + 1 < blocks_.size() && !blocks_[i + 1].used) {
+            blocks_[i].size += blocks_[i + 1].size;
+            blocks_.erase(blocks_.begin() + i + 1);
+        }
+        if (i > 0 && !blocks_[i - 1].used) {
+            blocks_[i - 1].size += blocks_[i].size;
+            blocks_.erase(blocks_.begin() + i);
+        }
+        return true;
+    }
+    return false;
+}
+
+uint64_t Arena::size_of(uint64_t off) const {
+    for (const Block& b : blocks_)
+        if (b.off == off && b.used) return b.size;
+    return 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Descriptor checks and the packed layout
+// ------------------------------------------------------------------------------------------
+bool validate_desc(const dl_module_desc& d, std::string* why) {
+    auto bad = [&](const char* m) { *why = m; return false; };
+    if (d.n_layers < 1 || d.n_layers > 4096) return bad("n_layers out of range");
+    if (d.d_model < 8 || d.d_model % 8) return bad("d_model must be a positive multiple of 8");
+    if (d.n_q_heads < 1 || d.n_kv_heads < 1 || d.n_q_heads % d.n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+    if (d.d_head < 8 || d.d_head % 8 || d.d_head > 128) return bad("d_head must be a multiple of 8 in [8, 128]");
+    if (d.norm != DL_NORM_RMS && d.norm != DL_NORM_LN) return bad("unknown norm");
+    if (d.act != DL_ACT_SWIGLU && d.act != DL_ACT_GELU) return bad("unknown activation");
+    if (d.d_ff < 8 || d.d_ff % 8) return bad("d_ff must be a positive multiple of 8");
+    if (d.act == DL_ACT_SWIGLU && d.d_ff % 32) return bad("d_ff must be a multiple of 32 for SwiGLU");
+    if (d.rope_theta < 0 || (d.rope_theta > 0 && d.d_head % 2)) return bad("bad rope_theta");
+    if (d.d_ctx < 0 || d.d_ctx % 8) return bad("d_ctx must be a multiple of 8");
+    if (d.d_ctx > 0 && d.max_ctx < 1) return bad("max_ctx must be positive when d_ctx > 0");
+    if (d.max_seq < 0 || d.max_tokens < 1) return bad("max_seq >= 0 and max_tokens >= 1 required");
+    if (d.max_seq > 0 && !d.causal) return bad("a KV cache needs a causal module");
+    if (d.max_seq > 0 && d.max_tokens > d.max_seq) return bad("max_tokens exceeds max_seq");
+    if (d.vocab < 0) return bad("vocab < 0");
+    if (!(d.norm_eps >= 0)) return bad("norm_eps < 0");
+    return true;
+}
+
+PackLayout make_layout(const dl_module_desc& d) {
+    PackLayout L;
+    const uint64_t dm = d.d_model, dq = uint64_t(d.n_q_heads) * d.d_head, dkv = uint64_t(d.n_kv_heads) * d.d_head;
+    const uint64_t f = d.d_ff;
+    const bool ln = d.norm == DL_NORM_LN, b = d.has_bias != 0, cross = d.d_ctx > 0, glu = d.act == DL_ACT_SWIGLU;
+    uint64_t off = 0, params = 0;
+    auto put = [&](uint64_t* field, uint64_t elems) {
+        *field = off;
+        off = align_up(off + 2 * elems);
+        params += elems;
+    };
+    L.n_qkv = int32_t(dq + 2 * dkv);
+    L.n_up = int32_t(glu ? 2 * f : f);
+    put(&L.norm1_g, dm);
+    if (ln) put(&L.norm1_b, dm);
+    put(&L.w_qkv, (dq + 2 * dkv) * dm);
+    if (b) put(&L.b_qkv, dq + 2 * dkv);
+    put(&L.w_o, dm * dq);
+    if (b) put(&L.b_o, dm);
+    if (cross) {
+        put(&L.normc_g, dm);
+        if (ln) put(&L.normc_b, dm);
+        put(&L.w_qc, dq * dm);
+        if (b) put(&L.b_qc, dq);
+        put(&L.w_kvc, 2 * dkv * uint64_t(d.d_ctx));
+        if (b) put(&L.b_kvc, 2 * dkv);
+        put(&L.w_oc, dm * dq);
+        if (b) put(&L.b_oc, dm);
+    }
+    put(&L.norm2_g, dm);
+    if (ln) put(&L.norm2_b, dm);
+    put(&L.w_up, uint64_t(L.n_up) * dm);
+    if (b) put(&L.b_up, f);
+    put(&L.w_down, dm * f);
+    if (b) put(&L.b_down, dm);
+    L.bytes = off;
+    L.param_bytes = 2 * params;
+    return L;
+}
+
+uint64_t tensor_elems(const dl_module_desc& d, int32_t tid) {
+    const uint64_t dm = d.d_model, dq = uint64_t(d.n_q_heads) * d.d_head, dkv = uint64_t(d.n_kv_heads) * d.d_head;
+    const uint64_t f = d.d_ff, dc = d.d_ctx;
+    const bool ln = d.norm == DL_NORM_LN, b = d.has_bias != 0, cross = d.d_ctx > 0, glu = d.act == DL_ACT_SWIGLU;
+    switch (tid) {
+        case DL_T_NORM1_G: case DL_T_NORM2_G: return dm;
+        case DL_T_NORM1_B: case DL_T_NORM2_B: return ln ? dm : 0;
+        case DL_T_WQ: return dq * dm;
+        case DL_T_WK: case DL_T_WV: return dkv * dm;
+        case DL_T_BQ: return b ? dq : 0;
+        case DL_T_BK: case DL_T_BV: return b ? dkv : 0;
+        case DL_T_WO: return dm * dq;
+        case DL_T_BO: return b ? dm : 0;
+        case DL_T_W_GATE: return glu ? f * dm : 0;
+        case DL_T_W_UP: return f * dm;
+        case DL_T_B_UP: return b ? f : 0;
+        case DL_T_W_DOWN: return dm * f;
+        case DL_T_B_DOWN: return b ? dm : 0;
+        case DL_T_NORMC_G: return cross ? dm : 0;
+        case DL_T_NORMC_B: return cross && ln ? dm : 0;
+        case DL_T_WQ_C: return cross ? dq * dm : 0;
+        case DL_T_WK_C: case DL_T_WV_C: return cross ? dkv * dc : 0;
+        case DL_T_BQ_C: return cross && b ? dq : 0;
+        case DL_T_BK_C: case DL_T_BV_C: return cross && b ? dkv : 0;
+        case DL_T_WO_C: return cross ? dm * dq : 0;
+        case DL_T_BO_C: return cross && b ? dm : 0;
+        default: return 0;
+    }
+}
+
+uint32_t required_tensor_mask(const dl_module_desc& d) {
+    uint32_t m = 0;
+    for (int32_t t = 0; t < DL_T_COUNT; ++t)
+        if (tensor_elems(d, t)) m |= 1u << t;
+    return m;
+}
+
+void pack_tensor(const dl_module_desc& d, const PackLayout& L, int32_t tid, const uint16_t* src, uint8_t* blob) {
+    const uint64_t dm = d.d_model, dq = uint64_t(d.n_q_heads) * d.d_head, dkv = uint64_t(d.n_kv_heads) * d.d_head;
+    const uint64_t f = d.d_ff, dc = d.d_ctx;
+    const uint64_t n = tensor_elems(d, tid);
+    auto plain = [&](uint64_t off, uint64_t elem_off) { std::memcpy(blob + off + 2 * elem_off, src, 2 * n); };
+    switch (tid) {
+        case DL_T_NORM1_G: plain(L.norm1_g, 0); break;
+        case DL_T_NORM1_B: plain(L.norm1_b, 0); break;
+        case DL_T_NORM2_G: plain(L.norm2_g, 0); break;
+        case DL_T_NORM2_B: plain(L.norm2_b, 0); break;
+        case DL_T_NORMC_G: plain(L.normc_g, 0); break;
+        case DL_T_NORMC_B: plain(L.normc_b, 0); break;
+        // fused QKV: rows [0,dq) = Q, [dq,dq+dkv) = K, [dq+dkv, dq+2dkv) = V
+        case DL_T_WQ: plain(L.w_qkv, 0); break;
+        case DL_T_WK: plain(L.w_qkv, dq * dm); break;
+        case DL_T_WV: plain(L.w_qkv, (dq + dkv) * dm); break;
+        case DL_T_BQ: plain(L.b_qkv, 0); break;
+        case DL_T_BK: plain(L.b_qkv, dq); break;
+        case DL_T_BV: plain(L.b_qkv, dq + dkv); break;
+        case DL_T_WO: plain(L.w_o, 0); break;
+        case DL_T_BO: plain(L.b_o, 0); break;
+        case DL_T_WQ_C: plain(L.w_qc, 0); break;
+        case DL_T_BQ_C: plain(L.b_qc, 0); break;
+        case DL_T_WK_C: plain(L.w_kvc, 0); break;
+        case DL_T_WV_C: plain(L.w_kvc, dkv * dc); break;
+        case DL_T_BK_C: plain(L.b_kvc, 0); break;
+        case DL_T_BV_C: plain(L.b_kvc, dkv); break;
+        case DL_T_WO_C: plain(L.w_oc, 0); break;
+        case DL_T_BO_C: plain(L.b_oc, 0); break;
+        case DL_T_B_UP: plain(L.b_up, 0); break;
+        case DL_T_W_DOWN: plain(L.w_down, 0); break;
+        case DL_T_B_DOWN: plain(L.b_down, 0); break;
+        case DL_T_W_GATE:
+        case DL_T_W_UP:
+            if (d.act == DL_ACT_SWIGLU) {
+                // gate and up rows interleaved in groups of 32: packed row (f/32)*64 + f%32 is gate row f,
+                // 32 rows further is up row f; the GEMM epilogue then finds both in one wave
+                const uint64_t shift = (tid == DL_T_W_UP) ? 32 : 0;
+                for (uint64_t r = 0; r < f; ++r) {
+                    uint64_t pr = (r / 32) * 64 + (r % 32) + shift;
+                    std::memcpy(blob + L.w_up + 2 * pr * dm, src + r * dm, 2 * dm);
+                }
+            } else {
+                plain(L.w_up, 0);
+            }
+            break;
+        default: break;
+    }
+}
+
+WorkspaceLayout make_workspace(const dl_module_desc& d) {
+    WorkspaceLayout W;
+    const uint64_t T = d.max_tokens, dm = d.d_model, dq = uint64_t(d.n_q_heads) * d.d_head,
+                   dkv = uint64_t(d.n_kv_heads) * d.d_head, f = d.d_ff;
+    uint64_t off = 0;
+    auto put = [&](uint64_t* field, uint64_t bytes) { *field = off; off = align_up(off + bytes); };
+    put(&W.nbuf, 2 * T * dm);
+    put(&W.qkv, 2 * T * (dq + 2 * dkv));
+    put(&W.attn, 2 * T * dq);
+    put(&W.mid, 2 * T * f);
+    if (d.max_seq == 0) {
+        W.vt_ld = int32_t(align_up(T, 64));
+        put(&W.vt, 2 * dkv * uint64_t(W.vt_ld));
+    }
+    if (d.d_ctx > 0) {
+        const uint64_t C = d.max_ctx;
+        W.vtc_ld = int32_t(align_up(C, 64));
+        put(&W.ctxn, 2 * C * uint64_t(d.d_ctx));
+        put(&W.kvc, 2 * C * 2 * dkv);
+        put(&W.vtc, 2 * dkv * uint64_t(W.vtc_ld));
+    }
+    if (d.vocab > 0) {
+        put(&W.logits, 4 * uint64_t(d.vocab));
+        put(&W.token, 256);
+    }
+    W.bytes = off;
+    return W;
+}
+
+KvLayout make_kv(const dl_module_desc& d) {
+    KvLayout K;
+    if (d.max_seq <= 0) return K;
+    const uint64_t dkv = uint64_t(d.n_kv_heads) * d.d_head;
+    K.v_ld = int32_t(align_up(uint64_t(d.max_seq), 64));
+    K.k_layer_bytes = align_up(2 * dkv * uint64_t(d.max_seq));
+    K.v_layer_bytes = align_up(2 * dkv * uint64_t(K.v_ld));
+    K.bytes = uint64_t(d.n_layers) * (K.k_layer_bytes + K.v_layer_bytes);
+    return K;
+}
+
+// ------------------------------------------------------------------------------------------
+// One pass as a list of queue operations (Sec. IV-C(ii): slots, DMA-done / compute-done events)
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int32_t QC = 0, QD = 1;   // compute queue, copy (DMA) queue
+dl_trace_op mk(int32_t q, int32_t op, int32_t ev, int32_t slot, int32_t module, int32_t layer) {
+    return dl_trace_op{q, op, ev, slot, module, layer, 0};
+}
+}  // namespace
+
+void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32_t mode, int32_t wrap_prefetch,
+                bool force_stream_all, SlotBook* book, std::vector<dl_trace_op>* ops) {
+    std::vector<int32_t> streamed;
+    for (int32_t i = 0; i < n_layers; ++i)
+        if (force_stream_all || !resident[i]) streamed.push_back(i);
+    std::vector<int32_t> slot_of(n_layers, -1);
+
+    if (mode == DL_MODE_SEQUENTIAL) {
+        // Sec. IV-B: the copy of a layer starts only when the previous layer has finished
+        book->pending_module = book->pending_layer = book->pending_slot = -1;
+        size_t si = 0;
+        for (int32_t i = 0; i < n_layers; ++i) {
+            const bool st = si < streamed.size() && streamed[si] == i;
+            int32_t s = -1;
+            if (st) {
+                ++si;
+                s = int32_t(book->ordinal++ % 2);
+                if (book->pass_recorded) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_PASS_DONE, -1, module, i));
+                ops->push_back(mk(QD, DL_OP_COPY, -1, s, module, i));
+                ops->push_back(mk(QD, DL_OP_RECORD, DL_EV_DMA_DONE, s, module, i));
+                book->dma_recorded[s] = true;
+                ops->push_back(mk(QC, DL_OP_WAIT, DL_EV_DMA_DONE, s, module, i));
+            }
+            ops->push_back(mk(QC, DL_OP_EXEC, -1, s, module, i));
+            if (st) {
+                ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_COMPUTE_DONE, s, module, i));
+                book->compute_recorded[s] = true;
+            }
+            ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_PASS_DONE, -1, module, i));
+            book->pass_recorded = true;
+        }
+        return;
+    }
+
+    auto issue_copy = [&](int32_t layer, bool gate_on_pass) -> int32_t {
+        const int32_t s = int32_t(book->ordinal++ % 2);
+        if (gate_on_pass && book->pass_recorded) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_PASS_DONE, -1, module, layer));
+        // the slot may be overwritten only after the layer that last used it has executed
+        if (book->compute_recorded[s]) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_COMPUTE_DONE, s, module, layer));
+        ops->push_back(mk(QD, DL_OP_COPY, -1, s, module, layer));
+        ops->push_back(mk(QD, DL_OP_RECORD, DL_EV_DMA_DONE, s, module, layer));
+        book->dma_recorded[s] = true;
+        return s;
+    };
+
+    if (!streamed.empty()) {
+        const int32_t first = streamed[0];
+        if (book->pending_module == module && book->pending_layer == first && book->pending_slot >= 0) {
+            slot_of[first] = book->pending_slot;          // prefetched at the end of the previous pass
+        } else {
+            slot_of[first] = issue_copy(first, /*gate_on_pass=*/!wrap_prefetch);
+        }
+    }
+    book->pending_module = book->pending_layer = book->pending_slot = -1;
+
+    size_t si = 0;
+    for (int32_t i = 0; i < n_layers; ++i) {
+        const bool st = si < streamed.size() && streamed[si] == i;
+        int32_t s = -1;
+        if (st) {
+            s = slot_of[i];
+            // a layer never executes before its parameters have arrived
+            ops->push_back(mk(QC, DL_OP_WAIT, DL_EV_DMA_DONE, s, module, i));
+            ++si;
+            if (si < streamed.size()) {
+                slot_of[streamed[si]] = issue_copy(streamed[si], false);   // prefetch the next streamed layer
+            } else if (wrap_prefetch) {
+                book->pending_slot = issue_copy(streamed[0], false);       // first streamed layer of the next pass
+                for (size_t b = ops->size(); b-- > 0;)
+                    if ((*ops)[b].op == DL_OP_COPY) { (*ops)[b].flags |= DL_OPF_NEXT_PASS; break; }
+                book->pending_module = module;
+                book->pending_layer = streamed[0];
+            }
+        }
+        ops->push_back(mk(QC, DL_OP_EXEC, -1, s, module, i));
+        if (st) {
+            ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_COMPUTE_DONE, s, module, i));
+            book->compute_recorded[s] = true;
+        }
+    }
+    ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_PASS_DONE, -1, module, n_layers - 1));
+    book->pass_recorded = true;
+}
+
+}  // namespace dl
+
+// ------------------------------------------------------------------------------------------
+// Planner and predictor: pure functions of the C ABI
+// ------------------------------------------------------------------------------------------
+extern "C" {
+
+int32_t dl_place_interleaved(int32_t n_layers, int32_t k, int32_t* idx_out) {
+    if (n_layers < 1 || k < 0 || k > n_layers || (k > 0 && !idx_out)) return DL_ERR_INVALID_ARG;
+    if (k == n_layers) {
+        for (int32_t i = 0; i < k; ++i) idx_out[i] = i;
+        return DL_OK;
+    }
+    for (int32_t i = 0; i < k; ++i) idx_out[i] = int32_t((int64_t(i) * (n_layers - 1)) / k);
+    return DL_OK;
+}
+
+int32_t dl_benefit(double c_dma_ms, double m_mib, int32_t n_phases, const double* c_exe_ms, const int32_t* reps,
+                   double* out3) {
+    if (!(c_dma_ms >= 0) || !(m_mib > 0) || n_phases < 1 || !c_exe_ms || !reps || !out3) return DL_ERR_INVALID_ARG;
+    double first = 0, mid = 0, last = 0;
+    for (int32_t p = 0; p < n_phases; ++p) {
+        if (reps[p] < 0 || !(c_exe_ms[p] >= 0)) return DL_ERR_INVALID_ARG;
+        const double R = reps[p];
+        if (c_dma_ms <= c_exe_ms[p]) {
+            // EXE-intensive phase (Table IV): only the exposed leading copy of each pass is saved
+            first += R * c_dma_ms;
+        } else {
+            // DMA-intensive phase (Table V): every copy is on the critical path; removing the last one
+            // leaves a new trailing execution behind
+            first += R * c_dma_ms;
+            mid += R * c_dma_ms;
+            last += R * (c_dma_ms - c_exe_ms[p]);
+        }
+    }
+    out3[0] = first / m_mib;
+    out3[1] = mid / m_mib;
+    out3[2] = last / m_mib;
+    return DL_OK;
+}
+
+int32_t dl_consecutive_limit(double c_dma_ms, double c_exe_ms, int32_t* out) {
+    if (!(c_dma_ms >= 0) || !(c_exe_ms > 0) || !out) return DL_ERR_INVALID_ARG;
+    *out = int32_t(std::floor(c_dma_ms / c_exe_ms));
+    return DL_OK;
+}
+
+int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t k, double* out) {
+    if (k < 0 || !out) return DL_ERR_INVALID_ARG;
+    *out = c_total0_ms - double(k) * slope_ms_per_layer;
+    return DL_OK;
+}
+
+int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_t* streamed, const uint8_t* pass_start,
+                    const int32_t* module_id, int32_t n, int32_t mode, int32_t wrap_prefetch, double overhead_ms,
+                    double* total_ms, double* hidden_frac, double* exposed_ms) {
+    if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
+    if (mode != DL_MODE_PIPELINED && mode != DL_MODE_SEQUENTIAL) return DL_ERR_INVALID_ARG;
+    if (n > 0 && !pass_start[0]) return DL_ERR_INVALID_ARG;
+    // Replays the very schedule a pass enqueues (build_pass) on two in-order queues.
+    struct Pass { int32_t j0, j1, module; };
+    std::vector<Pass> passes;
+    for (int32_t j = 0; j < n;) {
+        int32_t j1 = j + 1;
+        while (j1 < n && !pass_start[j1]) ++j1;
+        passes.push_back({j, j1, module_id ? module_id[j] : 0});
+        j = j1;
+    }
+    dl::SlotBook book;
+    double t[2] = {0, 0};                       // queue clocks: [0] compute, [1] copy
+    double ev_dma[2] = {0, 0}, ev_comp[2] = {0, 0}, ev_pass = 0;
+    double copy_start[2] = {0, 0}, copy_dur[2] = {0, 0};
+    double exposed = 0, dma_sum = 0;
+    std::vector<dl_trace_op> ops;
+    std::vector<uint8_t> resident;
+    for (size_t p = 0; p < passes.size(); ++p) {
+        const Pass& P = passes[p];
+        resident.assign(size_t(P.j1 - P.j0), 0);
+        for (int32_t j = P.j0; j < P.j1; ++j) resident[size_t(j - P.j0)] = streamed[j] ? 0 : 1;
+        ops.clear();
+        dl::build_pass(P.module, P.j1 - P.j0, resident.data(), mode, wrap_prefetch, false, &book, &ops);
+        for (const dl_trace_op& o : ops) {
+            const int32_t q = o.queue;
+            const int32_t j = P.j0 + o.layer;
+            switch (o.op) {
+                case DL_OP_WAIT: {
+                    const double e = o.event_kind == DL_EV_DMA_DONE ? ev_dma[o.slot]
+                                   : o.event_kind == DL_EV_COMPUTE_DONE ? ev_comp[o.slot] : ev_pass;
+                    if (q == 0 && o.event_kind == DL_EV_DMA_DONE) {
+                        // time the compute queue idles while the copy it needs is in flight
+                        exposed += std::max(0.0, e - std::max(t[0], copy_start[o.slot]));
+                        dma_sum += copy_dur[o.slot];
+                    }
+                    t[q] = std::max(t[q], e);
+                    break;
+                }
+                case DL_OP_RECORD:
+                    if (o.event_kind == DL_EV_DMA_DONE) ev_dma[o.slot] = t[q];
+                    else if (o.event_kind == DL_EV_COMPUTE_DONE) ev_comp[o.slot] = t[q];
+                    else ev_pass = t[q];
+                    break;
+                case DL_OP_COPY: {
+                    int32_t jj = j;
+                    if (o.flags & DL_OPF_NEXT_PASS) {
+                        // prefetch for the next pass: takes that pass's copy time when it runs the same module
+                        if (p + 1 < passes.size() && passes[p + 1].module == P.module &&
+                            o.layer < passes[p + 1].j1 - passes[p + 1].j0)
+                            jj = passes[p + 1].j0 + o.layer;
+                    }
+                    copy_start[o.slot] = t[q];
+                    copy_dur[o.slot] = c_dma_ms[jj];
+                    t[q] += c_dma_ms[jj];
+                    break;
+                }
+                case DL_OP_EXEC:
+                    t[q] += c_exe_ms[j] + overhead_ms;
+                    break;
+                default: break;
+            }
+        }
+    }
+    if (total_ms) *total_ms = t[0];
+    if (exposed_ms) *exposed_ms = exposed;
+    if (hidden_frac) *hidden_frac = dma_sum > 0 ? 1.0 - exposed / dma_sum : 1.0;
+    return DL_OK;
+}
+
+int32_t dl_plan(int32_t n_modules, const int32_t* n_layers, const uint64_t* layer_bytes, const double* b3,
+                uint64_t budget_bytes, int32_t* k_out) {
+    if (n_modules < 1 || !n_layers || !layer_bytes || !b3 || !k_out) return DL_ERR_INVALID_ARG;
+    // candidate groups: a module's first layer, its middle layers, its last layer (Tables IV-VI rank them
+    // first >= middle >= last inside a module); groups are taken in order of benefit per MiB
+    struct Group { double b; int32_t module, order, count; };
+    std::vector<Group> groups;
+    for (int32_t m = 0; m < n_modules; ++m) {
+        if (n_layers[m] < 1 || layer_bytes[m] == 0) return DL_ERR_INVALID_ARG;
+        const double* b = b3 + 3 * m;
+        if (!(b[0] >= 0) || !(b[1] >= 0) || !(b[2] >= 0)) return DL_ERR_INVALID_ARG;
+        k_out[m] = 0;
+        if (n_layers[m] == 1) {
+            groups.push_back({b[0], m, 0, 1});
+            continue;
+        }
+        groups.push_back({b[0], m, 0, 1});
+        if (n_layers[m] > 2) groups.push_back({std::min(b[1], b[0]), m, 1, n_layers[m] - 2});
+        groups.push_back({std::min(b[2], std::min(b[1], b[0])), m, 2, 1});
+    }
+    std::stable_sort(groups.begin(), groups.end(), [](const Group& a, const Group& c) {
+        if (a.b != c.b) return a.b > c.b;
+        if (a.module != c.module) return a.module < c.module;
+        return a.order < c.order;
+    });
+    uint64_t left = budget_bytes;
+    std::vector<int32_t> next_order(size_t(n_modules), 0);
+    for (const Group& g : groups) {
+        if (!(g.b > 0)) break;                              // no time to win: keep the memory
+        if (g.order != next_order[size_t(g.module)]) continue;   // never skip ahead inside a module
+        const uint64_t each = layer_bytes[g.module];
+        const int32_t take = int32_t(std::min<uint64_t>(uint64_t(g.count), left / each));
+        k_out[g.module] += take;
+        left -= uint64_t(take) * each;
+        if (take == g.count) next_order[size_t(g.module)] = g.order + 1;
+        else next_order[size_t(g.module)] = 99;             // group cut short: nothing further from this module
+    }
+    return DL_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,177 @@
+// Row-wise kernels that move activations once through HBM: normalisation (wavefront reductions),
+// rotary embedding + KV scatter after the QKV projection, embedding lookup, greedy argmax.
+#include "kernels.hpp"
+
+namespace dlk {
+
+namespace {
+
+__device__ __forceinline__ float bf16_to_f(bf16_t v) { return __uint_as_float(uint32_t(v) << 16); }
+__device__ __forceinline__ bf16_t f_to_bf16(float f) {
+    __bf16 b = (__bf16)f;
+    return *reinterpret_cast<bf16_t*>(&b);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// sum over a 256-thread block; every thread gets the result
+__device__ __forceinline__ float block_sum_256(float v, float* red) {
+    v = wave_sum(v);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();               // red may still be read from a previous call
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+}
+
+template <int KIND, bool OUT_F32>
+__global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, const bf16_t* __restrict__ g,
+                                                   const bf16_t* __restrict__ b, void* __restrict__ out, int d,
+                                                   float eps) {
+    __shared__ float red[4];
+    const float* row = x + size_t(blockIdx.x) * d;
+    const int tid = threadIdx.x;
+    float mean = 0.0f;
+    if (KIND == 1) {
+        float s = 0.0f;
+        for (int i = tid; i < d; i += 256) s += row[i];
+        mean = block_sum_256(s, red) / float(d);
+    }
+    float ss = 0.0f;
+    for (int i = tid; i < d; i += 256) {
+        const float c = row[i] - mean;
+        ss += c * c;
+    }
+    const float inv = rsqrtf(block_sum_256(ss, red) / float(d) + eps);
+    for (int i = tid; i < d; i += 256) {
+        float v = (row[i] - mean) * inv * bf16_to_f(g[i]);
+        if (KIND == 1) v += bf16_to_f(b[i]);
+        if (OUT_F32) static_cast<float*>(out)[size_t(blockIdx.x) * d + i] = v;
+        else static_cast<bf16_t*>(out)[size_t(blockIdx.x) * d + i] = f_to_bf16(v);
+    }
+}
+
+__global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, uint64_t n) {
+    for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += uint64_t(gridDim.x) * 256)
+        out[i] = f_to_bf16(x[i]);
+}
+
+__global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs p) {
+    const int t = blockIdx.x, pos = p.pos0 + t;
+    bf16_t* row = p.qkv + size_t(t) * p.n_qkv;
+    const int half = p.dh >> 1;
+    const float l2t = p.theta > 0.0f ? log2f(p.theta) : 0.0f;
+    // q: rotate in place
+    if (p.theta > 0.0f && p.q_off >= 0) {
+        for (int idx = threadIdx.x; idx < p.Hq * half; idx += 256) {
+            const int h = idx / half, i = idx % half;
+            const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * l2t);
+            float sn, cs;
+            sincosf(ang, &sn, &cs);
+            bf16_t* q = row + p.q_off + h * p.dh;
+            const float a = bf16_to_f(q[i]), b = bf16_to_f(q[i + half]);
+            q[i] = f_to_bf16(a * cs - b * sn);
+            q[i + half] = f_to_bf16(a * sn + b * cs);
+        }
+    }
+    // k: rotate, then to the cache (or back in place)
+    for (int idx = threadIdx.x; idx < p.Hkv * half; idx += 256) {
+        const int g = idx / half, i = idx % half;
+        const bf16_t* k = row + p.k_off + g * p.dh;
+        float a = bf16_to_f(k[i]), b = bf16_to_f(k[i + half]);
+        if (p.theta > 0.0f) {
+            const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * l2t);
+            float sn, cs;
+            sincosf(ang, &sn, &cs);
+            const float ra = a * cs - b * sn, rb = a * sn + b * cs;
+            a = ra;
+            b = rb;
+        }
+        bf16_t* dst = p.k_out ? p.k_out + size_t(g) * p.k_head_stride + size_t(pos) * p.dh
+                              : row + p.k_off + g * p.dh;
+        if (p.k_out || p.theta > 0.0f) {
+            dst[i] = f_to_bf16(a);
+            dst[i + half] = f_to_bf16(b);
+        }
+    }
+    // v: transposed store, position-contiguous rows per feature
+    for (int idx = threadIdx.x; idx < p.Hkv * p.dh; idx += 256) {
+        const int g = idx / p.dh, e = idx % p.dh;
+        p.vt_out[size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + pos] = row[p.v_off + idx];
+    }
+}
+
+__global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ table, int d,
+                                                    const int32_t* __restrict__ token_dev, int token_host,
+                                                    float* __restrict__ x_out) {
+    const int tok = token_dev ? *token_dev : token_host;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < d; i += gridDim.x * 256)
+        x_out[i] = bf16_to_f(table[size_t(tok) * d + i]);
+}
+
+__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ v, int n, int32_t* __restrict__ out) {
+    __shared__ float sv[1024];
+    __shared__ int si[1024];
+    float best = -INFINITY;
+    int bi = 0x7FFFFFFF;
+    for (int i = threadIdx.x; i < n; i += 1024) {
+        const float x = v[i];
+        if (x > best || (x == best && i < bi)) { best = x; bi = i; }
+    }
+    sv[threadIdx.x] = best;
+    si[threadIdx.x] = bi;
+    __syncthreads();
+    for (int s = 512; s > 0; s >>= 1) {
+        if (threadIdx.x < s) {
+            const float o = sv[threadIdx.x + s];
+            const int oi = si[threadIdx.x + s];
+            if (o > sv[threadIdx.x] || (o == sv[threadIdx.x] && oi < si[threadIdx.x])) {
+                sv[threadIdx.x] = o;
+                si[threadIdx.x] = oi;
+            }
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *out = si[0] == 0x7FFFFFFF ? 0 : si[0];
+}
+
+}  // namespace
+
+void norm_rows(int kind, const float* x, const bf16_t* g, const bf16_t* b, void* out, bool out_f32, int T, int d,
+               float eps, hipStream_t st) {
+    if (T <= 0) return;
+    dim3 grid(T), block(256);
+    if (kind == 0) {
+        if (out_f32) hipLaunchKernelGGL((norm_kernel<0, true>), grid, block, 0, st, x, g, b, out, d, eps);
+        else hipLaunchKernelGGL((norm_kernel<0, false>), grid, block, 0, st, x, g, b, out, d, eps);
+    } else {
+        if (out_f32) hipLaunchKernelGGL((norm_kernel<1, true>), grid, block, 0, st, x, g, b, out, d, eps);
+        else hipLaunchKernelGGL((norm_kernel<1, false>), grid, block, 0, st, x, g, b, out, d, eps);
+    }
+}
+
+void cast_f32_bf16(const float* x, bf16_t* out, uint64_t n, hipStream_t st) {
+    if (n == 0) return;
+    const uint64_t blocks = (n + 255) / 256;
+    dim3 grid(unsigned(blocks < 4096 ? blocks : 4096)), block(256);
+    hipLaunchKernelGGL(cast_kernel, grid, block, 0, st, x, out, n);
+}
+
+void qkv_post(const QkvPostArgs& a, hipStream_t st) {
+    if (a.T <= 0) return;
+    hipLaunchKernelGGL(qkv_post_kernel, dim3(a.T), dim3(256), 0, st, a);
+}
+
+void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_host, float* x_out, hipStream_t st) {
+    hipLaunchKernelGGL(embed_kernel, dim3((d + 255) / 256), dim3(256), 0, st, table, d, token_dev, token_host, x_out);
+}
+
+void argmax_f32(const float* logits, int n, int32_t* token_dev, hipStream_t st) {
+    hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(1024), 0, st, logits, n, token_dev);
+}
+
+}  // namespace dlk

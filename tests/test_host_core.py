@@ -1,0 +1,321 @@
+"""CPU tests of the library's host logic through the C ABI: exports, packing sizes, planner and
+predictor against the oracle, the slot protocol on a host-only context, budget accounting."""
+import itertools
+import json
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+from oracle import planner as P
+from paper_2605_11678_amd import binding as B
+from paper_2605_11678_amd import build, configs as CFG
+from paper_2605_11678_amd.harness import Engine, desc_fields
+from tests.des_sim import simulate
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOLD = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_values.json")))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _built():
+    build.ensure_built()
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "demand_layering.h")).read()
+    names = set(re.findall(r"\b(dl_[a-z_0-9]+)\s*\(", hdr))
+    assert len(names) >= 30
+    lib = B.lib()
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+    assert names == set(B.SIGNATURES), names ^ set(B.SIGNATURES)
+
+
+def tiny_weights(c, rng):
+    def gen(l):
+        return {tid: rng.integers(0, 2 ** 16, size=shape, dtype=np.uint16) for tid, shape, _ in CFG.layer_tensors(c)}
+    return gen
+
+
+def small_cfg(n_layers=4, **kw):
+    c = CFG.tiny_decoder()
+    c.n_layers = n_layers
+    c.vocab = 0
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_packed_layer_sizes_match_paper():
+    eng = Engine(1 << 40, device=-1)
+    for c, want_mib in ((CFG.decoder_8b(n_layers=1), GOLD["layer_sizes_MiB"]["vlm"]),
+                        (CFG.vit_encoder(n_layers=1), GOLD["layer_sizes_MiB"]["vit"])):
+        c.vocab = 0
+        mid = eng.ctx.module_create(**desc_fields(c, 16))
+        packed, params = eng.ctx.module_layer_bytes(mid)
+        assert params == 2 * CFG.layer_param_count(c)
+        assert abs(params / 2 ** 20 - want_mib) < 0.05          # Sec. IV-D prints 368.0 and 29.1 (MiB)
+        assert params <= packed <= params + 64 * 256            # sections are 256-byte aligned, nothing else added
+    eng.close()
+
+
+def test_placement_matches_eq8():
+    for L in (1, 4, 8, 27, 36):
+        for k in range(0, L + 1):
+            assert B.place_interleaved(L, k) == P.interleaved_placement(k, L)
+    with pytest.raises(B.DLError):
+        B.place_interleaved(4, 5)
+
+
+def test_benefit_tables_and_limit():
+    rnd = random.Random(3)
+    for _ in range(50):
+        c_dma, m = rnd.uniform(0.5, 12), rnd.uniform(20, 400)
+        lo, hi = c_dma * rnd.uniform(0.05, 0.9), c_dma * rnd.uniform(1.1, 4)
+        R = rnd.randint(1, 30)
+        assert B.benefit(c_dma, m, [hi], [R]) == pytest.approx(P.benefit_exe_intensive(R, c_dma, m))
+        assert B.benefit(c_dma, m, [lo], [R]) == pytest.approx(P.benefit_dma_intensive(R, c_dma, lo, m))
+        assert B.benefit(c_dma, m, [hi, lo], [1, R]) == pytest.approx(P.benefit_hybrid(R, c_dma, lo, m))
+    t7 = GOLD["table7_benefit_ms_per_MB"]
+    assert B.benefit(10.9, 368.0, [16.6, 0.9], [1, 21]) == pytest.approx(t7["vlm"], abs=1e-3)
+    assert B.benefit(3.6, 120.8, [1.0], [10]) == pytest.approx(t7["expert"], abs=1e-3)
+    assert B.benefit(0.9, 29.1, [8.3], [1]) == pytest.approx(t7["vit"], abs=1e-3)
+    assert B.consecutive_limit(10.9, 0.9) == P.consecutive_residency_limit(10.9, 0.9) == 12
+
+
+def test_predict_linear_table8():
+    t8 = GOLD["table8_prediction"]
+    for row in t8["rows"]:
+        got = B.predict_linear(t8["C_total_0_s"] * 1e3, -t8["slope_ms_per_layer"], row["k"]) / 1e3
+        assert abs(got - row["predicted_s"]) < 6e-4
+
+
+def _flatten(invocations):
+    dma, exe, st, ps = [], [], [], []
+    for layers in invocations:
+        for i, (d, e, s) in enumerate(layers):
+            dma.append(d), exe.append(e), st.append(s), ps.append(i == 0)
+    return dma, exe, st, ps
+
+
+@pytest.mark.parametrize("wrap", [0, 1])
+def test_timeline_matches_oracle_recurrence(wrap):
+    rnd = random.Random(11)
+    for trial in range(200):
+        L = rnd.randint(1, 7)
+        n_pass = rnd.randint(1, 4)
+        mask = [rnd.random() < 0.6 for _ in range(L)]
+        dma = [rnd.uniform(0.1, 5) for _ in range(L)]
+        inv = [[(dma[i], rnd.uniform(0.1, 5), mask[i]) for i in range(L)] for _ in range(n_pass)]
+        want = P.timeline(inv, wrap_prefetch=bool(wrap))
+        got = B.timeline(*_flatten(inv), wrap_prefetch=wrap)
+        assert got["total"] == pytest.approx(want["total"], rel=1e-12)
+        assert got["exposed"] == pytest.approx(want["exposed"], rel=1e-9, abs=1e-12)
+        assert got["hidden"] == pytest.approx(want["hidden"], rel=1e-9, abs=1e-12)
+        seq = B.timeline(*_flatten(inv), mode=B.DL_MODE_SEQUENTIAL)
+        assert seq["total"] == pytest.approx(P.sequential_time(inv), rel=1e-12)
+
+
+def test_timeline_closed_forms_eq5_eq6_eq7():
+    L, R = 36, 21
+    uni = lambda d, e: [(d, e, True)] * L
+    assert B.timeline(*_flatten([uni(0.9, 8.3)]))["total"] == pytest.approx(P.module_time_exe_intensive(1, L, 0.9, 8.3))
+    assert B.timeline(*_flatten([uni(3.6, 1.0)] * 10))["total"] == pytest.approx(P.module_time_dma_intensive(10, L, 3.6, 1.0))
+    hyb = [uni(10.9, 16.6)] + [uni(10.9, 0.9)] * R
+    assert B.timeline(*_flatten(hyb))["total"] == pytest.approx(P.module_time_hybrid(R, L, 10.9, 16.6, 0.9))
+
+
+def _host_engine_with_module(c, cap=1 << 34, max_tokens=8):
+    eng = Engine(cap, device=-1)
+    rng = np.random.default_rng(0)
+    mid = eng.add_module(c, max_tokens, weights=tiny_weights(c, rng))
+    return eng, mid
+
+
+def _ops_for_des(trace, dma, exe):
+    ops = []
+    for o in trace:
+        q = "compute" if o["queue"] == 0 else "copy"
+        if o["op"] == B.DL_OP_WAIT:
+            ops.append((q, ("wait", (o["event_kind"], o["slot"]))))
+        elif o["op"] == B.DL_OP_RECORD:
+            ops.append((q, ("record", (o["event_kind"], o["slot"]))))
+        elif o["op"] == B.DL_OP_COPY:
+            ops.append((q, ("copy", dma[o["layer"]], o)))
+        else:
+            ops.append((q, ("exec", exe[o["layer"]], o)))
+    return ops
+
+
+@pytest.mark.parametrize("wrap", [0, 1])
+def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap):
+    """The schedule dl_forward enqueues (recorded by a host-only context) is replayed on an independent
+    two-queue simulator: a layer never executes before its copy ended, a slot is never overwritten while
+    the layer that used it is still running (Sec. IV-C(ii)), and the end time equals both predictors."""
+    rnd = random.Random(5)
+    for L in (1, 2, 3, 5, 6):
+        c = small_cfg(L)
+        eng, mid = _host_engine_with_module(c)
+        eng.ctx.set_mode(B.DL_MODE_PIPELINED, wrap)
+        dma = [rnd.uniform(0.2, 4) for _ in range(L)]
+        exe = [rnd.uniform(0.2, 4) for _ in range(L)]
+        for mask in itertools.product([0, 1], repeat=L):
+            resident = [i for i in range(L) if mask[i]]
+            eng.ctx.set_residency(mid, resident)
+            assert eng.ctx.get_residency(mid, L) == resident
+            n_pass = 3
+            for _ in range(n_pass):
+                eng.ctx.forward(mid, 0, 0, 1, 0)
+            trace = eng.ctx.trace_read()
+            execs = [o for o in trace if o["op"] == B.DL_OP_EXEC]
+            assert [o["layer"] for o in execs] == list(range(L)) * n_pass
+            for o in execs:
+                assert (o["slot"] < 0) == (o["layer"] in resident)
+            ops = _ops_for_des(trace, dma, exe)
+            times = simulate(ops)
+            # safety: pair every streamed exec with the last copy into its slot
+            last_copy = {}
+            busy_until = {0: 0.0, 1: 0.0}
+            for (q, op), (t0, t1) in zip(ops, times):
+                if op[0] == "copy":
+                    s = op[2]["slot"]
+                    assert t0 >= busy_until[s] - 1e-12, "slot overwritten while in use"
+                    last_copy[s] = (op[2]["layer"], t1)
+                elif op[0] == "exec" and op[2]["slot"] >= 0:
+                    s = op[2]["slot"]
+                    assert last_copy[s][0] == op[2]["layer"], "layer executed from a slot holding another layer"
+                    assert t0 >= last_copy[s][1] - 1e-12, "layer executed before its parameters arrived"
+                    busy_until[s] = t1
+            total = max(t1 for (q, op), (t0, t1) in zip(ops, times) if q == "compute")
+            inv = [[(dma[i], exe[i], not mask[i]) for i in range(L)]] * n_pass
+            assert total == pytest.approx(P.timeline(inv, wrap_prefetch=bool(wrap))["total"], rel=1e-12)
+            assert total == pytest.approx(B.timeline(*_flatten(inv), wrap_prefetch=wrap)["total"], rel=1e-12)
+        eng.close()
+
+
+def test_sequential_schedule_never_overlaps():
+    L = 4
+    c = small_cfg(L)
+    eng, mid = _host_engine_with_module(c)
+    eng.ctx.set_mode(B.DL_MODE_SEQUENTIAL, 0)
+    eng.ctx.set_residency(mid, [1])
+    for _ in range(2):
+        eng.ctx.forward(mid, 0, 0, 1, 0)
+    trace = eng.ctx.trace_read()
+    dma, exe = [1.0, 2.0, 3.0, 4.0], [0.5, 0.25, 0.125, 1.5]
+    ops = _ops_for_des(trace, dma, exe)
+    times = simulate(ops)
+    spans = sorted((t0, t1) for (q, op), (t0, t1) in zip(ops, times) if op[0] in ("copy", "exec"))
+    for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+        assert b0 >= a1 - 1e-12
+    assert spans[-1][1] == pytest.approx(2 * (sum(exe) + dma[0] + dma[2] + dma[3]))
+    eng.close()
+
+
+def test_budget_two_slots_plus_one_resident_layer():
+    """Tiny-decoder budget: room for the workspace, the KV cache, two slots and ONE resident layer."""
+    c = small_cfg(4)
+    probe, mid = _host_engine_with_module(c, cap=1 << 30, max_tokens=128)
+    packed, _ = probe.ctx.module_layer_bytes(mid)
+    base = probe.ctx.arena_stats()["used"]          # workspace + KV cache + two slots
+    probe.close()
+    eng, mid = _host_engine_with_module(c, cap=base + packed + 256, max_tokens=128)
+    eng.ctx.set_residency(mid, [0])
+    used1 = eng.ctx.arena_stats()["used"]
+    assert used1 == base + packed
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.set_residency(mid, [0, 2])
+    assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED
+    # the failed call changed nothing
+    assert eng.ctx.get_residency(mid, 4) == [0] and eng.ctx.arena_stats()["used"] == used1
+    eng.ctx.set_residency(mid, [3])
+    assert eng.ctx.get_residency(mid, 4) == [3] and eng.ctx.arena_stats()["used"] == used1
+    eng.ctx.set_residency(mid, [])
+    assert eng.ctx.arena_stats()["used"] == base
+    eng.close()
+
+
+def test_all_resident_releases_slots_and_bigger_module_resizes_them():
+    c = small_cfg(3)
+    eng, mid = _host_engine_with_module(c, cap=1 << 30)
+    packed, _ = eng.ctx.module_layer_bytes(mid)
+    base = eng.ctx.arena_stats()["used"]
+    eng.ctx.set_residency(mid, [0, 1, 2])
+    assert eng.ctx.arena_stats()["used"] == base - 2 * packed + 3 * packed
+    eng.ctx.forward(mid, 0, 0, 1, 0)
+    assert all(o["op"] in (B.DL_OP_EXEC, B.DL_OP_RECORD) and o["queue"] == 0 for o in eng.ctx.trace_read())
+    eng.ctx.set_residency(mid, [])
+    assert eng.ctx.arena_stats()["used"] == base
+    big = small_cfg(2, d_ff=1536)
+    rng = np.random.default_rng(1)
+    mid2 = eng.add_module(big, 8, weights=tiny_weights(big, rng))
+    packed2, _ = eng.ctx.module_layer_bytes(mid2)
+    assert packed2 > packed
+    ws_kv2 = eng.ctx.arena_stats()["used"] - base - 2 * (packed2 - packed)
+    assert ws_kv2 > 0            # slots grew to the largest layer over all modules (2 x M_max), plus module 2's workspace
+    eng.close()
+
+
+def test_error_paths():
+    c = small_cfg(2)
+    eng = Engine(1 << 30, device=-1)
+    mid = eng.ctx.module_create(**desc_fields(c, 8))
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.forward(mid, 0, 0, 1, 0)
+    assert e.value.code == B.DL_ERR_BAD_STATE
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.module_finalize(mid)           # tensors missing
+    assert e.value.code == B.DL_ERR_BAD_STATE
+    rng = np.random.default_rng(2)
+    w = tiny_weights(c, rng)
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.layer_set_tensor(mid, 0, CFG.T_WQ, np.zeros(7, np.uint16))      # wrong size
+    assert e.value.code == B.DL_ERR_INVALID_ARG
+    with pytest.raises(B.DLError):
+        eng.ctx.layer_set_tensor(mid, 0, CFG.T_BQ, np.zeros(256, np.uint16))    # tensor the module does not have
+    with pytest.raises(B.DLError):
+        eng.ctx.layer_set_tensor(mid, 5, CFG.T_WQ, np.zeros(256 * 256, np.uint16))
+    for l in range(2):
+        for tid, arr in w(l).items():
+            eng.ctx.layer_set_tensor(mid, l, tid, arr.reshape(-1))
+    eng.ctx.module_finalize(mid)
+    for bad in ([2], [-1], [0, 0]):
+        with pytest.raises(B.DLError) as e:
+            eng.ctx.set_residency(mid, bad)
+        assert e.value.code == B.DL_ERR_INVALID_ARG
+    with pytest.raises(B.DLError):
+        eng.ctx.forward(mid, 0, 0, 9, 0)       # more tokens than max_tokens
+    with pytest.raises(B.DLError):
+        eng.ctx.forward(mid, 0, 0, 1, 160)     # beyond max_seq
+    with pytest.raises(B.DLError):
+        eng.ctx.module_create(**desc_fields(small_cfg(2, d_head=12), 8))
+    eng.close()
+    # a slot pair that does not fit the arena is refused at finalize, and nothing stays allocated
+    small = Engine(600_000, device=-1)
+    mid = small.ctx.module_create(**desc_fields(c, 8))
+    for l in range(2):
+        for tid, arr in w(l).items():
+            small.ctx.layer_set_tensor(mid, l, tid, arr.reshape(-1))
+    with pytest.raises(B.DLError) as e:
+        small.ctx.module_finalize(mid)
+    assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED and small.ctx.arena_stats()["used"] == 0
+    small.close()
+
+
+def test_plan_follows_benefit_ranking():
+    t7 = GOLD["table7_benefit_ms_per_MB"]
+    MiB = 1 << 20
+    n_layers = [27, 36, 36]
+    sizes = [int(29.1 * MiB), int(368.0 * MiB), int(120.8 * MiB)]
+    b3 = [t7["vit"], t7["vlm"], t7["expert"]]
+    # Sec. IV-D: with the RTX 5070 Ti numbers the budget goes to VLM layers only
+    assert B.plan(n_layers, sizes, b3, 28 * sizes[1] + 1000) == [0, 28, 0]
+    # an unlimited budget takes everything that saves time: VLM, expert, and only the first ViT layer
+    assert B.plan(n_layers, sizes, b3, 1 << 50) == [1, 36, 36]
+    # budget runs out inside the VLM middle group
+    assert B.plan(n_layers, sizes, b3, 10 * sizes[1]) == [0, 10, 0]
+    # after all VLM layers, the expert layers come next (0.298 > 0.031)
+    assert B.plan(n_layers, sizes, b3, 36 * sizes[1] + 5 * sizes[2] + 10) == [0, 36, 5]
