@@ -201,6 +201,24 @@ typedef struct {
 int32_t dl_set_timing(dl_ctx* ctx, int32_t on);
 int32_t dl_collect_stats(dl_ctx* ctx, dl_run_stats* stats, dl_layer_record* records, int32_t cap);
 
+/* Per-kernel-class timing inside the layers (HIP events on the compute stream around every launch).
+ * flops / bytes are the ALGORITHMIC work of the launches: 2*M*N*K for a linear map, 4*d_head per
+ * (query, visible key) pair for attention; operands read once and results written once for bytes. */
+enum {
+    DL_K_NORM = 0, DL_K_GEMM_QKV = 1, DL_K_QKV_POST = 2, DL_K_ATTN = 3, DL_K_GEMM_O = 4,
+    DL_K_GEMM_UP = 5, DL_K_GEMM_DOWN = 6, DL_K_CROSS = 7, DL_K_COUNT = 8
+};
+typedef struct {
+    int32_t kind;        /* DL_K_* */
+    int32_t launches;
+    double total_ms;
+    double flops;
+    double bytes;
+} dl_kernel_time;
+int32_t dl_set_kernel_timing(dl_ctx* ctx, int32_t on);
+/* synchronises; out: host array [DL_K_COUNT], entry i describes kind i; resets the accumulation */
+int32_t dl_collect_kernel_times(dl_ctx* ctx, dl_kernel_time* out);
+
 /* The schedule one forward pass enqueues, as data (also recorded by host-only contexts). */
 enum { DL_OP_WAIT = 0, DL_OP_RECORD = 1, DL_OP_COPY = 2, DL_OP_EXEC = 3 };
 enum { DL_EV_DMA_DONE = 0, DL_EV_COMPUTE_DONE = 1, DL_EV_PASS_DONE = 2 };

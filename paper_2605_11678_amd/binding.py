@@ -48,6 +48,14 @@ class dl_layer_record(C.Structure):
                 ("exe_end_ms", C.c_float)]
 
 
+class dl_kernel_time(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
+DL_K_NAMES = ["norm", "gemm_qkv", "qkv_post", "attn", "gemm_o", "gemm_up", "gemm_down", "cross"]
+
+
 class dl_trace_op(C.Structure):
     _fields_ = [("queue", C.c_int32), ("op", C.c_int32), ("event_kind", C.c_int32), ("slot", C.c_int32),
                 ("module", C.c_int32), ("layer", C.c_int32), ("flags", C.c_int32)]
@@ -84,6 +92,8 @@ SIGNATURES = {
     "dl_profile": (_i32, [_p, _i32, _i32, _i32, _p, _p, _i32, _i32, C.POINTER(dl_layer_profile)]),
     "dl_set_timing": (_i32, [_p, _i32]),
     "dl_collect_stats": (_i32, [_p, C.POINTER(dl_run_stats), C.POINTER(dl_layer_record), _i32]),
+    "dl_set_kernel_timing": (_i32, [_p, _i32]),
+    "dl_collect_kernel_times": (_i32, [_p, C.POINTER(dl_kernel_time)]),
     "dl_trace_enable": (_i32, [_p, _i32]),
     "dl_trace_read": (_i32, [_p, C.POINTER(dl_trace_op), _i32, _PI32]),
     "dl_place_interleaved": (_i32, [_i32, _i32, _PI32]),
@@ -257,6 +267,15 @@ class Context:
         n = min(st.n_layer_records, max_records)
         d["records"] = [{f: getattr(recs[i], f) for f, _ in dl_layer_record._fields_} for i in range(n)]
         return d
+
+    def set_kernel_timing(self, on):
+        self._ck(lib().dl_set_kernel_timing(self._h, int(on)))
+
+    def collect_kernel_times(self):
+        out = (dl_kernel_time * len(DL_K_NAMES))()
+        self._ck(lib().dl_collect_kernel_times(self._h, out))
+        return {DL_K_NAMES[o.kind]: dict(launches=o.launches, total_ms=o.total_ms, flops=o.flops, bytes=o.bytes)
+                for o in out}
 
     def trace_enable(self, on):
         self._ck(lib().dl_trace_enable(self._h, int(on)))

@@ -62,6 +62,9 @@ struct dl_ctx {
     int32_t last_copy_in_slot[2] = {-1, -1};
     std::vector<hipEvent_t> ev_pool;
     size_t ev_next = 0;
+    bool ktiming = false;
+    struct KRec { int32_t kind; hipEvent_t e0, e1; double flops, bytes; };
+    std::vector<KRec> krecs;
 };
 
 namespace {
@@ -214,10 +217,35 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     const int dm = d.d_model, dh = d.d_head, Hq = d.n_q_heads, Hkv = d.n_kv_heads;
     const int dq = Hq * dh, dkv = Hkv * dh;
     const bool cache = d.max_seq > 0;
+    const double Td = double(T);
+    // optional per-kernel timing: events around each launch, work counted algorithmically
+    dl_ctx::KRec* open_rec = nullptr;
+    auto kbegin = [&](int32_t kind, double flops, double bytes) {
+        if (!c->ktiming) return;
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        if (timing_event(c, &e0) != DL_OK || timing_event(c, &e1) != DL_OK) return;
+        c->krecs.push_back({kind, e0, e1, flops, bytes});
+        open_rec = &c->krecs.back();
+        (void)hipEventRecord(e0, st);
+    };
+    auto kend = [&]() {
+        if (open_rec) (void)hipEventRecord(open_rec->e1, st);
+        open_rec = nullptr;
+    };
+    auto lin_work = [&](double M_, double N_, double K_, double* fl, double* by) {
+        *fl = 2.0 * M_ * N_ * K_;
+        *by = 2.0 * (M_ * K_ + N_ * K_ + M_ * N_);
+    };
+    double fl, by;
 
     // attention sub-block
+    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
     dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
+    kend();
+    lin_work(Td, L.n_qkv, dm, &fl, &by);
+    kbegin(DL_K_GEMM_QKV, fl, by);
     linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
+    kend();
     bf16_t* kc = nullptr;
     bf16_t* vt;
     uint64_t k_hs, v_hs;
@@ -238,17 +266,29 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
         v_hs = uint64_t(dh) * ldv;
     }
     dlk::QkvPostArgs qp{qkv, L.n_qkv, T, pos0, Hq, Hkv, dh, d.rope_theta, kc, k_hs, vt, v_hs, ldv, 0, dq, dq + dkv};
+    kbegin(DL_K_QKV_POST, 0, Td * L.n_qkv * 4.0);
     dlk::qkv_post(qp, st);
+    kend();
     dlk::AttnArgs aa{qkv, L.n_qkv, cache ? kc : qkv + dq, ldk, k_hs, vt, ldv, v_hs, attn, dq,
                      T, pos0 + T, pos0, Hq, Hkv, dh, d.causal};
+    {
+        const double pairs = d.causal ? Td * pos0 + Td * (Td + 1.0) / 2.0 : Td * double(pos0 + T);
+        kbegin(DL_K_ATTN, 4.0 * dh * Hq * pairs, 2.0 * (2.0 * Td * dq + 2.0 * double(pos0 + T) * dkv));
+    }
     dlk::attention(aa, st);
+    kend();
+    lin_work(Td, dm, dq, &fl, &by);
+    kbegin(DL_K_GEMM_O, fl, by + 8.0 * Td * dm);
     linear(st, T, attn, dq, P(L.w_o), dq, dm, P(L.b_o), dlk::EPI_RESID_F32, out, dm, in, dm);
+    kend();
 
     // cross-attention sub-block
     if (d.d_ctx > 0) {
         bf16_t* ctxn = reinterpret_cast<bf16_t*>(ws + M.W.ctxn);
         bf16_t* kvc = reinterpret_cast<bf16_t*>(ws + M.W.kvc);
         bf16_t* vtc = reinterpret_cast<bf16_t*>(ws + M.W.vtc);
+        kbegin(DL_K_CROSS, 2.0 * (2.0 * Td * dq * dm + 2.0 * double(n_ctx) * dkv * d.d_ctx) + 4.0 * dh * Hq * Td * n_ctx,
+               2.0 * (2.0 * double(dq) * dm + 2.0 * double(dkv) * d.d_ctx));
         dlk::norm_rows(d.norm, out, P(L.normc_g), P(L.normc_b), nbuf, false, T, dm, d.norm_eps, st);
         linear(st, T, nbuf, dm, P(L.w_qc), dm, dq, P(L.b_qc), dlk::EPI_BF16, qkv, dq, nullptr, 0);
         dlk::cast_f32_bf16(ctx, ctxn, uint64_t(n_ctx) * d.d_ctx, st);
@@ -261,15 +301,24 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
                          T, n_ctx, 0, Hq, Hkv, dh, 0};
         dlk::attention(ca, st);
         linear(st, T, attn, dq, P(L.w_oc), dq, dm, P(L.b_oc), dlk::EPI_RESID_F32, out, dm, out, dm);
+        kend();
     }
 
     // feed-forward sub-block
+    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
     dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
+    kend();
+    lin_work(Td, L.n_up, dm, &fl, &by);
+    kbegin(DL_K_GEMM_UP, fl, 2.0 * (Td * dm + double(L.n_up) * dm + Td * d.d_ff));
     if (d.act == DL_ACT_SWIGLU)
         linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, d.d_ff, nullptr, 0);
     else
         linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, d.d_ff, nullptr, 0);
+    kend();
+    lin_work(Td, dm, d.d_ff, &fl, &by);
+    kbegin(DL_K_GEMM_DOWN, fl, by + 8.0 * Td * dm);
     linear(st, T, mid, d.d_ff, P(L.w_down), d.d_ff, dm, P(L.b_down), dlk::EPI_RESID_F32, out, dm, out, dm);
+    kend();
 }
 
 hipEvent_t event_of(dl_ctx* c, const dl_trace_op& o) {
@@ -741,7 +790,7 @@ int32_t dl_collect_stats(dl_ctx* c, dl_run_stats* stats, dl_layer_record* recs, 
     if (rc) return rc;
     if (c->execs.empty()) {
         c->copies.clear();
-        c->ev_next = 0;
+        if (c->krecs.empty()) c->ev_next = 0;
         return DL_OK;
     }
     // origin: the earlier of the first copy start and the first exec start
@@ -790,7 +839,7 @@ int32_t dl_collect_stats(dl_ctx* c, dl_run_stats* stats, dl_layer_record* recs, 
     c->copies.clear();
     c->execs.clear();
     c->last_copy_in_slot[0] = c->last_copy_in_slot[1] = -1;
-    c->ev_next = 0;
+    if (c->krecs.empty()) c->ev_next = 0;
     return DL_OK;
 }
 
@@ -846,7 +895,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     sync_streams(c);
     c->copies.clear();
     c->execs.clear();
-    c->ev_next = 0;
+    if (c->krecs.empty()) c->ev_next = 0;
     dl_arena_free(c, tmp);
     if (rc) return rc;
     for (int32_t i = 0; i < Ln; ++i) {
@@ -854,6 +903,35 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         out[i].c_exe_ms = exe[size_t(i)] / (iters - 1);
         out[i].bytes = M->L.bytes;
     }
+    return DL_OK;
+}
+
+int32_t dl_set_kernel_timing(dl_ctx* c, int32_t on) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    c->ktiming = on != 0;
+    return DL_OK;
+}
+
+int32_t dl_collect_kernel_times(dl_ctx* c, dl_kernel_time* out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!out) return fail(c, DL_ERR_INVALID_ARG, "null output");
+    for (int32_t k = 0; k < DL_K_COUNT; ++k) out[k] = dl_kernel_time{k, 0, 0.0, 0.0, 0.0};
+    if (!on_gpu(c)) return DL_OK;
+    rc = sync_streams(c);
+    if (rc) return rc;
+    for (const dl_ctx::KRec& r : c->krecs) {
+        float ms = 0;
+        DL_HIP(c, hipEventElapsedTime(&ms, r.e0, r.e1));
+        dl_kernel_time& o = out[r.kind];
+        o.launches += 1;
+        o.total_ms += ms;
+        o.flops += r.flops;
+        o.bytes += r.bytes;
+    }
+    c->krecs.clear();
+    if (c->copies.empty() && c->execs.empty()) c->ev_next = 0;
     return DL_OK;
 }
 
