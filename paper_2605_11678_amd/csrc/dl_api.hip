@@ -311,13 +311,13 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     lin_work(Td, L.n_up, dm, &fl, &by);
     kbegin(DL_K_GEMM_UP, fl, 2.0 * (Td * dm + double(L.n_up) * dm + Td * d.d_ff));
     if (d.act == DL_ACT_SWIGLU)
-        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, d.d_ff, nullptr, 0);
+        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, L.ffp, nullptr, 0);
     else
-        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, d.d_ff, nullptr, 0);
+        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, L.ffp, nullptr, 0);
     kend();
     lin_work(Td, dm, d.d_ff, &fl, &by);
     kbegin(DL_K_GEMM_DOWN, fl, by + 8.0 * Td * dm);
-    linear(st, T, mid, d.d_ff, P(L.w_down), d.d_ff, dm, P(L.b_down), dlk::EPI_RESID_F32, out, dm, out, dm);
+    linear(st, T, mid, L.ffp, P(L.w_down), L.ffp, dm, P(L.b_down), dlk::EPI_RESID_F32, out, dm, out, dm);
     kend();
 }
 
@@ -526,6 +526,7 @@ int32_t dl_module_create(dl_ctx* c, const dl_module_desc* desc, int32_t* module_
         M.store = static_cast<uint8_t*>(malloc(total));
         if (!M.store) return fail(c, DL_ERR_HOST_ALLOC, "host allocation failed");
     }
+    memset(M.store, 0, total);    // alignment gaps and K padding must be exact zeros
     M.set_mask.assign(size_t(desc->n_layers), 0u);
     M.resident.assign(size_t(desc->n_layers), 0);
     M.res_off.assign(size_t(desc->n_layers), 0);

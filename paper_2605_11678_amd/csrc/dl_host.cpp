@@ -102,6 +102,7 @@ PackLayout make_layout(const dl_module_desc& d) {
     };
     L.n_qkv = int32_t(dq + 2 * dkv);
     L.n_up = int32_t(glu ? 2 * f : f);
+    L.ffp = int32_t(align_up(f, 128));
     put(&L.norm1_g, dm);
     if (ln) put(&L.norm1_b, dm);
     put(&L.w_qkv, (dq + 2 * dkv) * dm);
@@ -122,7 +123,8 @@ PackLayout make_layout(const dl_module_desc& d) {
     if (ln) put(&L.norm2_b, dm);
     put(&L.w_up, uint64_t(L.n_up) * dm);
     if (b) put(&L.b_up, f);
-    put(&L.w_down, dm * f);
+    put(&L.w_down, dm * uint64_t(L.ffp));
+    params -= dm * (uint64_t(L.ffp) - f);      // the zero padding is not a parameter
     if (b) put(&L.b_down, dm);
     L.bytes = off;
     L.param_bytes = 2 * params;
@@ -196,7 +198,10 @@ void pack_tensor(const dl_module_desc& d, const PackLayout& L, int32_t tid, cons
         case DL_T_WO_C: plain(L.w_oc, 0); break;
         case DL_T_BO_C: plain(L.b_oc, 0); break;
         case DL_T_B_UP: plain(L.b_up, 0); break;
-        case DL_T_W_DOWN: plain(L.w_down, 0); break;
+        case DL_T_W_DOWN:
+            // rows padded to ffp elements; the padding stays zero (the store is zero-initialised)
+            for (uint64_t r = 0; r < dm; ++r) std::memcpy(blob + L.w_down + 2 * r * uint64_t(L.ffp), src + r * f, 2 * f);
+            break;
         case DL_T_B_DOWN: plain(L.b_down, 0); break;
         case DL_T_W_GATE:
         case DL_T_W_UP:
@@ -225,7 +230,7 @@ WorkspaceLayout make_workspace(const dl_module_desc& d) {
     put(&W.nbuf, 2 * T * dm);
     put(&W.qkv, 2 * T * (dq + 2 * dkv));
     put(&W.attn, 2 * T * dq);
-    put(&W.mid, 2 * T * f);
+    put(&W.mid, 2 * T * align_up(f, 128));
     if (d.max_seq == 0) {
         W.vt_ld = int32_t(align_up(T, 64));
         put(&W.vt, 2 * dkv * uint64_t(W.vt_ld));

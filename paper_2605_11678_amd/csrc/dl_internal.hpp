@@ -42,6 +42,8 @@ struct PackLayout {
     uint64_t param_bytes = 0;  // 2 * number of parameters
     int32_t n_qkv = 0;         // rows of the fused QKV matrix
     int32_t n_up = 0;          // rows of the first FFN matrix (2*d_ff interleaved for SwiGLU)
+    int32_t ffp = 0;           // d_ff rounded up to 128: row length of the second FFN matrix and of the
+                               // activation between the two (zero padding keeps the GEMM K a multiple of 128)
 };
 
 bool validate_desc(const dl_module_desc& d, std::string* why);

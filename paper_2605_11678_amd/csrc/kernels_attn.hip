@@ -9,8 +9,16 @@
 // accumulator registers = the 8 k-values a lane supplies).  V is kept transposed in memory
 // ([feature][position]) so V^T tiles are plain row loads.
 //
-// Block: 4 wavefronts x 32 queries = 128 queries of one head; K/V tiles of 64 positions in LDS.
+// Block: 4 wavefronts, K/V tiles of 64 positions in LDS, double-buffered; the next tile is fetched into
+// registers while the current one is multiplied.  Two work splits:
+//   HEADS = true  (grouped-query attention, group size a multiple of 4): the four wavefronts are four
+//                  query heads of ONE KV head on the same 32 query positions, so a K/V tile is loaded once
+//                  for four heads;
+//   HEADS = false: the four wavefronts are four 32-query slices of one head (128 queries per block).
 // Head dims 64 / 72 / 128 run as DHP = 64 / 96 / 128 with zero padding (exact zeros contribute nothing).
+// Softmax runs on raw scores: the 1/sqrt(dh) * log2(e) scale is folded into one FMA in front of the
+// base-2 exponential, masking is skipped on tiles that cannot need it, and the running output is
+// rescaled only when some lane's running maximum moved.
 #include "kernels.hpp"
 
 namespace dlk {
@@ -23,26 +31,31 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 namespace {
 
-constexpr int BQ = 128, BKV = 64;
+constexpr int BKV = 64;
 
-template <int DHP>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs p, float scale_log2) {
+template <int DHP, bool HEADS>
+__global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_log2) {
     constexpr int KLD = DHP + 8;     // sK row stride (elements)
     constexpr int VLD = BKV + 8;     // sV row stride
-    __shared__ __attribute__((aligned(16))) bf16_t sK[BKV * KLD];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[DHP * VLD];
+    constexpr int QB = HEADS ? 32 : 128;
+    constexpr int NKC = BKV * (DHP / 8) / 256, NVC = DHP * (BKV / 8) / 256;   // 16-byte chunks per thread
+    __shared__ __attribute__((aligned(16))) bf16_t sK[2][BKV * KLD];
+    __shared__ __attribute__((aligned(16))) bf16_t sV[2][DHP * VLD];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, g2 = lane >> 5;
-    const int h = blockIdx.y, kvh = h / (p.Hq / p.Hkv);
-    const int q0 = blockIdx.x * BQ;
-    const int tq = q0 + 32 * wave + lq;               // this lane's query (token index)
+    const int group = p.Hq / p.Hkv;
+    const int q0 = blockIdx.x * QB;
+    const int h = HEADS ? blockIdx.y * 4 + wave : blockIdx.y;
+    const int kvh = h / group;
+    const int wq0 = HEADS ? q0 : q0 + 32 * wave;       // first query of this wavefront
+    const int tq = wq0 + lq;                           // this lane's query (token index)
     const int qpos = p.q_pos0 + tq;
 
     // Q fragments (B operand): 8 consecutive features per lane and k-step
     bf16x8 qf[DHP / 16];
     {
-        const bf16_t* qrow = p.q + size_t(tq) * p.ldq + size_t(h) * p.dh;
+        const bf16_t* qrow = p.q + size_t(min(tq, p.T - 1)) * p.ldq + size_t(h) * p.dh;
 #pragma unroll
         for (int kk = 0; kk < DHP / 16; ++kk) {
             const int e = 16 * kk + 8 * g2;
@@ -57,33 +70,32 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs p, float scale_log2)
     for (int dt = 0; dt < DHP / 32; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[dt][r] = 0.0f;
-    float m_run = -INFINITY, l_run = 0.0f;
+    float m_run = -INFINITY, l_run = 0.0f;             // running maximum (raw score units) and sum
 
     const bf16_t* kbase = p.k + size_t(kvh) * p.k_head_stride;
     const bf16_t* vbase = p.vt + size_t(kvh) * p.v_head_stride;
-    int kv_end = p.S;
-    if (p.causal) {
-        const int last_q = p.q_pos0 + min(q0 + BQ, p.T);   // one past the last query position of the block
-        kv_end = min(p.S, last_q);
-    }
+    int kv_end = p.S;                                  // block-uniform: keys any query of the block may see
+    if (p.causal) kv_end = min(p.S, p.q_pos0 + min(q0 + QB, p.T));
+    const int wave_last = p.q_pos0 + min(wq0 + 31, p.T - 1);   // last query position of this wavefront
+    const int nt = (kv_end + BKV - 1) / BKV;
 
-    for (int j0 = 0; j0 < kv_end; j0 += BKV) {
-        __syncthreads();
-        // K tile: 64 positions x DHP features
-        for (int c = tid; c < BKV * (DHP / 8); c += 256) {
-            const int row = c / (DHP / 8), kc = (c % (DHP / 8)) * 8;
+    u32x4 rk[NKC], rv[NVC];
+    auto fetch = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < NKC; ++i) {
+            const int c = tid + 256 * i, row = c / (DHP / 8), kc = (c % (DHP / 8)) * 8;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (j0 + row < p.S && kc < p.dh)
                 v = *reinterpret_cast<const u32x4*>(kbase + size_t(j0 + row) * p.ldk + kc);
-            *reinterpret_cast<u32x4*>(&sK[row * KLD + kc]) = v;
+            rk[i] = v;
         }
-        // V^T tile: DHP features x 64 positions; positions >= S are zeroed (stale memory must not reach the MFMA)
-        for (int c = tid; c < DHP * (BKV / 8); c += 256) {
-            const int e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) {
+            const int c = tid + 256 * i, e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (e < p.dh && j0 + jc < p.S) {
                 v = *reinterpret_cast<const u32x4*>(vbase + size_t(e) * p.ldv + j0 + jc);
-                const int nvalid = p.S - (j0 + jc);          // > 0
+                const int nvalid = p.S - (j0 + jc);    // > 0; positions >= S hold stale memory: zero them
                 if (nvalid < 8) {
 #pragma unroll
                     for (int w = 0; w < 4; ++w) {
@@ -92,72 +104,105 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs p, float scale_log2)
                     }
                 }
             }
-            *reinterpret_cast<u32x4*>(&sV[e * VLD + jc]) = v;
+            rv[i] = v;
         }
-        __syncthreads();
-
-        // S^T tile: 64 keys x 32 queries per wavefront
-        f32x16 accS[2];
+    };
+    auto stash = [&](int s) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r) accS[i][r] = 0.0f;
-#pragma unroll
-            for (int kk = 0; kk < DHP / 16; ++kk) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sK[(32 * i + lq) * KLD + 16 * kk + 8 * g2]);
-                accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], accS[i], 0, 0, 0);
-            }
+        for (int i = 0; i < NKC; ++i) {
+            const int c = tid + 256 * i, row = c / (DHP / 8), kc = (c % (DHP / 8)) * 8;
+            *reinterpret_cast<u32x4*>(&sK[s][row * KLD + kc]) = rk[i];
         }
+#pragma unroll
+        for (int i = 0; i < NVC; ++i) {
+            const int c = tid + 256 * i, e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
+            *reinterpret_cast<u32x4*>(&sV[s][e * VLD + jc]) = rv[i];
+        }
+    };
 
-        // mask, online softmax (base-2 exponent; scale_log2 = log2(e) / sqrt(dh))
-        float mx = -INFINITY;
+    if (nt > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    for (int t = 0; t < nt; ++t) {
+        const int j0 = t * BKV, s = t & 1;
+        if (t + 1 < nt) fetch(j0 + BKV);
+        // a wavefront whose queries all lie before this tile has nothing to add (causal)
+        const bool active = !p.causal || j0 <= wave_last;
+        if (active) {
+            // S^T tile: 64 keys x 32 queries
+            f32x16 accS[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < 2; ++i) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int kv = j0 + 32 * i + 8 * (r >> 2) + 4 * g2 + (r & 3);
-                const bool ok = kv < p.S && (!p.causal || kv <= qpos);
-                const float s = ok ? accS[i][r] * scale_log2 : -INFINITY;
-                accS[i][r] = s;
-                mx = fmaxf(mx, s);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-        const float alpha = exp2f(m_run - m_use);
-        m_run = m_new;
-        float psum = 0.0f;
-        bf16x8 pf[2][2];
+                for (int r = 0; r < 16; ++r) accS[i][r] = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const float pv = exp2f(accS[i][8 * t + j] - m_use);
-                    psum += pv;
-                    pf[i][t][j] = (__bf16)pv;
+                for (int kk = 0; kk < DHP / 16; ++kk) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + lq) * KLD + 16 * kk + 8 * g2]);
+                    accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], accS[i], 0, 0, 0);
                 }
-        l_run = l_run * alpha + psum;
+            }
+            // masking only where it can bite: the diagonal tiles of a causal pass and the ragged last tile
+            const bool need_mask = (j0 + BKV > p.S) || (p.causal && j0 + BKV - 1 > p.q_pos0 + wq0);
+            if (need_mask) {
 #pragma unroll
-        for (int dt = 0; dt < DHP / 32; ++dt)
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) accO[dt][r] *= alpha;
-
-        // O^T += V^T * P^T
-#pragma unroll
-        for (int dt = 0; dt < DHP / 32; ++dt)
+                    for (int r = 0; r < 16; ++r) {
+                        const int kv = j0 + 32 * i + 8 * (r >> 2) + 4 * g2 + (r & 3);
+                        const bool ok = kv < p.S && (!p.causal || kv <= qpos);
+                        accS[i][r] = ok ? accS[i][r] : -INFINITY;
+                    }
+            }
+            float mx = -INFINITY;
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const bf16_t* vr = &sV[(32 * dt + lq) * VLD + 32 * i + 16 * t + 4 * g2];
-                    const u32x2 lo = *reinterpret_cast<const u32x2*>(vr);
-                    const u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 8);
-                    u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
-                    accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av), pf[i][t],
-                                                                       accO[dt], 0, 0, 0);
-                }
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accS[i][r]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
+            if (__any(m_new != m_run)) {
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2);
+                l_run *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < DHP / 32; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) accO[dt][r] *= alpha;
+                m_run = m_new;
+            }
+            const float ms = m_use * scale_log2;
+            float psum = 0.0f;
+            bf16x8 pf[2][2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        const float pv = __builtin_amdgcn_exp2f(fmaf(accS[i][8 * t2 + j], scale_log2, -ms));
+                        psum += pv;
+                        pf[i][t2][j] = (__bf16)pv;
+                    }
+            l_run += psum;
+            // O^T += V^T * P^T
+#pragma unroll
+            for (int dt = 0; dt < DHP / 32; ++dt)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2) {
+                        const bf16_t* vr = &sV[s][(32 * dt + lq) * VLD + 32 * i + 16 * t2 + 4 * g2];
+                        const u32x2 lo = *reinterpret_cast<const u32x2*>(vr);
+                        const u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 8);
+                        u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
+                        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av),
+                                                                           pf[i][t2], accO[dt], 0, 0, 0);
+                    }
+        }
+        if (t + 1 < nt) stash(s ^ 1);
+        __syncthreads();
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
@@ -178,15 +223,26 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs p, float scale_log2)
         }
 }
 
+template <int DHP>
+void launch_attn(const AttnArgs& a, float scale_log2, hipStream_t st) {
+    const int group = a.Hq / a.Hkv;
+    if (group % 4 == 0) {
+        dim3 grid((a.T + 31) / 32, a.Hq / 4), block(256);
+        hipLaunchKernelGGL((attn_kernel<DHP, true>), grid, block, 0, st, a, scale_log2);
+    } else {
+        dim3 grid((a.T + 127) / 128, a.Hq), block(256);
+        hipLaunchKernelGGL((attn_kernel<DHP, false>), grid, block, 0, st, a, scale_log2);
+    }
+}
+
 }  // namespace
 
 void attention(const AttnArgs& a, hipStream_t st) {
     if (a.T <= 0 || a.S <= 0) return;
-    dim3 grid((a.T + BQ - 1) / BQ, a.Hq), block(256);
     const float scale_log2 = 1.4426950408889634f / sqrtf(float(a.dh));
-    if (a.dh <= 64) hipLaunchKernelGGL(attn_kernel<64>, grid, block, 0, st, a, scale_log2);
-    else if (a.dh <= 96) hipLaunchKernelGGL(attn_kernel<96>, grid, block, 0, st, a, scale_log2);
-    else hipLaunchKernelGGL(attn_kernel<128>, grid, block, 0, st, a, scale_log2);
+    if (a.dh <= 64) launch_attn<64>(a, scale_log2, st);
+    else if (a.dh <= 96) launch_attn<96>(a, scale_log2, st);
+    else launch_attn<128>(a, scale_log2, st);
 }
 
 }  // namespace dlk

@@ -5,10 +5,23 @@
 // global -> registers -> LDS -> MFMA without any transposition.  Weights are stored [N,K]
 // by the packer for exactly this reason.
 //
-// Tiling: 256 threads = 4 wavefronts of 64 lanes in a 2x2 grid; block tile 128x128, K step 64;
-// each wavefront owns 64x64 = 2x2 MFMA tiles of 32x32 (4 x 16 fp32 accumulators per lane).
-// The next K tile is fetched into registers while the current one is multiplied out of LDS.
+// Two kernels share the epilogues:
+//
+//  * gemm_fast<BM,BN,EPI> — the production path for K % 128 == 0.  One workgroup per CU (256 threads =
+//    4 wavefronts in a 2x2 grid, each owning a (BM/2)x(BN/2) tile, i.e. up to 4x4 MFMA tiles = 256 fp32
+//    accumulators per lane).  K step 64.  Tiles go global -> LDS directly (global_load_lds_dwordx4, no
+//    staging registers) into two LDS stages that are separate arrays, so the compiler can tell the
+//    in-flight stage from the one being read and waits for the copies only at the barrier.  LDS rows
+//    are 128 bytes, unpadded (a wavefront's copy fills 1 KB contiguously); the 16-byte chunk index is
+//    XOR-swizzled with (row/2)%8 on both sides, which keeps the 64-lane b128 fragment reads conflict-free.
+//    Per K step four phases of 16 MFMAs; fragment reads, copies and MFMAs of different phases are
+//    interleaved through sched_group_barrier, and the stage barrier sits before the last MFMA phase so
+//    that the first fragment reads of the next stage hide behind it.
+//  * gemm_generic<EPI> — any shape (K % 8 == 0): 128x128 tile, 64x64 per wavefront, register-staged.
+//
 // Accumulator layout of a 32x32 tile: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace dlk {
@@ -34,7 +47,7 @@ __device__ __forceinline__ bf16_t f_to_bf16(float f) {
 }
 
 template <int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs p) {
+__global__ __launch_bounds__(256) void gemm_generic(GemmArgs p) {
     __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LDS_LD];
     __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LDS_LD];
 
@@ -142,18 +155,275 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs p) {
     }
 }
 
+
+// epilogue shared by both kernels: accumulator tile (i, j) of a wavefront whose tile starts at (mw, nw)
+template <int EPI, int TM, int TN>
+__device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM][TN], int mw, int nw, int lane) {
+    const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+    if (EPI == EPI_SWIGLU_BF16) {
+        // even tile columns hold gate rows, the next odd one the matching up rows (packed in groups of 32)
+        bf16_t* out = static_cast<bf16_t*>(p.out);
+#pragma unroll
+        for (int j = 0; j < TN; j += 2) {
+            const int pn = nw + 32 * j + col_in;            // packed column of the gate value
+            if (pn + 32 >= p.N) continue;
+            const int f = (nw + 32 * j) / 2 + col_in;        // feature index
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
+                    if (m < p.M) out[size_t(m) * p.ldo + f] = f_to_bf16(silu_f(acc[i][j][r]) * acc[i][j + 1][r]);
+                }
+        }
+        return;
+    }
+    if (EPI == EPI_RESID_F32) {
+        // out may be the same buffer as resid: every element is read and then written by the same lane only,
+        // so the pointers are declared non-aliasing to let all loads of a tile be issued ahead of its stores
+        const float* __restrict__ resid = p.resid;
+        float* __restrict__ out = static_cast<float*>(p.out);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int n = nw + 32 * j + col_in;
+            if (n >= p.N) continue;
+            const float bias = p.bias ? bf16_to_f(p.bias[n]) : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                float rv[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
+                    rv[r] = m < p.M ? resid[size_t(m) * p.ldr + n] : 0.0f;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
+                    if (m < p.M) out[size_t(m) * p.ldo + n] = rv[r] + acc[i][j][r] + bias;
+                }
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = nw + 32 * j + col_in;
+        if (n >= p.N) continue;
+        const float bias = p.bias ? bf16_to_f(p.bias[n]) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
+                if (m >= p.M) continue;
+                const float v = acc[i][j][r] + bias;
+                if (EPI == EPI_BF16) {
+                    static_cast<bf16_t*>(p.out)[size_t(m) * p.ldo + n] = f_to_bf16(v);
+                } else if (EPI == EPI_GELU_BF16) {
+                    static_cast<bf16_t*>(p.out)[size_t(m) * p.ldo + n] = f_to_bf16(gelu_tanh_f(v));
+                } else {
+                    static_cast<float*>(p.out)[size_t(m) * p.ldo + n] = v;
+                }
+            }
+    }
+}
+
+// blockIdx -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2): XCD x gets a
+// contiguous range of the tile order, and inside it 8 row-tiles x consecutive column-tiles run together,
+// so the tiles resident on one XCD share their A and B slabs in that XCD's L2.
+__device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int* tm, int* tn) {
+    const int total = tiles_m * tiles_n;
+    const int xcd = bid % 8, idx = bid / 8;
+    const int per = (total + 7) / 8;
+    const int lin = xcd * per + idx;
+    if (idx >= per || lin >= total) return false;
+    constexpr int GM = 8;
+    const int grp = lin / (GM * tiles_n), r = lin % (GM * tiles_n);
+    const int gm = min(GM, tiles_m - grp * GM);
+    *tm = grp * GM + r % gm;
+    *tn = r / gm;
+    return true;
+}
+
+#define DL_GLL16(g, l)                                                                                   \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
+                                     (__attribute__((address_space(3))) void*)(l), 16, 0, 0)
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
+    constexpr int BK = 64;
+    constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;
+    constexpr int JA = BM / 32, JB = BN / 32;            // 1 KB copy blocks per wavefront and tile
+    __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * BK];
+    __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * BK];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    int tm, tn;
+    if (!tile_of(blockIdx.x, tiles_m, tiles_n, &tm, &tn)) return;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // copy sources: block b = wave + 4*j of a tile holds rows 8b..8b+7; lane L lands at row 8b + L/8,
+    // physical chunk L%8, and therefore fetches logical chunk (L%8) ^ swizzle(row).  Rows past the
+    // matrix edge are clamped: they produce values that the epilogue never stores.
+    uint32_t offA[JA], offB[JB];
+#pragma unroll
+    for (int j = 0; j < JA; ++j) {
+        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
+        offA[j] = uint32_t((size_t(min(m0 + row, p.M - 1)) * p.lda + lc * 8) * 2);
+    }
+#pragma unroll
+    for (int j = 0; j < JB; ++j) {
+        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
+        offB[j] = uint32_t((size_t(min(n0 + row, p.N - 1)) * p.ldb + lc * 8) * 2);
+    }
+    const char* gA = reinterpret_cast<const char*>(p.A);
+    const char* gB = reinterpret_cast<const char*>(p.B);
+    // fragment read offsets (elements) inside a stage, one per 16-wide k step
+    const int lr = lane & 31, g2 = lane >> 5;
+    int rdA[4], rdB[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        const int pc = (2 * kk + g2) ^ ((lr >> 1) & 7);
+        rdA[kk] = ((BM / 2) * wm + lr) * BK + pc * 8;
+        rdB[kk] = BM * BK + ((BN / 2) * wn + lr) * BK + pc * 8;
+    }
+
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+    auto copyA = [&](bf16_t* S, int kt) {
+#pragma unroll
+        for (int j = 0; j < JA; ++j) DL_GLL16(gA + size_t(kt) * (BK * 2) + offA[j], S + (wave + 4 * j) * 512);
+    };
+    auto copyB = [&](bf16_t* S, int kt) {
+#pragma unroll
+        for (int j = 0; j < JB; ++j) DL_GLL16(gB + size_t(kt) * (BK * 2) + offB[j], S + BM * BK + (wave + 4 * j) * 512);
+    };
+    auto ldfrag = [&](bf16x8* a, bf16x8* b, const bf16_t* S, int kk) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[i] = *reinterpret_cast<const bf16x8*>(S + rdA[kk] + 32 * i * BK);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(S + rdB[kk] + 32 * j * BK);
+    };
+    auto mma = [&](const bf16x8* a, const bf16x8* b) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    };
+    // ask the scheduler for: 2 MFMA, 1 LDS read, (1 global->LDS copy) repeated over the phase
+    auto interleave = [&](bool with_copy) {
+#pragma unroll
+        for (int g = 0; g < TM * TN / 2; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            if (with_copy) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    const int nk = p.K / BK;                             // host guarantees K % 128 == 0: nk is even, >= 2
+    copyA(S0, 0);
+    copyB(S0, 0);
+    __syncthreads();
+    ldfrag(a0, b0, S0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    auto ktile = [&](const bf16_t* cur, bf16_t* nxt, int kt, auto more_c) {
+        constexpr bool MORE = decltype(more_c)::value;
+        ldfrag(a1, b1, cur, 1);
+        if (MORE) copyA(nxt, kt + 1);
+        mma(a0, b0);
+        interleave(MORE);
+        ldfrag(a0, b0, cur, 2);
+        if (MORE) copyB(nxt, kt + 1);
+        mma(a1, b1);
+        interleave(MORE);
+        ldfrag(a1, b1, cur, 3);
+        mma(a0, b0);
+        interleave(false);
+        __syncthreads();      // copies into nxt have landed; every wavefront has finished reading cur
+        if (MORE) ldfrag(a0, b0, nxt, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mma(a1, b1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int kt = 0;
+    for (; kt + 2 < nk; kt += 2) {
+        ktile(S0, S1, kt, std::true_type{});
+        ktile(S1, S0, kt + 1, std::true_type{});
+    }
+    ktile(S0, S1, kt, std::true_type{});
+    ktile(S1, S0, kt + 1, std::false_type{});
+
+    store_tiles<EPI, TM, TN>(p, acc, m0 + (BM / 2) * wm, n0 + (BN / 2) * wn, lane);
+}
+
+template <int BM, int BN, int EPI>
+void launch_fast(const GemmArgs& a, hipStream_t st) {
+    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    const int grid = (tiles + 7) / 8 * 8;
+    hipLaunchKernelGGL((gemm_fast<BM, BN, EPI>), dim3(grid), dim3(256), 0, st, a);
+}
+
+// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192.  Fewest rounds of 256 workgroups
+// weighted by tile area; the smaller tiles are a little less efficient per flop.
+int pick_tile(int M, int N, bool need_even_cols) {
+    const int bm[3] = {256, 192, 256}, bn[3] = {256, 256, 192};
+    const double eff[3] = {1.0, 0.93, 0.93};
+    int best = 0;
+    double best_cost = 1e300;
+    for (int c = 0; c < 3; ++c) {
+        if (need_even_cols && bn[c] != 256) continue;
+        const long tiles = long((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
+        const double rounds = tiles >= 768 ? double(tiles) / 256.0 : double((tiles + 255) / 256);
+        const double cost = rounds * bm[c] * bn[c] / eff[c];
+        if (cost < best_cost) { best_cost = cost; best = c; }
+    }
+    return best;
+}
+
+template <int EPI>
+void dispatch_fast(const GemmArgs& a, hipStream_t st) {
+    const int t = pick_tile(a.M, a.N, EPI == EPI_SWIGLU_BF16);
+    if (t == 0) launch_fast<256, 256, EPI>(a, st);
+    else if (t == 1) launch_fast<192, 256, EPI>(a, st);
+    else if (EPI != EPI_SWIGLU_BF16) launch_fast<256, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+}
+
 }  // namespace
 
 void gemm(const GemmArgs& a, hipStream_t st) {
     if (a.M <= 0 || a.N <= 0) return;
+    // fast path: K in whole pairs of 64-wide steps, 16-byte aligned rows, enough rows to fill a tile
+    const bool fast = a.K >= 128 && a.K % 128 == 0 && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.M >= 96 && a.N >= 128 &&
+                      a.epi != EPI_F32 &&
+                      size_t(a.M) * a.lda * 2 < (1ull << 32) && size_t(a.N) * a.ldb * 2 < (1ull << 32);
+    if (fast) {
+        switch (a.epi) {
+            case EPI_BF16: dispatch_fast<EPI_BF16>(a, st); return;
+            case EPI_RESID_F32: dispatch_fast<EPI_RESID_F32>(a, st); return;
+            case EPI_SWIGLU_BF16: dispatch_fast<EPI_SWIGLU_BF16>(a, st); return;
+            case EPI_GELU_BF16: dispatch_fast<EPI_GELU_BF16>(a, st); return;
+            default: break;
+        }
+    }
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
     dim3 grid(tiles), block(256);
     switch (a.epi) {
-        case EPI_BF16: hipLaunchKernelGGL(gemm_kernel<EPI_BF16>, grid, block, 0, st, a); break;
-        case EPI_RESID_F32: hipLaunchKernelGGL(gemm_kernel<EPI_RESID_F32>, grid, block, 0, st, a); break;
-        case EPI_SWIGLU_BF16: hipLaunchKernelGGL(gemm_kernel<EPI_SWIGLU_BF16>, grid, block, 0, st, a); break;
-        case EPI_GELU_BF16: hipLaunchKernelGGL(gemm_kernel<EPI_GELU_BF16>, grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL(gemm_kernel<EPI_F32>, grid, block, 0, st, a); break;
+        case EPI_BF16: hipLaunchKernelGGL(gemm_generic<EPI_BF16>, grid, block, 0, st, a); break;
+        case EPI_RESID_F32: hipLaunchKernelGGL(gemm_generic<EPI_RESID_F32>, grid, block, 0, st, a); break;
+        case EPI_SWIGLU_BF16: hipLaunchKernelGGL(gemm_generic<EPI_SWIGLU_BF16>, grid, block, 0, st, a); break;
+        case EPI_GELU_BF16: hipLaunchKernelGGL(gemm_generic<EPI_GELU_BF16>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(gemm_generic<EPI_F32>, grid, block, 0, st, a); break;
     }
 }
 
