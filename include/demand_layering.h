@@ -167,13 +167,16 @@ int32_t dl_sync(dl_ctx* ctx);
 
 typedef struct {
     double c_dma_ms;      /* un-overlapped host-to-device copy time of the layer */
-    double c_exe_ms;      /* un-overlapped execution time of the layer */
+    double c_exe_ms;      /* un-overlapped execution time of the layer, run right after its copy (the GPU was idle) */
+    double c_exe_hot_ms;  /* execution time of the layer inside an uninterrupted run of all layers (no copies, no
+                             idle gaps): what a layer costs when compute is continuous, e.g. between resident layers */
     uint64_t bytes;       /* bytes one copy moves */
 } dl_layer_profile;
 
 /* Sec. II-C / Table III: runs the module in sequential mode `iters` times at (n_tokens, pos0),
  * discards the first iteration, writes per-layer means.  Every layer is copied (into a slot)
- * and timed regardless of residency.  out: host array [n_layers].  Restores the KV-cache
+ * and timed regardless of residency.  Then all layers are run back to back without copies (on
+ * whatever parameters the slot holds: same shapes, same cost) to time them under continuous load.  out: host array [n_layers].  Restores the KV-cache
  * contents it touches only in the sense that positions pos0.. are rewritten by the next real pass. */
 int32_t dl_profile(dl_ctx* ctx, int32_t module, int32_t n_tokens, int32_t pos0, const void* x_dev,
                    const void* ctx_dev, int32_t n_ctx, int32_t iters, dl_layer_profile* out);
@@ -257,12 +260,15 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * The n layer invocations of all passes are flattened: c_dma_ms[j], c_exe_ms[j] = times of
  * invocation j; streamed[j] != 0 if its parameters are copied; pass_start[j] != 0 marks the first
  * layer of a pass; module_id[j] (NULL = all the same) tells passes over different stacks apart.
+ * c_exe_idle_ms (NULL = same as c_exe_ms): time of invocation j when the compute queue sat idle
+ * waiting for its copy right before it (a GPU that idled runs the next kernels slower than one
+ * kept busy; dl_profile measures both).
  * mode, wrap_prefetch: as dl_set_mode.  overhead_ms is added to every execution (fixed
  * host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
  * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
-int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_t* streamed,
-                    const uint8_t* pass_start, const int32_t* module_id, int32_t n, int32_t mode,
-                    int32_t wrap_prefetch, double overhead_ms,
+int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
+                    const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+                    int32_t mode, int32_t wrap_prefetch, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms);
 
 /* Budgeted choice of resident layers over several modules from one profiling run (Sec. IV-D).

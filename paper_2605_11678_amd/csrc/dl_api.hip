@@ -873,7 +873,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     c->tracing = false;
     c->book = dl::SlotBook();
     const int32_t Ln = M->d.n_layers;
-    std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0);
+    std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0), hot(size_t(Ln), 0.0);
     for (int32_t it = 0; it < iters && rc == DL_OK; ++it) {
         rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
         if (rc) break;
@@ -887,6 +887,28 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
             dma[size_t(i)] += double(recs[size_t(i)].dma_end_ms) - recs[size_t(i)].dma_start_ms;
             exe[size_t(i)] += double(recs[size_t(i)].exe_end_ms) - recs[size_t(i)].exe_start_ms;
         }
+    }
+    // all layers back to back, no copies: execution time under continuous load (second of two runs)
+    for (int32_t rep = 0; rep < 2 && rc == DL_OK; ++rep) {
+        for (int32_t i = 0; i < Ln && rc == DL_OK; ++i) {
+            TimedOp t{nullptr, nullptr, module, i, -1, -1};
+            rc = timing_event(c, &t.e0);
+            if (rc == DL_OK) rc = timing_event(c, &t.e1);
+            if (rc) break;
+            if (hipEventRecord(t.e0, c->s_compute) != hipSuccess) { rc = fail(c, DL_ERR_DEVICE, "event record failed"); break; }
+            run_layer(c, *M, i, c->base + c->slot_off[0], i == 0 ? static_cast<const float*>(x) : scratch, scratch, T, pos0,
+                      static_cast<const float*>(ctx), n_ctx);
+            if (hipEventRecord(t.e1, c->s_compute) != hipSuccess) { rc = fail(c, DL_ERR_DEVICE, "event record failed"); break; }
+            c->execs.push_back(t);
+        }
+        if (rc) break;
+        dl_run_stats st;
+        std::vector<dl_layer_record> recs;
+        recs.resize(size_t(Ln));
+        rc = dl_collect_stats(c, &st, recs.data(), Ln);
+        if (rc == DL_OK && rep == 1)
+            for (int32_t i = 0; i < Ln; ++i)
+                hot[size_t(i)] = double(recs[size_t(i)].exe_end_ms) - recs[size_t(i)].exe_start_ms;
     }
     c->mode = mode0;
     c->wrap = wrap0;
@@ -902,6 +924,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     for (int32_t i = 0; i < Ln; ++i) {
         out[i].c_dma_ms = dma[size_t(i)] / (iters - 1);
         out[i].c_exe_ms = exe[size_t(i)] / (iters - 1);
+        out[i].c_exe_hot_ms = hot[size_t(i)];
         out[i].bytes = M->L.bytes;
     }
     return DL_OK;

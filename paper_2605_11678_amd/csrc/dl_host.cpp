@@ -408,8 +408,9 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
     return DL_OK;
 }
 
-int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_t* streamed, const uint8_t* pass_start,
-                    const int32_t* module_id, int32_t n, int32_t mode, int32_t wrap_prefetch, double overhead_ms,
+int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
+                    const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+                    int32_t mode, int32_t wrap_prefetch, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms) {
     if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
     if (mode != DL_MODE_PIPELINED && mode != DL_MODE_SEQUENTIAL) return DL_ERR_INVALID_ARG;
@@ -428,6 +429,7 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_
     double ev_dma[2] = {0, 0}, ev_comp[2] = {0, 0}, ev_pass = 0;
     double copy_start[2] = {0, 0}, copy_dur[2] = {0, 0};
     double exposed = 0, dma_sum = 0;
+    bool idled = false;                          // the compute queue waited for the copy of the next layer
     std::vector<dl_trace_op> ops;
     std::vector<uint8_t> resident;
     for (size_t p = 0; p < passes.size(); ++p) {
@@ -447,6 +449,7 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_
                         // time the compute queue idles while the copy it needs is in flight
                         exposed += std::max(0.0, e - std::max(t[0], copy_start[o.slot]));
                         dma_sum += copy_dur[o.slot];
+                        idled = e > t[0];
                     }
                     t[q] = std::max(t[q], e);
                     break;
@@ -470,7 +473,8 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const uint8_
                     break;
                 }
                 case DL_OP_EXEC:
-                    t[q] += c_exe_ms[j] + overhead_ms;
+                    t[q] += ((idled && c_exe_idle_ms) ? c_exe_idle_ms[j] : c_exe_ms[j]) + overhead_ms;
+                    idled = false;
                     break;
                 default: break;
             }
