@@ -33,6 +33,161 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
+    """64 greedy steps at batch 1 after the T-token prefill.  Caps: the arena itself (16e9 B) and 12e9 B
+    (emulated by parking a ballast block in the arena).  Policies: nothing resident; the largest count
+    that fits placed by Eq. 8; the same count as the first k consecutive layers."""
+    import numpy as np
+    d = c.d_model
+    tp, tv = eng.alloc_f32(64)
+    # per-phase profile of the single-token pass (Table III's "VLM decode" row)
+    ctx.set_residency(mid, [])
+    prof = ctx.profile(mid, L, 1, T, xp, iters=3)
+    c_dma = [p["c_dma_ms"] for p in prof]
+    c_exe = [p["c_exe_ms"] for p in prof]
+    c_hot = [p["c_exe_hot_ms"] for p in prof]
+    res = {"profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_exe_ms": round(float(np.mean(c_exe)), 4),
+                       "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
+                       "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 1),
+                       "consecutive_limit": B.consecutive_limit(float(np.mean(c_dma)), float(np.mean(c_exe)))},
+           "runs": []}
+
+    # the greedy head (final norm, 4096x32768 GEMV, argmax, embedding row) runs once per token, always resident
+    ctx.forward(mid, xp, yp, T, 0)
+    ctx.sync()
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(50):
+        ctx.greedy_step(mid, yp, tp, xp + 4 * d)
+    ctx.sync()
+    head_ms = (time.perf_counter() - t) * 1e3 / 50
+    res["head_ms"] = round(head_ms, 4)
+
+    def run(resident, steps, wrap):
+        ctx.set_residency(mid, resident)
+        ctx.set_mode(B.DL_MODE_PIPELINED, wrap)
+        ctx.forward(mid, xp, yp, T, 0)                       # refresh the KV cache (untimed)
+        h_ptr = yp + 4 * (T - 1) * d
+        ctx.greedy_step(mid, h_ptr, tp, xp + 4 * d)          # next input lives behind row 0 so that xp's prefill rows stay intact
+        ctx.sync()
+        ctx.set_timing(True)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for s in range(steps):
+            ctx.forward(mid, xp + 4 * d, yp, 1, T + s)
+            ctx.greedy_step(mid, yp, tp + 4 * ((s + 1) % 64), xp + 4 * d)
+        ctx.sync()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t) * 1e3 / steps
+        st = ctx.collect_stats()
+        ctx.set_timing(False)
+        return ms, st
+
+    def predict(resident, steps, wrap):
+        rs = set(resident)
+        streamed = [i not in rs for i in range(L)] * steps
+        starts = [i == 0 for i in range(L)] * steps
+        return B.timeline(c_dma * steps, c_hot * steps, streamed, starts, wrap_prefetch=wrap,
+                          c_exe_idle_ms=c_exe * steps)["total"] / steps + head_ms
+
+    def fit_count():
+        for k in range(L, -1, -1):
+            try:
+                ctx.set_residency(mid, B.place_interleaved(L, k))
+                return k
+            except B.DLError as e:
+                if e.code != B.DL_ERR_BUDGET_EXCEEDED:
+                    raise
+        return 0
+
+    for cap_name, ballast_bytes in (("16e9", 0), ("12e9", 4_000_000_000)):
+        ctx.set_residency(mid, [])
+        ballast = ctx.arena_alloc(ballast_bytes) if ballast_bytes else None
+        try:
+            kfit = fit_count()
+            policies = [("none", []), ("interleaved_eq8", B.place_interleaved(L, kfit))]
+            if 0 < kfit < L:
+                policies.append(("first_k_consecutive", list(range(kfit))))
+            for name, resident in policies:
+                streamed_n = L - len(resident)
+                steps = 64 if streamed_n * float(np.mean(c_dma)) < 40 else 6
+                for wrap in ((0, 1) if streamed_n else (0,)):
+                    ms, st = run(resident, steps, wrap)
+                    pred = predict(resident, steps, wrap)
+                    row = {"cap": cap_name, "policy": name, "k": len(resident), "wrap_prefetch": wrap, "steps": steps,
+                           "ms_per_token": round(ms, 3), "predicted_ms_per_token": round(pred, 3),
+                           "pred_err_pct": round((pred - ms) / ms * 100, 2), "hidden_frac": round(st["hidden_frac"], 4),
+                           "h2d_gbps": round(st["h2d_gbps"], 2),
+                           "arena_gb": round(ctx.arena_stats()["used"] / 1e9 - ballast_bytes / 1e9, 3)}
+                    if not streamed_n:
+                        row["weight_stream_gbps"] = round(L * packed / (ms * 1e-3) / 1e9, 1)   # HBM-bound resident pass
+                    res["runs"].append(row)
+                    log("decode cap %s %-20s k=%2d wrap=%d: %.3f ms/token (predicted %.3f, %.2f%%) hidden %.3f" %
+                        (cap_name, name, len(resident), wrap, ms, pred, row["pred_err_pct"], st["hidden_frac"]))
+        finally:
+            ctx.set_residency(mid, [])
+            if ballast:
+                ctx.arena_free(ballast)
+    return res
+
+
+def vit_leg(B, CFG, Engine, torch, log):
+    """configs[1]: 27-layer d=1152 encoder, 4096 tokens, bidirectional; two slots; residency sweep."""
+    import numpy as np
+    c = CFG.vit_encoder()
+    T, L = 4096, c.n_layers
+    eng = Engine(int(2e9), device=0)
+    mid = eng.add_module(c, max_tokens=T)
+    ctx = eng.ctx
+    packed, params = ctx.module_layer_bytes(mid)
+    x = CFG.make_tokens(T, c.d_model, seed=7)
+    xp, xv = eng.alloc_f32(T * c.d_model)
+    yp, yv = eng.alloc_f32(T * c.d_model)
+    eng.upload(xv, x)
+    tried = eng.pick_copy_stream(mid, T, xp, yp)
+    log("vit copy-stream candidates (ms per fully streamed pass): " + ", ".join("%.2f" % t for _, t in tried))
+    prof = ctx.profile(mid, L, T, 0, xp, iters=4)
+    c_dma = [p["c_dma_ms"] for p in prof]
+    c_exe = [p["c_exe_ms"] for p in prof]
+    c_hot = [p["c_exe_hot_ms"] for p in prof]
+    rows = []
+    for k in (0, 7, 14, 20, 24, 27):
+        res = B.place_interleaved(L, k)
+        ctx.set_residency(mid, res)
+        ctx.forward(mid, xp, yp, T, 0)
+        ctx.sync()
+        samples = []
+        for _ in range(9):                                   # median of single passes: the host link is shared
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            ctx.forward(mid, xp, yp, T, 0)
+            ctx.sync()
+            samples.append((time.perf_counter() - t) * 1e3)
+        ms = float(np.median(samples))
+        ctx.set_timing(True)
+        ctx.forward(mid, xp, yp, T, 0)
+        st = ctx.collect_stats()
+        ctx.set_timing(False)
+        rs = set(res)
+        pred = B.timeline(c_dma, c_hot, [i not in rs for i in range(L)], [i == 0 for i in range(L)],
+                          c_exe_idle_ms=c_exe)["total"]
+        rows.append({"k": k, "measured_ms": round(ms, 3), "predicted_ms": round(pred, 3),
+                     "pred_err_pct": round((pred - ms) / ms * 100, 2), "hidden_frac": round(st["hidden_frac"], 4),
+                     "h2d_gbps": round(st["h2d_gbps"], 2)})
+        log("vit k=%2d measured %.3f ms predicted %.3f ms (%.2f%%) hidden %.3f H2D %.1f GB/s" %
+            (k, ms, pred, rows[-1]["pred_err_pct"], st["hidden_frac"], st["h2d_gbps"]))
+    flops_layer = 2.0 * T * c.d_model * 3 * c.d_model + 2.0 * T * c.d_model * c.d_model + 4.0 * T * c.d_model * c.d_ff \
+        + 4.0 * c.d_head * c.n_q_heads * float(T) * T
+    out = {"workload": "configs[1]: 27-layer d=1152 encoder (16x72 heads, GELU MLP 4304, LayerNorm, biases), T=4096",
+           "layer_bytes": packed,
+           "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_exe_ms": round(float(np.mean(c_exe)), 4),
+                       "c_exe_hot_ms": round(float(np.mean(c_hot)), 4), "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 2)},
+           "sweep": rows, "layer_flop": flops_layer,
+           "resident_tflops": round(flops_layer * L / (rows[-1]["measured_ms"] * 1e-3) / 1e12, 1)}
+    eng.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -43,6 +198,7 @@ def main():
     ap.add_argument("--cap", type=float, default=16e9)
     ap.add_argument("--sweep", type=str, default="0,9,18,27,33,35,36")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the decode and ViT legs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build is single-GPU by design (one process, one MI355X, no collectives); "
@@ -58,8 +214,7 @@ def main():
         log("bench.py: no GPU visible")
         sys.exit(3)
 
-    c = CFG.decoder_8b(n_layers=args.layers)
-    c.vocab = 0
+    c = CFG.decoder_8b(n_layers=args.layers)            # with the 4096x32768 head and embedding (decode leg)
     T, L = args.tokens, c.n_layers
     cap = int(args.cap)
     t0 = time.time()
@@ -73,6 +228,8 @@ def main():
     eng.upload(xv, x)
     ctx = eng.ctx
     ctx.set_mode(B.DL_MODE_PIPELINED, 0)
+    tried = eng.pick_copy_stream(mid, T, xp, yp, passes=2)
+    log("copy-stream candidates (ms per fully streamed pass): " + ", ".join("%.2f" % t for _, t in tried))
 
     # ---- one profiling run in sequential mode (Table III procedure) ----
     prof = ctx.profile(mid, L, T, 0, xp, iters=3)
@@ -130,7 +287,7 @@ def main():
     g_n = sum(kt[k]["launches"] for k in gemm_kinds)
     a_ms, a_fl = kt["attn"]["total_ms"], kt["attn"]["flops"]
     achieved = g_fl / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
-    roofline = {"bound": "mfma", "kernel": "gemm_kernel (BF16 MFMA, all epilogues)", "achieved": round(achieved, 2),
+    roofline = {"bound": "mfma", "kernel": "gemm_fast (BF16 MFMA, all epilogues and tile shapes)", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": None, "launches": g_n, "avg_launch_ms": round(g_ms / max(g_n, 1), 4),
                 "flop_per_launch_avg": g_fl / max(g_n, 1)}
@@ -194,6 +351,15 @@ def main():
     except B.DLError as e:
         progress["error"] = str(e)
 
+
+    # ---- decode leg (configs[3]): same stack, KV cache from the 3072-token prefill, greedy steps ----
+    extras = {}
+    if not args.no_extras:
+        try:
+            extras["decode"] = decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log)
+        except B.DLError as e:
+            extras["decode"] = {"error": str(e)}
+
     # ---- CPU oracle on a bounded sample: one layer of the same stack at the same T ----
     cpu = None
     if not args.no_cpu_baseline:
@@ -237,9 +403,15 @@ def main():
         "sweep": sweep,
         "progression": progress,
         "max_pred_err_pct": max([abs(r["pred_err_pct"]) for r in sweep if "pred_err_pct" in r] or [None]),
+        "extras": extras,
     }
-    print(json.dumps(out), flush=True)
     eng.close()
+    if not args.no_extras:
+        try:
+            out["extras"]["vit"] = vit_leg(B, CFG, Engine, torch, log)
+        except B.DLError as e:
+            out["extras"]["vit"] = {"error": str(e)}
+    print(json.dumps(out), flush=True)
 
 
 if __name__ == "__main__":

@@ -193,7 +193,7 @@ using dlk::bf16_t;
 void linear(hipStream_t st, int T, const bf16_t* A, int lda, const bf16_t* B, int K, int N, const bf16_t* bias,
             int epi, void* out, int ldo, const float* resid, int ldr) {
     if (T == 1) {
-        dlk::GemvArgs g{A, B, K, bias, out, resid, N, K, epi};
+        dlk::GemvArgs g{A, B, K, bias, out, resid, N, K, epi, nullptr, nullptr, nullptr, 0, 0.0f};
         dlk::gemv(g, st);
     } else {
         dlk::GemmArgs g{A, lda, B, K, bias, out, ldo, resid, ldr, T, N, K, epi};
@@ -238,13 +238,25 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     };
     double fl, by;
 
+    // single-token passes: the normalisation is folded into the matrix-vector kernel that consumes it
+    const bool fuse_norm = (T == 1);
+    auto gemv_normed = [&](const float* xin, uint64_t g_off, uint64_t b_off, uint64_t w_off, uint64_t bias_off, int N_,
+                           int epi, void* dst) {
+        dlk::GemvArgs g{nullptr, P(w_off), dm, P(bias_off), dst, nullptr, N_, dm, epi, xin, P(g_off), P(b_off), d.norm,
+                        d.norm_eps};
+        dlk::gemv(g, st);
+    };
+
     // attention sub-block
-    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
-    dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
-    kend();
+    if (!fuse_norm) {
+        kbegin(DL_K_NORM, 0, Td * dm * 6.0);
+        dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
+        kend();
+    }
     lin_work(Td, L.n_qkv, dm, &fl, &by);
     kbegin(DL_K_GEMM_QKV, fl, by);
-    linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
+    if (fuse_norm) gemv_normed(in, L.norm1_g, L.norm1_b, L.w_qkv, L.b_qkv, L.n_qkv, dlk::EPI_BF16, qkv);
+    else linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
     kend();
     bf16_t* kc = nullptr;
     bf16_t* vt;
@@ -275,7 +287,13 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
         const double pairs = d.causal ? Td * pos0 + Td * (Td + 1.0) / 2.0 : Td * double(pos0 + T);
         kbegin(DL_K_ATTN, 4.0 * dh * Hq * pairs, 2.0 * (2.0 * Td * dq + 2.0 * double(pos0 + T) * dkv));
     }
-    dlk::attention(aa, st);
+    if (T == 1 && cache) {
+        dlk::DecodeAttnArgs da{qkv, kc, ldk, k_hs, vt, ldv, v_hs, attn, reinterpret_cast<float*>(ws + M.W.dec_part),
+                               pos0 + 1, Hq, Hkv, dh};
+        dlk::decode_attention(da, st);
+    } else {
+        dlk::attention(aa, st);
+    }
     kend();
     lin_work(Td, dm, dq, &fl, &by);
     kbegin(DL_K_GEMM_O, fl, by + 8.0 * Td * dm);
@@ -305,12 +323,17 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     }
 
     // feed-forward sub-block
-    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
-    dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
-    kend();
+    if (!fuse_norm) {
+        kbegin(DL_K_NORM, 0, Td * dm * 6.0);
+        dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
+        kend();
+    }
     lin_work(Td, L.n_up, dm, &fl, &by);
     kbegin(DL_K_GEMM_UP, fl, 2.0 * (Td * dm + double(L.n_up) * dm + Td * d.d_ff));
-    if (d.act == DL_ACT_SWIGLU)
+    if (fuse_norm)
+        gemv_normed(out, L.norm2_g, L.norm2_b, L.w_up, d.act == DL_ACT_SWIGLU ? PackLayout::kNone : L.b_up, L.n_up,
+                    d.act == DL_ACT_SWIGLU ? dlk::EPI_SWIGLU_BF16 : dlk::EPI_GELU_BF16, mid);
+    else if (d.act == DL_ACT_SWIGLU)
         linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, L.ffp, nullptr, 0);
     else
         linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, L.ffp, nullptr, 0);
@@ -725,7 +748,7 @@ static int32_t head_common(dl_ctx* c, Module* M, const void* h) {
                    M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr,
                    nbuf, false, 1, M->d.d_model, M->d.norm_eps, st);
     dlk::GemvArgs g{nbuf, reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_HEAD]), M->d.d_model, nullptr,
-                    logits, nullptr, M->d.vocab, M->d.d_model, dlk::EPI_F32};
+                    logits, nullptr, M->d.vocab, M->d.d_model, dlk::EPI_F32, nullptr, nullptr, nullptr, 0, 0.0f};
     dlk::gemv(g, st);
     dlk::argmax_f32(logits, M->d.vocab, tok, st);
     DL_HIP(c, hipGetLastError());
@@ -906,9 +929,16 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         std::vector<dl_layer_record> recs;
         recs.resize(size_t(Ln));
         rc = dl_collect_stats(c, &st, recs.data(), Ln);
-        if (rc == DL_OK && rep == 1)
-            for (int32_t i = 0; i < Ln; ++i)
-                hot[size_t(i)] = double(recs[size_t(i)].exe_end_ms) - recs[size_t(i)].exe_start_ms;
+        if (rc == DL_OK && rep == 1) {
+            // start-to-start spacing, so that launch gaps between layers are part of the figure
+            double gap = 0;
+            for (int32_t i = 0; i + 1 < Ln; ++i) {
+                hot[size_t(i)] = double(recs[size_t(i + 1)].exe_start_ms) - recs[size_t(i)].exe_start_ms;
+                gap += double(recs[size_t(i + 1)].exe_start_ms) - recs[size_t(i)].exe_end_ms;
+            }
+            hot[size_t(Ln - 1)] = double(recs[size_t(Ln - 1)].exe_end_ms) - recs[size_t(Ln - 1)].exe_start_ms +
+                                  (Ln > 1 ? gap / (Ln - 1) : 0.0);
+        }
     }
     c->mode = mode0;
     c->wrap = wrap0;

@@ -234,6 +234,9 @@ WorkspaceLayout make_workspace(const dl_module_desc& d) {
     if (d.max_seq == 0) {
         W.vt_ld = int32_t(align_up(T, 64));
         put(&W.vt, 2 * dkv * uint64_t(W.vt_ld));
+    } else {
+        // partial results of the split single-token attention: [Hq][tiles of 64 positions][d_head + 2] floats
+        put(&W.dec_part, uint64_t(d.n_q_heads) * ((uint64_t(d.max_seq) + 63) / 64) * uint64_t(d.d_head + 2) * 4);
     }
     if (d.d_ctx > 0) {
         const uint64_t C = d.max_ctx;

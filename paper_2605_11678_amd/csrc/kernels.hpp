@@ -30,13 +30,15 @@ void gemm(const GemmArgs& a, hipStream_t st);
 
 // ---- matrix-vector for single-token passes: out[N] = B[N,K] * x[K], same epilogues ----------
 struct GemvArgs {
-    const bf16_t* x;              // [K] bf16
+    const bf16_t* x;              // [K] bf16 (used when xf == nullptr)
     const bf16_t* B; int ldb;     // [N,K]
     const bf16_t* bias;
     void* out;
     const float* resid;
     int N, K;
     int epi;
+    // optional fused normalisation of the input: x = Norm(xf) rounded to bf16 (norm_kind 0 RMS, 1 LayerNorm)
+    const float* xf; const bf16_t* ng; const bf16_t* nb; int norm_kind; float eps;
 };
 void gemv(const GemvArgs& a, hipStream_t st);
 
@@ -70,6 +72,20 @@ struct AttnArgs {
     int T, S, q_pos0, Hq, Hkv, dh, causal;
 };
 void attention(const AttnArgs& a, hipStream_t st);
+
+// Single-query attention over a KV cache (decode), split over the key range: one wavefront per
+// (KV head, 64-position tile) writes a partial (max, sum, output) per query head into `partial`
+// ([Hq][n_tiles][dh + 2] floats), a second kernel merges the tiles.  S = number of cached positions.
+struct DecodeAttnArgs {
+    const bf16_t* q;                                   // [Hq * dh] (already rotated)
+    const bf16_t* k; int ldk; uint64_t k_head_stride;
+    const bf16_t* vt; int ldv; uint64_t v_head_stride;
+    bf16_t* out;                                       // [Hq * dh]
+    float* partial;
+    int S, Hq, Hkv, dh;
+};
+uint64_t decode_attention_workspace_bytes(int max_seq, int Hq, int dh);
+void decode_attention(const DecodeAttnArgs& a, hipStream_t st);
 
 // ---- head --------------------------------------------------------------------------------------------
 void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_host, float* x_out, hipStream_t st);

@@ -58,6 +58,34 @@ class Engine:
         self.modules[mid] = c
         return mid
 
+    def pick_copy_stream(self, mid, n_tokens, x_ptr, y_ptr, pos0=0, candidates=6, passes=3):
+        """HIP maps streams onto a handful of hardware queues; two streams that land on the same queue do
+        not overlap.  Which pairs collide cannot be queried, so it is measured: every candidate copy stream
+        runs a few fully streamed passes back to back and the fastest one is kept.  Returns the
+        (stream index, ms per pass) list."""
+        import time
+        c = self.modules[mid]
+        keep_res = self.ctx.get_residency(mid, c.n_layers)
+        self.ctx.set_residency(mid, [])
+        tried = []
+        cands = [self.s_copy] + [self.torch.cuda.Stream(device=self.dev) for _ in range(candidates - 1)]
+        for i, st in enumerate(cands):
+            if st.cuda_stream == self.s_compute.cuda_stream:
+                continue
+            self.ctx.set_streams(self.s_compute.cuda_stream, st.cuda_stream, keep=st)
+            self.ctx.forward(mid, x_ptr, y_ptr, n_tokens, pos0)
+            self.ctx.sync()
+            t = time.perf_counter()
+            for _ in range(passes):
+                self.ctx.forward(mid, x_ptr, y_ptr, n_tokens, pos0)
+            self.ctx.sync()
+            tried.append((i, (time.perf_counter() - t) * 1e3 / passes))
+        best = min(tried, key=lambda r: r[1])[0]
+        self.s_copy = cands[best]
+        self.ctx.set_streams(self.s_compute.cuda_stream, self.s_copy.cuda_stream, keep=self.s_copy)
+        self.ctx.set_residency(mid, keep_res)
+        return tried
+
     # ---- activations (fp32, carved from the arena so that they count against the cap) ----
     def alloc_f32(self, n_elems: int):
         ptr = self.ctx.arena_alloc(4 * int(n_elems))
