@@ -163,6 +163,24 @@ int32_t dl_logits_argmax(dl_ctx* ctx, int32_t module, const void* h_dev, int32_t
 int32_t dl_greedy_step(dl_ctx* ctx, int32_t module, const void* h_dev, int32_t* token_dev, void* x_dev);
 int32_t dl_sync(dl_ctx* ctx);
 
+/* ---- always-resident dense parts between the layer stacks (Sec. II-A patch merger, output heads; Sec. IV-D:
+ *      non-layer components stay resident in every configuration) ------------------------------------------ */
+
+/* y = W2 * gelu_tanh(W1 * x + b1) + b2 when d_hidden > 0, else y = W2 * x + b2.  w1: host BF16 [d_hidden, d_in],
+ * w2: host BF16 [d_out, d_hidden or d_in]; b1, b2: host BF16 or NULL.  Parameters and a [max_tokens, .] BF16
+ * workspace are placed in the arena (DL_ERR_BUDGET_EXCEEDED if they do not fit).  d_in, d_hidden % 8 == 0. */
+int32_t dl_mlp_create(dl_ctx* ctx, int32_t d_in, int32_t d_hidden, int32_t d_out, const void* w1, const void* b1,
+                      const void* w2, const void* b2, int32_t max_tokens, int32_t* mlp_out);
+/* x_dev: device fp32 [n_tokens, d_in]; y_dev: device fp32 [n_tokens, d_out]; on the compute stream. */
+int32_t dl_mlp_forward(dl_ctx* ctx, int32_t mlp, const void* x_dev, void* y_dev, int32_t n_tokens);
+/* y_dev[t, :] = mean of x_dev[t*group .. t*group+group-1, :]  (fp32, d columns, t < n_out) */
+int32_t dl_mean_pool(dl_ctx* ctx, const void* x_dev, void* y_dev, int32_t n_out, int32_t group, int32_t d);
+/* y_dev[i] += alpha * x_dev[i], i < n  (one Euler step of the flow-matching action head, Sec. II-A) */
+int32_t dl_axpy(dl_ctx* ctx, void* y_dev, float alpha, const void* x_dev, uint64_t n);
+/* y_dev[t, i] = x_dev[t, i] + e_i(t_value): sinusoidal embedding of the flow time added to every token;
+ * e_i = sin(1000 t w_i) for i < d/2, cos(1000 t w_{i-d/2}) otherwise, w_j = 10000^(-j/(d/2)). */
+int32_t dl_add_time_embedding(dl_ctx* ctx, const void* x_dev, void* y_dev, float t_value, int32_t n_tokens, int32_t d);
+
 /* ---- measurement ------------------------------------------------------------------------ */
 
 typedef struct {

@@ -89,6 +89,11 @@ SIGNATURES = {
     "dl_logits_argmax": (_i32, [_p, _i32, _p, _PI32, C.POINTER(C.c_float)]),
     "dl_greedy_step": (_i32, [_p, _i32, _p, _p, _p]),
     "dl_sync": (_i32, [_p]),
+    "dl_mlp_create": (_i32, [_p, _i32, _i32, _i32, _p, _p, _p, _p, _i32, _PI32]),
+    "dl_mlp_forward": (_i32, [_p, _i32, _p, _p, _i32]),
+    "dl_mean_pool": (_i32, [_p, _p, _p, _i32, _i32, _i32]),
+    "dl_axpy": (_i32, [_p, _p, C.c_float, _p, _u64]),
+    "dl_add_time_embedding": (_i32, [_p, _p, _p, C.c_float, _i32, _i32]),
     "dl_profile": (_i32, [_p, _i32, _i32, _i32, _p, _p, _i32, _i32, C.POINTER(dl_layer_profile)]),
     "dl_set_timing": (_i32, [_p, _i32]),
     "dl_collect_stats": (_i32, [_p, C.POINTER(dl_run_stats), C.POINTER(dl_layer_record), _i32]),
@@ -249,6 +254,29 @@ class Context:
 
     def sync(self):
         self._ck(lib().dl_sync(self._h))
+
+    def mlp_create(self, d_in, d_hidden, d_out, w1, b1, w2, b2, max_tokens):
+        def ptr(a):
+            if a is None:
+                return None
+            assert a.dtype.name == "uint16" and a.flags.c_contiguous
+            return _p(a.ctypes.data)
+        out = _i32()
+        self._ck(lib().dl_mlp_create(self._h, d_in, d_hidden, d_out, ptr(w1), ptr(b1), ptr(w2), ptr(b2), max_tokens,
+                                     C.byref(out)))
+        return out.value
+
+    def mlp_forward(self, mlp, x_ptr, y_ptr, n_tokens):
+        self._ck(lib().dl_mlp_forward(self._h, mlp, _p(x_ptr), _p(y_ptr), n_tokens))
+
+    def mean_pool(self, x_ptr, y_ptr, n_out, group, d):
+        self._ck(lib().dl_mean_pool(self._h, _p(x_ptr), _p(y_ptr), n_out, group, d))
+
+    def axpy(self, y_ptr, alpha, x_ptr, n):
+        self._ck(lib().dl_axpy(self._h, _p(y_ptr), alpha, _p(x_ptr), n))
+
+    def add_time_embedding(self, x_ptr, y_ptr, t_value, n_tokens, d):
+        self._ck(lib().dl_add_time_embedding(self._h, _p(x_ptr), _p(y_ptr), t_value, n_tokens, d))
 
     # ---- measurement ----
     def profile(self, module, n_layers, n_tokens, pos0, x_ptr, iters=4, ctx_ptr=None, n_ctx=0):

@@ -135,6 +135,16 @@ def make_head(c: ModuleConfig, seed: int = 8) -> Dict[int, np.ndarray]:
     return out
 
 
+def make_mlp(d_in: int, d_hidden: int, d_out: int, seed: int):
+    """(w1 [d_hidden, d_in], b1, w2 [d_out, d_hidden or d_in], b2) as BF16 bits ~ N(0, 0.02); w1, b1 None if d_hidden == 0."""
+    k2 = d_hidden if d_hidden > 0 else d_in
+    w1 = synth.normal_bf16(d_hidden * d_in, seed, 0, 0.0, 0.02).reshape(d_hidden, d_in) if d_hidden > 0 else None
+    b1 = synth.normal_bf16(d_hidden, seed, 1, 0.0, 0.02) if d_hidden > 0 else None
+    w2 = synth.normal_bf16(d_out * k2, seed, 2, 0.0, 0.02).reshape(d_out, k2)
+    b2 = synth.normal_bf16(d_out, seed, 3, 0.0, 0.02)
+    return w1, b1, w2, b2
+
+
 # ---- the workloads ---------------------------------------------------------
 def tiny_decoder() -> ModuleConfig:
     return ModuleConfig("tiny_decoder", 4, 256, 4, 4, 64, 768, NORM_RMS, ACT_SWIGLU, 0, 1, 1e4,

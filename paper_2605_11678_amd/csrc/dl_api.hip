@@ -32,6 +32,12 @@ struct Module {
     bool rt_set[DL_R_COUNT] = {false, false, false, false};
 };
 
+struct Mlp {
+    int32_t d_in = 0, d_hidden = 0, d_out = 0, max_tokens = 0;
+    uint64_t w1 = 0, b1 = 0, w2 = 0, b2 = 0, xin = 0, hid = 0;   // arena offsets
+    bool has_b1 = false, has_b2 = false;
+};
+
 struct TimedOp {
     hipEvent_t e0, e1;
     int32_t module, layer, slot;
@@ -48,6 +54,7 @@ struct dl_ctx {
     hipStream_t s_compute = nullptr, s_copy = nullptr;
     bool streams_set = false;
     std::vector<Module> mods;
+    std::vector<Mlp> mlps;
     uint64_t slot_bytes = 0;
     uint64_t slot_off[2] = {0, 0};
     bool slots_alloc = false;
@@ -785,6 +792,101 @@ int32_t dl_greedy_step(dl_ctx* c, int32_t module, const void* h, int32_t* token_
     if (token_dev) DL_HIP(c, hipMemcpyAsync(token_dev, tok, 4, hipMemcpyDeviceToDevice, c->s_compute));
     dlk::embed_row(reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_EMBED]), M->d.d_model, tok, 0,
                    static_cast<float*>(x_dev), c->s_compute);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_mlp_create(dl_ctx* c, int32_t d_in, int32_t d_hidden, int32_t d_out, const void* w1, const void* b1,
+                      const void* w2, const void* b2, int32_t max_tokens, int32_t* mlp_out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!mlp_out || !w2 || d_in < 8 || d_in % 8 || d_hidden < 0 || d_hidden % 8 || d_out < 1 || max_tokens < 1 ||
+        (d_hidden > 0 && !w1))
+        return fail(c, DL_ERR_INVALID_ARG, "bad MLP description");
+    if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
+    Mlp m;
+    m.d_in = d_in; m.d_hidden = d_hidden; m.d_out = d_out; m.max_tokens = max_tokens;
+    m.has_b1 = d_hidden > 0 && b1 != nullptr;
+    m.has_b2 = b2 != nullptr;
+    const uint64_t k2 = d_hidden > 0 ? d_hidden : d_in;
+    struct Part { uint64_t* off; uint64_t bytes; const void* src; };
+    std::vector<Part> parts;
+    if (d_hidden > 0) parts.push_back({&m.w1, 2ull * d_hidden * d_in, w1});
+    if (m.has_b1) parts.push_back({&m.b1, 2ull * d_hidden, b1});
+    parts.push_back({&m.w2, 2ull * d_out * k2, w2});
+    if (m.has_b2) parts.push_back({&m.b2, 2ull * d_out, b2});
+    parts.push_back({&m.xin, 2ull * max_tokens * d_in, nullptr});
+    if (d_hidden > 0) parts.push_back({&m.hid, 2ull * max_tokens * d_hidden, nullptr});
+    dl::Arena A = c->arena;                       // all or nothing
+    for (Part& p : parts)
+        if (!A.alloc(p.bytes, p.off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the MLP");
+    c->arena = A;
+    if (on_gpu(c)) {
+        rc = sync_streams(c);
+        if (rc) return rc;
+        for (Part& p : parts)
+            if (p.src) DL_HIP(c, hipMemcpy(c->base + *p.off, p.src, p.bytes, hipMemcpyHostToDevice));
+    }
+    c->mlps.push_back(m);
+    *mlp_out = int32_t(c->mlps.size() - 1);
+    return DL_OK;
+}
+
+int32_t dl_mlp_forward(dl_ctx* c, int32_t mlp, const void* x, void* y, int32_t T) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (mlp < 0 || size_t(mlp) >= c->mlps.size()) return fail(c, DL_ERR_INVALID_ARG, "no such MLP");
+    const Mlp& m = c->mlps[size_t(mlp)];
+    if (T < 1 || T > m.max_tokens) return fail(c, DL_ERR_INVALID_ARG, "n_tokens outside [1, max_tokens]");
+    if (!on_gpu(c)) return DL_OK;
+    if (!x || !y) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
+    hipStream_t st = c->s_compute;
+    auto P = [&](uint64_t off) { return reinterpret_cast<bf16_t*>(c->base + off); };
+    dlk::cast_f32_bf16(static_cast<const float*>(x), P(m.xin), uint64_t(T) * m.d_in, st);
+    const bf16_t* a2 = P(m.xin);
+    int k2 = m.d_in;
+    if (m.d_hidden > 0) {
+        dlk::GemmArgs g1{P(m.xin), m.d_in, P(m.w1), m.d_in, m.has_b1 ? P(m.b1) : nullptr, P(m.hid), m.d_hidden, nullptr, 0,
+                         T, m.d_hidden, m.d_in, dlk::EPI_GELU_BF16};
+        dlk::gemm(g1, st);
+        a2 = P(m.hid);
+        k2 = m.d_hidden;
+    }
+    dlk::GemmArgs g2{a2, k2, P(m.w2), k2, m.has_b2 ? P(m.b2) : nullptr, y, m.d_out, nullptr, 0, T, m.d_out, k2, dlk::EPI_F32};
+    dlk::gemm(g2, st);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_mean_pool(dl_ctx* c, const void* x, void* y, int32_t n_out, int32_t group, int32_t d) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (n_out < 1 || group < 1 || d < 1) return fail(c, DL_ERR_INVALID_ARG, "bad sizes");
+    if (!on_gpu(c)) return DL_OK;
+    if (!x || !y || x == y) return fail(c, DL_ERR_INVALID_ARG, "null or aliasing pointers");
+    dlk::mean_pool_rows(static_cast<const float*>(x), static_cast<float*>(y), n_out, group, d, c->s_compute);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_axpy(dl_ctx* c, void* y, float alpha, const void* x, uint64_t n) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!on_gpu(c)) return DL_OK;
+    if (!x || !y) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    dlk::axpy_f32(static_cast<float*>(y), alpha, static_cast<const float*>(x), n, c->s_compute);
+    DL_HIP(c, hipGetLastError());
+    return DL_OK;
+}
+
+int32_t dl_add_time_embedding(dl_ctx* c, const void* x, void* y, float tval, int32_t T, int32_t d) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (T < 1 || d < 2 || d % 2) return fail(c, DL_ERR_INVALID_ARG, "bad sizes");
+    if (!on_gpu(c)) return DL_OK;
+    if (!x || !y) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    dlk::add_time_embedding(static_cast<const float*>(x), static_cast<float*>(y), tval, T, d, c->s_compute);
     DL_HIP(c, hipGetLastError());
     return DL_OK;
 }

@@ -87,6 +87,14 @@ struct DecodeAttnArgs {
 uint64_t decode_attention_workspace_bytes(int max_seq, int Hq, int dh);
 void decode_attention(const DecodeAttnArgs& a, hipStream_t st);
 
+// ---- small elementwise helpers of the multi-module pipeline (fp32 activations) ----------------------
+// y[t, :] = mean over j < group of x[t*group + j, :]
+void mean_pool_rows(const float* x, float* y, int T_out, int group, int d, hipStream_t st);
+// y[i] += alpha * x[i]
+void axpy_f32(float* y, float alpha, const float* x, uint64_t n, hipStream_t st);
+// y[t, i] = x[t, i] + (i < d/2 ? sin : cos)(1000 * tval * 10000^(-(i mod d/2) / (d/2)))
+void add_time_embedding(const float* x, float* y, float tval, int T, int d, hipStream_t st);
+
 // ---- head --------------------------------------------------------------------------------------------
 void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_host, float* x_out, hipStream_t st);
 void argmax_f32(const float* logits, int n, int32_t* token_dev, hipStream_t st);

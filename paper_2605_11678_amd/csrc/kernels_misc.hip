@@ -60,6 +60,33 @@ __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ x, 
         out[i] = f_to_bf16(x[i]);
 }
 
+__global__ __launch_bounds__(256) void mean_pool_kernel(const float* __restrict__ x, float* __restrict__ y, int group,
+                                                        int d) {
+    const int t = blockIdx.x;
+    const float inv = 1.0f / float(group);
+    for (int i = threadIdx.x; i < d; i += 256) {
+        float s = 0.0f;
+        for (int j = 0; j < group; ++j) s += x[(size_t(t) * group + j) * d + i];
+        y[size_t(t) * d + i] = s * inv;
+    }
+}
+
+__global__ __launch_bounds__(256) void axpy_kernel(float* __restrict__ y, float alpha, const float* __restrict__ x,
+                                                   uint64_t n) {
+    for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += uint64_t(gridDim.x) * 256)
+        y[i] = fmaf(alpha, x[i], y[i]);
+}
+
+__global__ __launch_bounds__(256) void time_embed_kernel(const float* __restrict__ x, float* __restrict__ y, float tval,
+                                                         int d) {
+    const int t = blockIdx.x, half = d >> 1;
+    for (int i = threadIdx.x; i < d; i += 256) {
+        const int j = i < half ? i : i - half;
+        const float ang = 1000.0f * tval * exp2f(-float(j) / float(half) * 13.287712379549449f);   // log2(10000)
+        y[size_t(t) * d + i] = x[size_t(t) * d + i] + (i < half ? sinf(ang) : cosf(ang));
+    }
+}
+
 __global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs p) {
     const int t = blockIdx.x, pos = p.pos0 + t;
     bf16_t* row = p.qkv + size_t(t) * p.n_qkv;
@@ -159,6 +186,22 @@ void cast_f32_bf16(const float* x, bf16_t* out, uint64_t n, hipStream_t st) {
     const uint64_t blocks = (n + 255) / 256;
     dim3 grid(unsigned(blocks < 4096 ? blocks : 4096)), block(256);
     hipLaunchKernelGGL(cast_kernel, grid, block, 0, st, x, out, n);
+}
+
+void mean_pool_rows(const float* x, float* y, int T_out, int group, int d, hipStream_t st) {
+    if (T_out <= 0) return;
+    hipLaunchKernelGGL(mean_pool_kernel, dim3(T_out), dim3(256), 0, st, x, y, group, d);
+}
+
+void axpy_f32(float* y, float alpha, const float* x, uint64_t n, hipStream_t st) {
+    if (n == 0) return;
+    const uint64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(axpy_kernel, dim3(unsigned(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, y, alpha, x, n);
+}
+
+void add_time_embedding(const float* x, float* y, float tval, int T, int d, hipStream_t st) {
+    if (T <= 0) return;
+    hipLaunchKernelGGL(time_embed_kernel, dim3(T), dim3(256), 0, st, x, y, tval, d);
 }
 
 void qkv_post(const QkvPostArgs& a, hipStream_t st) {

@@ -104,3 +104,82 @@ class Engine:
     def download(self, view) -> np.ndarray:
         self.ctx.sync()
         return view.cpu().numpy().copy()
+
+
+class VlaPipeline:
+    """The five-stage pipeline (vision encoder, merger, decoder prefill, decoder decode, action head with
+    Euler steps) wired from C-ABI calls.  One context, one slot pair shared by the three layer stacks.
+    Plumbing only: every arithmetic step is a library call."""
+
+    def __init__(self, eng: Engine, vit: CFG.ModuleConfig, dec: CFG.ModuleConfig, act: CFG.ModuleConfig,
+                 n_patches: int, n_text: int, n_actions: int = 64, pool: int = 4, out_dim: int = 3,
+                 seeds=(11, 12, 13, 14, 15, 16)):
+        self.eng, self.vit, self.dec, self.act = eng, vit, dec, act
+        self.n_patches, self.n_text, self.n_actions, self.pool = n_patches, n_text, n_actions, pool
+        self.n_vis = n_patches // pool
+        self.n_prefill = self.n_vis + n_text
+        ctx = eng.ctx
+        self.m_vit = eng.add_module(vit, max_tokens=n_patches)
+        self.m_dec = eng.add_module(dec, max_tokens=self.n_prefill)
+        self.m_act = eng.add_module(act, max_tokens=n_actions, max_ctx=self.n_prefill)
+        self.proj_w = CFG.make_mlp(vit.d_model, dec.d_model, dec.d_model, seeds[0])
+        self.out_w = CFG.make_mlp(act.d_model, 0, out_dim, seeds[1])
+        self.mlp_proj = ctx.mlp_create(vit.d_model, dec.d_model, dec.d_model, *self.proj_w, max_tokens=n_patches)
+        self.mlp_out = ctx.mlp_create(act.d_model, 0, out_dim, None, None, self.out_w[2], self.out_w[3],
+                                      max_tokens=n_actions)
+        self.patches = CFG.make_tokens(n_patches, vit.d_model, seed=seeds[2])
+        self.text = CFG.make_tokens(n_text, dec.d_model, seed=seeds[3])
+        self.a0 = CFG.make_tokens(n_actions, act.d_model, seed=seeds[4])
+        A = eng.alloc_f32
+        self.p_patch, self.v_patch = A(n_patches * vit.d_model)
+        self.p_vit, self.v_vit = A(n_patches * vit.d_model)
+        self.p_proj, self.v_proj = A(n_patches * dec.d_model)
+        self.p_seq, self.v_seq = A(self.n_prefill * dec.d_model)
+        self.p_h, self.v_h = A(self.n_prefill * dec.d_model)
+        self.p_ctx, self.v_ctx = A(self.n_prefill * dec.d_model)
+        self.p_x1, self.v_x1 = A(dec.d_model)
+        self.p_y1, self.v_y1 = A(dec.d_model)
+        self.p_tok, self.v_tok = A(256)
+        self.p_a, self.v_a = A(n_actions * act.d_model)
+        self.p_ain, self.v_ain = A(n_actions * act.d_model)
+        self.p_vel, self.v_vel = A(n_actions * act.d_model)
+        self.p_traj, self.v_traj = A(n_actions * out_dim)
+        self.out_dim = out_dim
+        eng.upload(self.v_patch, self.patches)
+
+    def run(self, n_decode: int, n_euler: int = 10):
+        """Enqueues one whole inference; returns after the final synchronisation."""
+        e, ctx = self.eng, self.eng.ctx
+        d = self.dec.d_model
+        # text embeddings and the initial action noise are inputs: (re)upload them untimed by the caller if needed
+        e.upload(self.v_seq[self.n_vis * d:], self.text)
+        e.upload(self.v_a, self.a0)
+        self.enqueue(n_decode, n_euler)
+        ctx.sync()
+
+    def enqueue(self, n_decode: int, n_euler: int = 10):
+        ctx = self.eng.ctx
+        d, da = self.dec.d_model, self.act.d_model
+        ctx.forward(self.m_vit, self.p_patch, self.p_vit, self.n_patches, 0)
+        ctx.mlp_forward(self.mlp_proj, self.p_vit, self.p_proj, self.n_patches)
+        ctx.mean_pool(self.p_proj, self.p_seq, self.n_vis, self.pool, d)
+        ctx.forward(self.m_dec, self.p_seq, self.p_h, self.n_prefill, 0)
+        ctx.final_norm(self.m_dec, self.p_h, self.p_ctx, self.n_prefill)
+        h_ptr = self.p_h + 4 * (self.n_prefill - 1) * d
+        for s in range(n_decode):
+            ctx.greedy_step(self.m_dec, h_ptr, self.p_tok + 4 * (s % 64), self.p_x1)
+            ctx.forward(self.m_dec, self.p_x1, self.p_y1, 1, self.n_prefill + s)
+            h_ptr = self.p_y1
+        for s in range(n_euler):
+            ctx.add_time_embedding(self.p_a, self.p_ain, s / n_euler, self.n_actions, da)
+            ctx.forward(self.m_act, self.p_ain, self.p_vel, self.n_actions, 0, self.p_ctx, self.n_prefill)
+            ctx.axpy(self.p_a, 1.0 / n_euler, self.p_vel, self.n_actions * da)
+        ctx.mlp_forward(self.mlp_out, self.p_a, self.p_traj, self.n_actions)
+
+    def results(self, n_decode: int):
+        e = self.eng
+        toks = e.download(self.v_tok[:min(n_decode, 64)]).view(np.int32).tolist() if n_decode else []
+        return dict(tokens=toks,
+                    hidden_ctx=e.download(self.v_ctx).reshape(self.n_prefill, self.dec.d_model),
+                    actions=e.download(self.v_a).reshape(self.n_actions, self.act.d_model),
+                    trajectory=e.download(self.v_traj).reshape(self.n_actions, self.out_dim))

@@ -340,3 +340,46 @@ def test_generate_greedy_consistency():
         assert lg == pytest.approx(logits[s], rel=1e-10)
         seq = np.vstack([seq, head[0][toks[s]][None, :]])
     assert hs.shape == (4, c["d_model"])
+
+
+# ---------------- pipeline oracle (oracle/pipeline.py) ----------------------------------------------
+def test_pipeline_small_pieces_hand_values():
+    from oracle import pipeline as PL
+    x = np.arange(16.0).reshape(8, 2)
+    assert PL.mean_pool(x, 4).tolist() == [[3.0, 4.0], [11.0, 12.0]]
+    # t = 0: sines vanish, cosines are one
+    assert PL.time_embedding(0.0, 6).tolist() == [0.0, 0.0, 0.0, 1.0, 1.0, 1.0]
+    e = PL.time_embedding(0.001 * math.pi / 2, 4)          # 1000 t = pi/2: first frequency is 1
+    assert e[0] == pytest.approx(1.0) and e[2] == pytest.approx(0.0, abs=1e-15)
+    assert e[1] == pytest.approx(math.sin(math.pi / 2 * 10000.0 ** -0.5))
+    # MLP against scalar loops
+    rng = np.random.default_rng(0)
+    w1, b1, w2, b2 = rng.standard_normal((5, 3)), rng.standard_normal(5), rng.standard_normal((2, 5)), rng.standard_normal(2)
+    xin = rng.standard_normal((4, 3))
+    got = PL.mlp(xin, w1, b1, w2, b2)
+    for t in range(4):
+        hid = [sum(xin[t][i] * w1[o][i] for i in range(3)) + b1[o] for o in range(5)]
+        hid = [0.5 * u * (1 + math.tanh(math.sqrt(2 / math.pi) * (u + 0.044715 * u ** 3))) for u in hid]
+        for o in range(2):
+            assert got[t][o] == pytest.approx(sum(hid[i] * w2[o][i] for i in range(5)) + b2[o])
+    assert PL.mlp(xin, None, None, w2[:, :3], None) == pytest.approx(xin @ w2[:, :3].T)
+
+
+def test_pipeline_euler_closed_form():
+    """With zero output projections the action stack is the identity, so the velocity is a + e(t) and
+    ten Euler steps have the closed form a_10 = 1.1^10 a_0 + sum_s 1.1^(9-s) * 0.1 * e(s/10)."""
+    from oracle import pipeline as PL
+    rng = np.random.default_rng(1)
+    c = cfg_encoder(d_ctx=4, n_layers=1)
+    W = rand_weights(c, rng)
+    for t in (F.T_WO, F.T_W_DOWN, F.T_WO_C):
+        W[t] = np.zeros_like(W[t])
+    for t in (F.T_BO, F.T_B_DOWN, F.T_BO_C):
+        W[t] = np.zeros_like(W[t])
+    a0 = rng.standard_normal((3, c["d_model"]))
+    ctx = rng.standard_normal((5, 4))
+    got = PL.euler_actions(c, lambda l: W, a0, ctx, 10)
+    want = 1.1 ** 10 * a0
+    for s in range(10):
+        want = want + 1.1 ** (9 - s) * 0.1 * PL.time_embedding(s / 10, c["d_model"])[None, :]
+    assert got == pytest.approx(want, rel=1e-12)
