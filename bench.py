@@ -187,6 +187,116 @@ def vit_leg(B, CFG, Engine, torch, log):
     eng.close()
     return out
 
+def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
+    """configs[4]: vision encoder -> merger -> 8B decoder prefill + 64 decode steps -> action head (10 Euler
+    steps, 64 tokens cross-attending to the decoder's hidden states), all under one arena; one slot pair shared
+    by the three stacks; residency per module chosen by the planner from one profiling run."""
+    import numpy as np
+    from paper_2605_11678_amd.harness import VlaPipeline
+    vit, dec, act = CFG.vit_encoder(), CFG.decoder_8b(max_seq=3072 + n_decode), CFG.action_head()
+    eng = Engine(int(cap), device=0)
+    t0 = time.time()
+    pipe = VlaPipeline(eng, vit, dec, act, n_patches=4096, n_text=2048, n_actions=64)
+    ctx = eng.ctx
+    mods = [pipe.m_vit, pipe.m_dec, pipe.m_act]
+    cfgs = [vit, dec, act]
+    Ls = [c.n_layers for c in cfgs]
+    sizes = [ctx.module_layer_bytes(m)[0] for m in mods]
+    log("vla setup %.1f s; layer bytes %s; arena used %.3f GB (everything streamed)" %
+        (time.time() - t0, sizes, ctx.arena_stats()["used"] / 1e9))
+    ctx.set_mode(B.DL_MODE_PIPELINED, 1)
+    pipe.run(1)                                              # warm every kernel once, fills the KV cache and ctx
+    eng.pick_copy_stream(pipe.m_vit, 4096, pipe.p_patch, pipe.p_vit)
+    # ---- one profiling run per module and phase ----
+    P = {}
+    P["vit"] = ctx.profile(pipe.m_vit, Ls[0], 4096, 0, pipe.p_patch, iters=3)
+    P["prefill"] = ctx.profile(pipe.m_dec, Ls[1], pipe.n_prefill, 0, pipe.p_seq, iters=3)
+    P["decode"] = ctx.profile(pipe.m_dec, Ls[1], 1, pipe.n_prefill, pipe.p_x1, iters=3)
+    P["action"] = ctx.profile(pipe.m_act, Ls[2], 64, 0, pipe.p_ain, iters=3, ctx_ptr=pipe.p_ctx, n_ctx=pipe.n_prefill)
+    mean = lambda rows, key: float(np.mean([r[key] for r in rows]))
+    prof = {k: {"c_dma_ms": round(mean(v, "c_dma_ms"), 4), "c_exe_ms": round(mean(v, "c_exe_ms"), 4),
+                "c_exe_hot_ms": round(mean(v, "c_exe_hot_ms"), 4)} for k, v in P.items()}
+    MiB = float(1 << 20)
+    b3 = [B.benefit(prof["vit"]["c_dma_ms"], sizes[0] / MiB, [prof["vit"]["c_exe_ms"]], [1]),
+          B.benefit(prof["prefill"]["c_dma_ms"], sizes[1] / MiB, [prof["prefill"]["c_exe_ms"], prof["decode"]["c_exe_ms"]],
+                    [1, n_decode]),
+          B.benefit(prof["action"]["c_dma_ms"], sizes[2] / MiB, [prof["action"]["c_exe_ms"]], [10])]
+    st = ctx.arena_stats()
+    budget = st["capacity"] - st["used"] - (128 << 20)      # head-room for 256-byte rounding and first-fit holes
+    k_plan = B.plan(Ls, sizes, [list(b) for b in b3], budget)
+    log("vla benefit (ms/MiB) first/mid/last: vit %s, decoder %s, action %s; budget %.2f GB -> k = %s" %
+        (np.round(b3[0], 4).tolist(), np.round(b3[1], 4).tolist(), np.round(b3[2], 4).tolist(), budget / 1e9, k_plan))
+
+    # greedy head per token (resident, outside the layer passes)
+    ctx.sync()
+    t = time.perf_counter()
+    for _ in range(30):
+        ctx.greedy_step(pipe.m_dec, pipe.p_y1, pipe.p_tok, pipe.p_x1)
+    ctx.sync()
+    head_ms = (time.perf_counter() - t) * 1e3 / 30
+
+    def predict(ks, wrap):
+        dma, hot, idle, streamed, starts, mids = [], [], [], [], [], []
+        def add_pass(mi, rows, res):
+            for i, r in enumerate(rows):
+                dma.append(r["c_dma_ms"]); hot.append(r["c_exe_hot_ms"]); idle.append(r["c_exe_ms"])
+                streamed.append(i not in res); starts.append(i == 0); mids.append(mi)
+        rs = [set(B.place_interleaved(Ls[m], ks[m])) for m in range(3)]
+        add_pass(0, P["vit"], rs[0])
+        add_pass(1, P["prefill"], rs[1])
+        for _ in range(n_decode):
+            add_pass(1, P["decode"], rs[1])
+        for _ in range(10):
+            add_pass(2, P["action"], rs[2])
+        return B.timeline(dma, hot, streamed, starts, module_id=mids, wrap_prefetch=wrap, c_exe_idle_ms=idle)["total"] \
+            + head_ms * n_decode
+
+    def measure(ks, wrap, reps):
+        for m in range(3):
+            ctx.set_residency(mods[m], [])                   # release first: the new plan may not fit next to the old one
+        for m in range(3):
+            ctx.set_residency(mods[m], B.place_interleaved(Ls[m], ks[m]))
+        ctx.set_mode(B.DL_MODE_PIPELINED, wrap)
+        eng.upload(pipe.v_seq[pipe.n_vis * dec.d_model:], pipe.text)
+        samples = []
+        for _ in range(reps):
+            eng.upload(pipe.v_a, pipe.a0)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            pipe.enqueue(n_decode)
+            ctx.sync()
+            samples.append((time.perf_counter() - t) * 1e3)
+        return float(np.median(samples)), pipe.results(n_decode)
+
+    rows, ref = [], None
+    # second policy of the comparison: small modules fully resident first, the decoder gets what is left
+    left = budget - Ls[0] * sizes[0] - Ls[2] * sizes[2]
+    k_alt = [Ls[0], max(0, min(Ls[1], int(left // sizes[1]))), Ls[2]]
+    for name, ks, reps in (("planner", k_plan, 3), ("vit_and_action_resident_first", k_alt, 3), ("all_streamed", [0, 0, 0], 1)):
+        try:
+            ms, out = measure(ks, 1, reps)
+        except B.DLError as e:
+            rows.append({"policy": name, "k": ks, "error": str(e)})
+            continue
+        pred = predict(ks, 1)
+        same = None
+        if ref is None:
+            ref = out
+        else:
+            same = bool(np.array_equal(out["trajectory"].view(np.uint32), ref["trajectory"].view(np.uint32))
+                        and out["tokens"] == ref["tokens"])
+        rows.append({"policy": name, "k_vit_dec_act": ks, "ms_per_inference": round(ms, 2), "predicted_ms": round(pred, 2),
+                     "pred_err_pct": round((pred - ms) / ms * 100, 2), "arena_gb": round(ctx.arena_stats()["used"] / 1e9, 3),
+                     "bit_identical_to_first": same})
+        log("vla %-30s k=%s: %.1f ms/inference (predicted %.1f, %.2f%%) identical=%s" % (name, ks, ms, pred, rows[-1]["pred_err_pct"], same))
+    res = {"workload": "configs[4]: ViT 27L T=4096 -> merger -> 8B decoder prefill 3072 + %d decode steps -> action head 8L x 10 Euler "
+                       "steps on 64 tokens; cap %.3g B" % (n_decode, cap),
+           "layer_bytes": sizes, "profile": prof, "benefit_ms_per_MiB": [np.round(b, 5).tolist() for b in b3],
+           "budget_gb": round(budget / 1e9, 3), "head_ms": round(head_ms, 4), "runs": rows,
+           "trajectory_finite": bool(np.all(np.isfinite(ref["trajectory"]))) if ref else None}
+    eng.close()
+    return res
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -411,6 +521,10 @@ def main():
             out["extras"]["vit"] = vit_leg(B, CFG, Engine, torch, log)
         except B.DLError as e:
             out["extras"]["vit"] = {"error": str(e)}
+        try:
+            out["extras"]["vla"] = vla_leg(B, CFG, Engine, torch, log, cap)
+        except B.DLError as e:
+            out["extras"]["vla"] = {"error": str(e)}
     print(json.dumps(out), flush=True)
 
 
