@@ -374,14 +374,14 @@ void launch_fast(const GemmArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((gemm_fast<BM, BN, EPI>), dim3(grid), dim3(256), 0, st, a);
 }
 
-// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192.  Fewest rounds of 256 workgroups
-// weighted by tile area; the smaller tiles are a little less efficient per flop.
+// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192.  Fewest rounds of 256
+// workgroups weighted by tile area; the smaller tiles are a little less efficient per flop.
 int pick_tile(int M, int N, bool need_even_cols) {
-    const int bm[3] = {256, 192, 256}, bn[3] = {256, 256, 192};
-    const double eff[3] = {1.0, 0.93, 0.93};
+    const int bm[4] = {256, 192, 256, 192}, bn[4] = {256, 256, 192, 192};
+    const double eff[4] = {1.0, 0.93, 0.93, 0.86};
     int best = 0;
     double best_cost = 1e300;
-    for (int c = 0; c < 3; ++c) {
+    for (int c = 0; c < 4; ++c) {
         if (need_even_cols && bn[c] != 256) continue;
         const long tiles = long((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
         const double rounds = tiles >= 768 ? double(tiles) / 256.0 : double((tiles + 255) / 256);
@@ -396,7 +396,11 @@ void dispatch_fast(const GemmArgs& a, hipStream_t st) {
     const int t = pick_tile(a.M, a.N, EPI == EPI_SWIGLU_BF16);
     if (t == 0) launch_fast<256, 256, EPI>(a, st);
     else if (t == 1) launch_fast<192, 256, EPI>(a, st);
-    else if (EPI != EPI_SWIGLU_BF16) launch_fast<256, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+    else if (EPI != EPI_SWIGLU_BF16) {
+        // odd numbers of 32-wide tile columns per wavefront cannot pair gate/up rows: never chosen for SwiGLU
+        if (t == 2) launch_fast<256, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+        else launch_fast<192, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+    }
 }
 
 }  // namespace

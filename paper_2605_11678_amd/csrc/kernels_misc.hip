@@ -28,31 +28,73 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     return red[0] + red[1] + red[2] + red[3];
 }
 
+// One 256-thread workgroup per row; rows are read as float4 (d % 4 == 0) and kept in registers between the
+// reduction and the scaling pass when they fit (d <= 4096), so a row is read from memory once.
 template <int KIND, bool OUT_F32>
 __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, const bf16_t* __restrict__ g,
                                                    const bf16_t* __restrict__ b, void* __restrict__ out, int d,
                                                    float eps) {
     __shared__ float red[4];
-    const float* row = x + size_t(blockIdx.x) * d;
-    const int tid = threadIdx.x;
+    const float4* row = reinterpret_cast<const float4*>(x + size_t(blockIdx.x) * d);
+    const int tid = threadIdx.x, nv = d >> 2;
+    constexpr int KEEP = 4;                       // float4 per thread held in registers
+    float4 v[KEEP];
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        const int i = tid + 256 * j;
+        v[j] = i < nv ? row[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
     float mean = 0.0f;
     if (KIND == 1) {
         float s = 0.0f;
-        for (int i = tid; i < d; i += 256) s += row[i];
+#pragma unroll
+        for (int j = 0; j < KEEP; ++j) s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+        for (int i = tid + 256 * KEEP; i < nv; i += 256) {
+            const float4 t = row[i];
+            s += (t.x + t.y) + (t.z + t.w);
+        }
         mean = block_sum_256(s, red) / float(d);
     }
     float ss = 0.0f;
-    for (int i = tid; i < d; i += 256) {
-        const float c = row[i] - mean;
-        ss += c * c;
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        if (tid + 256 * j < nv) {
+            const float a0 = v[j].x - mean, a1 = v[j].y - mean, a2 = v[j].z - mean, a3 = v[j].w - mean;
+            ss += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
+    }
+    for (int i = tid + 256 * KEEP; i < nv; i += 256) {
+        const float4 t = row[i];
+        const float a0 = t.x - mean, a1 = t.y - mean, a2 = t.z - mean, a3 = t.w - mean;
+        ss += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
     }
     const float inv = rsqrtf(block_sum_256(ss, red) / float(d) + eps);
-    for (int i = tid; i < d; i += 256) {
-        float v = (row[i] - mean) * inv * bf16_to_f(g[i]);
-        if (KIND == 1) v += bf16_to_f(b[i]);
-        if (OUT_F32) static_cast<float*>(out)[size_t(blockIdx.x) * d + i] = v;
-        else static_cast<bf16_t*>(out)[size_t(blockIdx.x) * d + i] = f_to_bf16(v);
-    }
+    auto emit = [&](int i, const float4& t) {
+        const uint2 gg = reinterpret_cast<const uint2*>(g)[i];
+        float o0 = (t.x - mean) * inv * __uint_as_float(gg.x << 16);
+        float o1 = (t.y - mean) * inv * __uint_as_float(gg.x & 0xFFFF0000u);
+        float o2 = (t.z - mean) * inv * __uint_as_float(gg.y << 16);
+        float o3 = (t.w - mean) * inv * __uint_as_float(gg.y & 0xFFFF0000u);
+        if (KIND == 1) {
+            const uint2 bb = reinterpret_cast<const uint2*>(b)[i];
+            o0 += __uint_as_float(bb.x << 16);
+            o1 += __uint_as_float(bb.x & 0xFFFF0000u);
+            o2 += __uint_as_float(bb.y << 16);
+            o3 += __uint_as_float(bb.y & 0xFFFF0000u);
+        }
+        if (OUT_F32) {
+            reinterpret_cast<float4*>(static_cast<float*>(out) + size_t(blockIdx.x) * d)[i] = make_float4(o0, o1, o2, o3);
+        } else {
+            uint2 pk;
+            pk.x = uint32_t(f_to_bf16(o0)) | (uint32_t(f_to_bf16(o1)) << 16);
+            pk.y = uint32_t(f_to_bf16(o2)) | (uint32_t(f_to_bf16(o3)) << 16);
+            reinterpret_cast<uint2*>(static_cast<bf16_t*>(out) + size_t(blockIdx.x) * d)[i] = pk;
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j)
+        if (tid + 256 * j < nv) emit(tid + 256 * j, v[j]);
+    for (int i = tid + 256 * KEEP; i < nv; i += 256) emit(i, row[i]);
 }
 
 __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, uint64_t n) {
