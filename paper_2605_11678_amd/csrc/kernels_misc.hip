@@ -129,48 +129,63 @@ __global__ __launch_bounds__(256) void time_embed_kernel(const float* __restrict
     }
 }
 
-__global__ __launch_bounds__(256) void qkv_post_kernel(QkvPostArgs p) {
+// Rotary embedding of q (in place) and k (to the cache, or in place): one workgroup per token.  The angle
+// depends on (position, i) only, so each thread evaluates one sin/cos pair and reuses it for every head.
+__global__ __launch_bounds__(256) void rope_kernel(QkvPostArgs p) {
     const int t = blockIdx.x, pos = p.pos0 + t;
     bf16_t* row = p.qkv + size_t(t) * p.n_qkv;
     const int half = p.dh >> 1;
-    const float l2t = p.theta > 0.0f ? log2f(p.theta) : 0.0f;
-    // q: rotate in place
+    const int lanes = half < 256 ? half : 256;            // threads that own a frequency index
+    const int i = threadIdx.x % lanes, hg = threadIdx.x / lanes, n_hg = 256 / lanes;
+    float sn = 0.0f, cs = 1.0f;
+    if (p.theta > 0.0f) {
+        const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * log2f(p.theta));
+        sincosf(ang, &sn, &cs);
+    }
+    if (hg >= n_hg) return;
     if (p.theta > 0.0f && p.q_off >= 0) {
-        for (int idx = threadIdx.x; idx < p.Hq * half; idx += 256) {
-            const int h = idx / half, i = idx % half;
-            const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * l2t);
-            float sn, cs;
-            sincosf(ang, &sn, &cs);
+        for (int h = hg; h < p.Hq; h += n_hg) {
             bf16_t* q = row + p.q_off + h * p.dh;
-            const float a = bf16_to_f(q[i]), b = bf16_to_f(q[i + half]);
-            q[i] = f_to_bf16(a * cs - b * sn);
-            q[i + half] = f_to_bf16(a * sn + b * cs);
+            for (int ii = i; ii < half; ii += lanes) {
+                const float a = bf16_to_f(q[ii]), b = bf16_to_f(q[ii + half]);
+                q[ii] = f_to_bf16(a * cs - b * sn);
+                q[ii + half] = f_to_bf16(a * sn + b * cs);
+            }
         }
     }
-    // k: rotate, then to the cache (or back in place)
-    for (int idx = threadIdx.x; idx < p.Hkv * half; idx += 256) {
-        const int g = idx / half, i = idx % half;
-        const bf16_t* k = row + p.k_off + g * p.dh;
-        float a = bf16_to_f(k[i]), b = bf16_to_f(k[i + half]);
-        if (p.theta > 0.0f) {
-            const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * l2t);
-            float sn, cs;
-            sincosf(ang, &sn, &cs);
-            const float ra = a * cs - b * sn, rb = a * sn + b * cs;
-            a = ra;
-            b = rb;
-        }
-        bf16_t* dst = p.k_out ? p.k_out + size_t(g) * p.k_head_stride + size_t(pos) * p.dh
-                              : row + p.k_off + g * p.dh;
-        if (p.k_out || p.theta > 0.0f) {
-            dst[i] = f_to_bf16(a);
-            dst[i + half] = f_to_bf16(b);
+    if (p.k_out || p.theta > 0.0f) {
+        for (int g = hg; g < p.Hkv; g += n_hg) {
+            const bf16_t* k = row + p.k_off + g * p.dh;
+            bf16_t* dst = p.k_out ? p.k_out + size_t(g) * p.k_head_stride + size_t(pos) * p.dh : row + p.k_off + g * p.dh;
+            for (int ii = i; ii < half; ii += lanes) {
+                const float a = bf16_to_f(k[ii]), b = bf16_to_f(k[ii + half]);
+                dst[ii] = f_to_bf16(a * cs - b * sn);
+                dst[ii + half] = f_to_bf16(a * sn + b * cs);
+            }
         }
     }
-    // v: transposed store, position-contiguous rows per feature
-    for (int idx = threadIdx.x; idx < p.Hkv * p.dh; idx += 256) {
-        const int g = idx / p.dh, e = idx % p.dh;
-        p.vt_out[size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + pos] = row[p.v_off + idx];
+}
+
+// V -> V^T: a 64-token x 64-feature tile goes through LDS so that both the reads (token rows) and the
+// writes (feature rows of the transposed cache, 64 consecutive positions = 128 bytes) are contiguous.
+__global__ __launch_bounds__(256) void v_transpose_kernel(QkvPostArgs p) {
+    __shared__ bf16_t tile[64][66];
+    const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;          // first token / first column of V (= g*dh + e)
+    const int ncol = p.Hkv * p.dh;
+    for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+        const int r = idx >> 6, c = idx & 63;
+        bf16_t v = 0;
+        if (t0 + r < p.T && c0 + c < ncol) v = p.qkv[size_t(t0 + r) * p.n_qkv + p.v_off + c0 + c];
+        tile[r][c] = v;
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
+        const int c = idx >> 6, r = idx & 63;                       // consecutive threads -> consecutive positions
+        const int col = c0 + c;
+        if (t0 + r < p.T && col < ncol) {
+            const int g = col / p.dh, e = col % p.dh;
+            p.vt_out[size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + p.pos0 + t0 + r] = tile[r][c];
+        }
     }
 }
 
@@ -248,7 +263,8 @@ void add_time_embedding(const float* x, float* y, float tval, int T, int d, hipS
 
 void qkv_post(const QkvPostArgs& a, hipStream_t st) {
     if (a.T <= 0) return;
-    hipLaunchKernelGGL(qkv_post_kernel, dim3(a.T), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(rope_kernel, dim3(a.T), dim3(256), 0, st, a);
+    hipLaunchKernelGGL(v_transpose_kernel, dim3((a.T + 63) / 64, (a.Hkv * a.dh + 63) / 64), dim3(256), 0, st, a);
 }
 
 void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_host, float* x_out, hipStream_t st) {
