@@ -45,7 +45,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, g2 = lane >> 5;
     const int group = p.Hq / p.Hkv;
-    const int q0 = blockIdx.x * QB;
+    // causal passes: the last query blocks see the most keys; launch them first so the tail of the grid is short
+    const int q0 = (p.causal ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x)) * QB;
     const int h = HEADS ? blockIdx.y * 4 + wave : blockIdx.y;
     const int kvh = h / group;
     const int wq0 = HEADS ? q0 : q0 + 32 * wave;       // first query of this wavefront
