@@ -236,7 +236,9 @@ typedef struct {
     double flops;
     double bytes;
 } dl_kernel_time;
-int32_t dl_set_kernel_timing(dl_ctx* ctx, int32_t on);
+/* mask: bit k set = time launches of class k (DL_K_*); 0 = off; -1 = every class.  Each timed launch costs
+ * two event records on the compute stream, which drain the queue between kernels (a few microseconds each). */
+int32_t dl_set_kernel_timing(dl_ctx* ctx, int32_t mask);
 /* synchronises; out: host array [DL_K_COUNT], entry i describes kind i; resets the accumulation */
 int32_t dl_collect_kernel_times(dl_ctx* ctx, dl_kernel_time* out);
 

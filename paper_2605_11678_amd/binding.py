@@ -296,8 +296,12 @@ class Context:
         d["records"] = [{f: getattr(recs[i], f) for f, _ in dl_layer_record._fields_} for i in range(n)]
         return d
 
-    def set_kernel_timing(self, on):
-        self._ck(lib().dl_set_kernel_timing(self._h, int(on)))
+    def set_kernel_timing(self, on, kinds=None):
+        """on False: off.  on True: every kernel class, or only the DL_K_* ids listed in `kinds`."""
+        mask = 0
+        if on:
+            mask = -1 if kinds is None else sum(1 << int(k) for k in kinds)
+        self._ck(lib().dl_set_kernel_timing(self._h, mask))
 
     def collect_kernel_times(self):
         out = (dl_kernel_time * len(DL_K_NAMES))()

@@ -69,7 +69,7 @@ struct dl_ctx {
     int32_t last_copy_in_slot[2] = {-1, -1};
     std::vector<hipEvent_t> ev_pool;
     size_t ev_next = 0;
-    bool ktiming = false;
+    uint32_t ktiming = 0;   // bit k set: launches of kernel class k are bracketed with events
     struct KRec { int32_t kind; hipEvent_t e0, e1; double flops, bytes; };
     std::vector<KRec> krecs;
 };
@@ -228,7 +228,7 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     // optional per-kernel timing: events around each launch, work counted algorithmically
     dl_ctx::KRec* open_rec = nullptr;
     auto kbegin = [&](int32_t kind, double flops, double bytes) {
-        if (!c->ktiming) return;
+        if (!((c->ktiming >> kind) & 1u)) return;
         hipEvent_t e0 = nullptr, e1 = nullptr;
         if (timing_event(c, &e0) != DL_OK || timing_event(c, &e1) != DL_OK) return;
         c->krecs.push_back({kind, e0, e1, flops, bytes});
@@ -1065,7 +1065,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
 int32_t dl_set_kernel_timing(dl_ctx* c, int32_t on) {
     int32_t rc = enter(c);
     if (rc) return rc;
-    c->ktiming = on != 0;
+    c->ktiming = uint32_t(on);
     return DL_OK;
 }
 

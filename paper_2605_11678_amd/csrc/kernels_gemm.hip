@@ -9,14 +9,14 @@
 //
 //  * gemm_fast<BM,BN,EPI> — the production path for K % 128 == 0.  One workgroup per CU (256 threads =
 //    4 wavefronts in a 2x2 grid, each owning a (BM/2)x(BN/2) tile, i.e. up to 4x4 MFMA tiles = 256 fp32
-//    accumulators per lane).  K step 64.  Tiles go global -> LDS directly (global_load_lds_dwordx4, no
-//    staging registers) into two LDS stages that are separate arrays, so the compiler can tell the
-//    in-flight stage from the one being read and waits for the copies only at the barrier.  LDS rows
-//    are 128 bytes, unpadded (a wavefront's copy fills 1 KB contiguously); the 16-byte chunk index is
-//    XOR-swizzled with (row/2)%8 on both sides, which keeps the 64-lane b128 fragment reads conflict-free.
-//    Per K step four phases of 16 MFMAs; fragment reads, copies and MFMAs of different phases are
-//    interleaved through sched_group_barrier, and the stage barrier sits before the last MFMA phase so
-//    that the first fragment reads of the next stage hide behind it.
+//    accumulators per lane).  K step 32.  Tiles go global -> LDS directly (global_load_lds_dwordx4, no
+//    staging registers) into four LDS stages that are separate arrays, so the compiler can tell the
+//    in-flight stages from the one being read; the wait for a copy is an explicit s_waitcnt vmcnt(n) that
+//    leaves the younger copies (up to three k-tiles ahead) in flight.  LDS rows are 64 bytes, unpadded
+//    (a wavefront's copy fills 1 KB contiguously); the 16-byte chunk index is XOR-swizzled with (row/4)%4
+//    on both sides, which keeps the 64-lane b128 fragment reads conflict-free.  Per K step two phases of
+//    16 MFMAs; fragment reads, copies and MFMAs are interleaved through sched_group_barrier so that the
+//    vector-memory path sees an even one copy per four MFMAs, and one bare s_barrier per K step.
 //  * gemm_generic<EPI> — any shape (K % 8 == 0): 128x128 tile, 64x64 per wavefront, register-staged.
 //
 // Accumulator layout of a 32x32 tile: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.
@@ -249,13 +249,22 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int* 
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
                                      (__attribute__((address_space(3))) void*)(l), 16, 0, 0)
 
+// s_waitcnt with an explicit vector-memory count (6 bits, split 4 + 2 in the gfx9 encoding); expcnt is left
+// unconstrained, lgkmcnt is either unconstrained or zero
+#define DL_WAIT_VM(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
+#define DL_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0x0 << 8))
+
 template <int BM, int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
-    constexpr int BK = 64;
+    constexpr int BK = 32;
     constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;
-    constexpr int JA = BM / 32, JB = BN / 32;            // 1 KB copy blocks per wavefront and tile
+    constexpr int JA = BM / 64, JB = BN / 64;            // 1 KB copy blocks (16 rows x 64 B) per wavefront and k-tile
+    constexpr int NL = JA + JB;
+    static_assert(3 * NL < 64, "outstanding copies must fit the vmcnt field");
     __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * BK];
     __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * BK];
+    __shared__ __attribute__((aligned(1024))) bf16_t S2[(BM + BN) * BK];
+    __shared__ __attribute__((aligned(1024))) bf16_t S3[(BM + BN) * BK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
@@ -271,28 +280,28 @@ __global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // copy sources: block b = wave + 4*j of a tile holds rows 8b..8b+7; lane L lands at row 8b + L/8,
-    // physical chunk L%8, and therefore fetches logical chunk (L%8) ^ swizzle(row).  Rows past the
+    // copy sources: block b = wave + 4*j of a tile holds rows 16b..16b+15; lane L lands at row 16b + L/4,
+    // physical chunk L%4, and therefore fetches logical chunk (L%4) ^ swizzle(row).  Rows past the
     // matrix edge are clamped: they produce values that the epilogue never stores.
     uint32_t offA[JA], offB[JB];
 #pragma unroll
     for (int j = 0; j < JA; ++j) {
-        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = 16 * (wave + 4 * j) + (lane >> 2), lc = (lane & 3) ^ ((row >> 2) & 3);
         offA[j] = uint32_t((size_t(min(m0 + row, p.M - 1)) * p.lda + lc * 8) * 2);
     }
 #pragma unroll
     for (int j = 0; j < JB; ++j) {
-        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
+        const int row = 16 * (wave + 4 * j) + (lane >> 2), lc = (lane & 3) ^ ((row >> 2) & 3);
         offB[j] = uint32_t((size_t(min(n0 + row, p.N - 1)) * p.ldb + lc * 8) * 2);
     }
     const char* gA = reinterpret_cast<const char*>(p.A);
     const char* gB = reinterpret_cast<const char*>(p.B);
     // fragment read offsets (elements) inside a stage, one per 16-wide k step
     const int lr = lane & 31, g2 = lane >> 5;
-    int rdA[4], rdB[4];
+    int rdA[2], rdB[2];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        const int pc = (2 * kk + g2) ^ ((lr >> 1) & 7);
+    for (int kk = 0; kk < 2; ++kk) {
+        const int pc = (2 * kk + g2) ^ ((lr >> 2) & 3);
         rdA[kk] = ((BM / 2) * wm + lr) * BK + pc * 8;
         rdB[kk] = BM * BK + ((BN / 2) * wn + lr) * BK + pc * 8;
     }
@@ -319,50 +328,62 @@ __global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     };
-    // ask the scheduler for: 2 MFMA, 1 LDS read, (1 global->LDS copy) repeated over the phase
-    auto interleave = [&](bool with_copy) {
+    // ask the scheduler for: 2 MFMA, 1 LDS read, and for the first ncopy groups 1 global->LDS copy
+    auto interleave = [&](int ncopy) {
 #pragma unroll
         for (int g = 0; g < TM * TN / 2; ++g) {
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (with_copy) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            if (g < ncopy) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int nk = p.K / BK;                             // host guarantees K % 128 == 0: nk is even, >= 2
-    copyA(S0, 0);
-    copyB(S0, 0);
-    __syncthreads();
+    const int nk = p.K / BK;                             // host guarantees K % 128 == 0: nk is a multiple of 4
+    copyA(S0, 0); copyB(S0, 0);
+    copyA(S1, 1); copyB(S1, 1);
+    copyA(S2, 2); copyB(S2, 2);
+    DL_WAIT_VM(2 * NL);                                  // k-tile 0 has landed (this wavefront's share)
+    __builtin_amdgcn_s_barrier();
     ldfrag(a0, b0, S0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    auto ktile = [&](const bf16_t* cur, bf16_t* nxt, int kt, auto more_c) {
-        constexpr bool MORE = decltype(more_c)::value;
+    // One k-tile = two phases of TM*TN MFMAs.  In steady state (AHEAD == 3) the copy of k-tile kt+3 goes into
+    // the stage that k-tile kt-1 was read from, its A half spread over the first phase, its B half over the
+    // second, so that the vector-memory path sees one copy per four MFMAs throughout.  The barrier between the
+    // phases is preceded by a wait for this wavefront's share of k-tile kt+1 and for all of its own LDS reads;
+    // past it (a) k-tile kt+1 has landed for everyone and (b) nobody reads stage kt any more after the reads
+    // already returned, so the copy issued in the next k-tile may overwrite it.
+    auto ktile = [&](const bf16_t* cur, const bf16_t* nxt, bf16_t* fill, int kt, auto ahead_c) {
+        constexpr int AHEAD = decltype(ahead_c)::value;  // 3: steady state; 2, 1, 0: tail, nothing left to copy
         ldfrag(a1, b1, cur, 1);
-        if (MORE) copyA(nxt, kt + 1);
+        if (AHEAD == 3) copyA(fill, kt + 3);
         mma(a0, b0);
-        interleave(MORE);
-        ldfrag(a0, b0, cur, 2);
-        if (MORE) copyB(nxt, kt + 1);
+        interleave(AHEAD == 3 ? JA : 0);
+        if (AHEAD >= 1) {
+            // k-tile kt+1 must have landed; younger copies may stay in flight: A and B of kt+2, A of kt+3
+            if (AHEAD == 3) DL_WAIT_VM_LGKM0(JA + NL);
+            else if (AHEAD == 2) DL_WAIT_VM_LGKM0(NL);
+            else DL_WAIT_VM_LGKM0(0);
+            __builtin_amdgcn_s_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            ldfrag(a0, b0, nxt, 0);
+        }
+        if (AHEAD == 3) copyB(fill, kt + 3);
         mma(a1, b1);
-        interleave(MORE);
-        ldfrag(a1, b1, cur, 3);
-        mma(a0, b0);
-        interleave(false);
-        __syncthreads();      // copies into nxt have landed; every wavefront has finished reading cur
-        if (MORE) ldfrag(a0, b0, nxt, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mma(a1, b1);
-        __builtin_amdgcn_sched_barrier(0);
+        interleave(AHEAD == 3 ? JB : 0);
     };
     int kt = 0;
-    for (; kt + 2 < nk; kt += 2) {
-        ktile(S0, S1, kt, std::true_type{});
-        ktile(S1, S0, kt + 1, std::true_type{});
+    for (; kt + 4 < nk; kt += 4) {
+        ktile(S0, S1, S3, kt, std::integral_constant<int, 3>{});
+        ktile(S1, S2, S0, kt + 1, std::integral_constant<int, 3>{});
+        ktile(S2, S3, S1, kt + 2, std::integral_constant<int, 3>{});
+        ktile(S3, S0, S2, kt + 3, std::integral_constant<int, 3>{});
     }
-    ktile(S0, S1, kt, std::true_type{});
-    ktile(S1, S0, kt + 1, std::false_type{});
+    ktile(S0, S1, S3, kt, std::integral_constant<int, 3>{});
+    ktile(S1, S2, S0, kt + 1, std::integral_constant<int, 2>{});
+    ktile(S2, S3, S1, kt + 2, std::integral_constant<int, 1>{});
+    ktile(S3, S0, S2, kt + 3, std::integral_constant<int, 0>{});
 
     store_tiles<EPI, TM, TN>(p, acc, m0 + (BM / 2) * wm, n0 + (BN / 2) * wn, lane);
 }
