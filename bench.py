@@ -46,6 +46,7 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
     c_dma = [p["c_dma_ms"] for p in prof]
     c_exe = [p["c_exe_ms"] for p in prof]
     c_hot = [p["c_exe_hot_ms"] for p in prof]
+    c_fence = [p["c_fence_ms"] for p in prof]
     res = {"profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_exe_ms": round(float(np.mean(c_exe)), 4),
                        "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
                        "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 1),
@@ -89,7 +90,7 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
         streamed = [i not in rs for i in range(L)] * steps
         starts = [i == 0 for i in range(L)] * steps
         return B.timeline(c_dma * steps, c_hot * steps, streamed, starts, wrap_prefetch=wrap,
-                          c_exe_idle_ms=c_exe * steps)["total"] / steps + head_ms
+                          c_exe_idle_ms=c_exe * steps, c_fence_ms=c_fence * steps)["total"] / steps + head_ms
 
     def fit_count():
         for k in range(L, -1, -1):
@@ -151,6 +152,7 @@ def vit_leg(B, CFG, Engine, torch, log):
     c_dma = [p["c_dma_ms"] for p in prof]
     c_exe = [p["c_exe_ms"] for p in prof]
     c_hot = [p["c_exe_hot_ms"] for p in prof]
+    c_fence = [p["c_fence_ms"] for p in prof]
     rows = []
     for k in (0, 7, 14, 20, 24, 27):
         res = B.place_interleaved(L, k)
@@ -172,7 +174,7 @@ def vit_leg(B, CFG, Engine, torch, log):
         ctx.set_timing(False)
         rs = set(res)
         pred = B.timeline(c_dma, c_hot, [i not in rs for i in range(L)], [i == 0 for i in range(L)],
-                          c_exe_idle_ms=c_exe)["total"]
+                          c_exe_idle_ms=c_exe, c_fence_ms=c_fence)["total"]
         rows.append({"k": k, "measured_ms": round(ms, 3), "predicted_ms": round(pred, 3),
                      "pred_err_pct": round((pred - ms) / ms * 100, 2), "hidden_frac": round(st["hidden_frac"], 4),
                      "h2d_gbps": round(st["h2d_gbps"], 2)})
@@ -183,7 +185,8 @@ def vit_leg(B, CFG, Engine, torch, log):
     out = {"workload": "configs[1]: 27-layer d=1152 encoder (16x72 heads, GELU MLP 4304, LayerNorm, biases), T=4096",
            "layer_bytes": packed,
            "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_exe_ms": round(float(np.mean(c_exe)), 4),
-                       "c_exe_hot_ms": round(float(np.mean(c_hot)), 4), "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 2)},
+                       "c_exe_hot_ms": round(float(np.mean(c_hot)), 4), "c_fence_ms": round(float(np.mean(c_fence)), 4),
+                       "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 2)},
            "sweep": rows, "layer_flop": flops_layer,
            "resident_tflops": round(flops_layer * L / (rows[-1]["measured_ms"] * 1e-3) / 1e12, 1)}
     eng.close()
@@ -217,7 +220,8 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     P["action"] = ctx.profile(pipe.m_act, Ls[2], 64, 0, pipe.p_ain, iters=3, ctx_ptr=pipe.p_ctx, n_ctx=pipe.n_prefill)
     mean = lambda rows, key: float(np.mean([r[key] for r in rows]))
     prof = {k: {"c_dma_ms": round(mean(v, "c_dma_ms"), 4), "c_exe_ms": round(mean(v, "c_exe_ms"), 4),
-                "c_exe_hot_ms": round(mean(v, "c_exe_hot_ms"), 4)} for k, v in P.items()}
+                "c_exe_hot_ms": round(mean(v, "c_exe_hot_ms"), 4), "c_fence_ms": round(mean(v, "c_fence_ms"), 4)}
+            for k, v in P.items()}
     MiB = float(1 << 20)
     b3 = [B.benefit(prof["vit"]["c_dma_ms"], sizes[0] / MiB, [prof["vit"]["c_exe_ms"]], [1]),
           B.benefit(prof["prefill"]["c_dma_ms"], sizes[1] / MiB, [prof["prefill"]["c_exe_ms"], prof["decode"]["c_exe_ms"]],
@@ -229,6 +233,19 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     log("vla benefit (ms/MiB) first/mid/last: vit %s, decoder %s, action %s; budget %.2f GB -> k = %s" %
         (np.round(b3[0], 4).tolist(), np.round(b3[1], 4).tolist(), np.round(b3[2], 4).tolist(), budget / 1e9, k_plan))
 
+    # benefit per MiB as a function of the decode length N and of the number of Euler steps (Sec. IV-D: the
+    # ranking of the modules, and with it the plan, depends on how often each module's layers are invoked)
+    def b3_for(n_dec, n_eul):
+        return [B.benefit(prof["vit"]["c_dma_ms"], sizes[0] / MiB, [prof["vit"]["c_exe_ms"]], [1]),
+                B.benefit(prof["prefill"]["c_dma_ms"], sizes[1] / MiB,
+                          [prof["prefill"]["c_exe_ms"], prof["decode"]["c_exe_ms"]], [1, n_dec]),
+                B.benefit(prof["action"]["c_dma_ms"], sizes[2] / MiB, [prof["action"]["c_exe_ms"]], [n_eul])]
+    crossover = []
+    for n_dec, n_eul in [(0, 10), (1, 10), (4, 10), (15, 10), (21, 10), (64, 10), (256, 10), (1024, 10), (64, 1), (64, 4), (64, 20), (64, 50)]:
+        bb = b3_for(n_dec, n_eul)
+        crossover.append({"n_decode": n_dec, "n_euler": n_eul, "b_mid_ms_per_MiB_vit_dec_act": [round(float(b[1]), 5) for b in bb],
+                          "k_vit_dec_act": B.plan(Ls, sizes, [list(b) for b in bb], budget)})
+
     # greedy head per token (resident, outside the layer passes)
     ctx.sync()
     t = time.perf_counter()
@@ -238,10 +255,10 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     head_ms = (time.perf_counter() - t) * 1e3 / 30
 
     def predict(ks, wrap):
-        dma, hot, idle, streamed, starts, mids = [], [], [], [], [], []
+        dma, hot, idle, fence, streamed, starts, mids = [], [], [], [], [], [], []
         def add_pass(mi, rows, res):
             for i, r in enumerate(rows):
-                dma.append(r["c_dma_ms"]); hot.append(r["c_exe_hot_ms"]); idle.append(r["c_exe_ms"])
+                dma.append(r["c_dma_ms"]); hot.append(r["c_exe_hot_ms"]); idle.append(r["c_exe_ms"]); fence.append(r["c_fence_ms"])
                 streamed.append(i not in res); starts.append(i == 0); mids.append(mi)
         rs = [set(B.place_interleaved(Ls[m], ks[m])) for m in range(3)]
         add_pass(0, P["vit"], rs[0])
@@ -250,7 +267,8 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
             add_pass(1, P["decode"], rs[1])
         for _ in range(10):
             add_pass(2, P["action"], rs[2])
-        return B.timeline(dma, hot, streamed, starts, module_id=mids, wrap_prefetch=wrap, c_exe_idle_ms=idle)["total"] \
+        return B.timeline(dma, hot, streamed, starts, module_id=mids, wrap_prefetch=wrap, c_exe_idle_ms=idle,
+                          c_fence_ms=fence)["total"] \
             + head_ms * n_decode
 
     def measure(ks, wrap, reps):
@@ -295,6 +313,7 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
                        "steps on 64 tokens; cap %.3g B" % (n_decode, cap),
            "layer_bytes": sizes, "profile": prof, "benefit_ms_per_MiB": [np.round(b, 5).tolist() for b in b3],
            "budget_gb": round(budget / 1e9, 3), "head_ms": round(head_ms, 4), "runs": rows,
+           "benefit_vs_decode_length_and_euler_steps": crossover,
            "trajectory_finite": bool(np.all(np.isfinite(ref["trajectory"]))) if ref else None}
     eng.close()
     return res
@@ -351,6 +370,7 @@ def main():
     c_dma = [p["c_dma_ms"] for p in prof]
     c_exe = [p["c_exe_ms"] for p in prof]              # right after the copy (GPU was idle): the paper's C_EXE
     c_hot = [p["c_exe_hot_ms"] for p in prof]          # the same layer re-run at once (GPU busy)
+    c_fence = [p["c_fence_ms"] for p in prof]          # cross-stream hand-offs of a streamed layer
     log("profile: C_DMA %.3f ms  C_EXE %.3f ms (%.3f ms when compute is continuous) per layer (means), r = %.2f" %
         (np.mean(c_dma), np.mean(c_exe), np.mean(c_hot), np.mean(c_dma) / np.mean(c_exe)))
 
@@ -372,7 +392,8 @@ def main():
     def predict(k, mode=B.DL_MODE_PIPELINED):
         res = set(B.place_interleaved(L, k))
         streamed = [i not in res for i in range(L)]
-        return B.timeline(c_dma, c_hot, streamed, [i == 0 for i in range(L)], mode=mode, c_exe_idle_ms=c_exe)
+        return B.timeline(c_dma, c_hot, streamed, [i == 0 for i in range(L)], mode=mode, c_exe_idle_ms=c_exe,
+                          c_fence_ms=c_fence)
 
     # ---- largest resident count the arena holds ----
     k_best = None
@@ -435,6 +456,37 @@ def main():
                    "gbps": round(v["bytes"] / (v["total_ms"] * 1e-3) / 1e9, 1) if v["total_ms"] > 0 else None}
                for k, v in kt.items() if v["launches"]}
 
+    # ---- the box's own ceilings, measured in this run ----
+    # register-only MFMA rate (zero operands and hashed +-[1,2) operands: the chip is power-limited, the rate depends
+    # on operand toggling), and the best pinned host-to-device copy of 1 GiB on the copy stream
+    peaks = {}
+    try:
+        peaks["mfma_zero_operands_tflops"] = round(ctx.probe_mfma_rate(0), 1)
+        peaks["mfma_random_operands_tflops"] = round(ctx.probe_mfma_rate(1), 1)
+        hsrc = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+        hsrc.zero_()
+        ddst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        best = 1e30
+        for _ in range(3):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            with torch.cuda.stream(eng.s_copy):
+                e0.record()
+                ddst.copy_(hsrc, non_blocking=True)
+                e1.record()
+            eng.s_copy.synchronize()
+            best = min(best, e0.elapsed_time(e1))
+        peaks["h2d_1gib_gbps"] = round((1 << 30) / (best * 1e6), 2)
+        del hsrc, ddst
+    except B.DLError as e:
+        peaks["error"] = str(e)
+    log("box ceilings: %s" % peaks)
+
+    flops_layer = 2.0 * T * c.d_model * (c.n_q_heads * c.d_head + 2 * c.n_kv_heads * c.d_head) \
+        + 2.0 * T * c.d_model * c.n_q_heads * c.d_head + 6.0 * T * c.d_model * c.d_ff \
+        + 4.0 * c.d_head * c.n_q_heads * (T * (T + 1) / 2.0)
+    roof_dma = [packed / (LINK_GBPS_THEORY * 1e6)] * L          # ms per layer at the link's theoretical rate
+    roof_exe = [flops_layer / (PEAK_BF16_TFLOPS * 1e9)] * L     # ms per layer at the vendor MFMA peak
+
     # ---- residency sweep: measured vs predicted, hidden fraction, link rate ----
     sweep = []
     ks = sorted({min(max(int(s), 0), L) for s in args.sweep.split(",") if s.strip() != ""})
@@ -469,6 +521,10 @@ def main():
                "hidden_frac": round(st["hidden_frac"], 4), "hideable_frac": round(hideable, 4),
                "h2d_gbps": round(st["h2d_gbps"], 2), "timed_pass_ms": round(st["total_ms"], 3),
                "exe_ms_per_layer": round(st["exe_ms"] / L, 4), "arena_gb": round(ctx.arena_stats()["used"] / 1e9, 3)}
+        res_k = set(B.place_interleaved(L, k))
+        roof = B.timeline(roof_dma, roof_exe, [i not in res_k for i in range(L)], [i == 0 for i in range(L)])["total"]
+        row["roofline_ms"] = round(roof, 3)
+        row["roofline_frac"] = round(roof / meas, 4)
         if c_total0 is not None:
             # Eq. 9 with the slope taken from the profile alone (DMA-intensive, R = 1: one C_DMA per layer)
             lin = B.predict_linear(c_total0, float(np.mean(c_dma)), k)
@@ -521,9 +577,6 @@ def main():
         cpu = {"value": round(dt / n_samp * L * 1e3, 1), "unit": "ms", "cores": int(cores), "kind": "oracle",
                "sample": "%d of %d layers at T=%d in fp64 numpy (%.1f s), scaled to %d layers" % (n_samp, L, T, dt, L)}
 
-    flops_layer = 2.0 * T * c.d_model * (c.n_q_heads * c.d_head + 2 * c.n_kv_heads * c.d_head) \
-        + 2.0 * T * c.d_model * c.n_q_heads * c.d_head + 6.0 * T * c.d_model * c.d_ff \
-        + 4.0 * c.d_head * c.n_q_heads * (T * (T + 1) / 2.0)
     out = {
         "metric": "ms/inference under VRAM cap", "value": round(ms_per_step, 3), "unit": "ms",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
@@ -534,11 +587,15 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "mfma_util": round(mfma_util, 4),
+        "mfma_util_vs_measured_peak": round(mfma_util * PEAK_BF16_TFLOPS / peaks["mfma_random_operands_tflops"], 4)
+        if peaks.get("mfma_random_operands_tflops") else None,
+        "box_ceilings": peaks,
         "layer_flop": flops_layer,
         "inference_tflops": round(flops_layer * L / (ms_per_step * 1e-3) / 1e12, 2),
         "kernels": kernels,
         "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_exe_ms": round(float(np.mean(c_exe)), 4),
                     "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
+                    "c_fence_ms": round(float(np.mean(c_fence)), 4),
                     "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 3),
                     "h2d_gbps": round(packed / (float(np.mean(c_dma)) * 1e6), 2),
                     "h2d_frac_of_63GBps": round(packed / (float(np.mean(c_dma)) * 1e6) / LINK_GBPS_THEORY, 3)},

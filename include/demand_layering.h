@@ -140,9 +140,15 @@ int32_t dl_get_residency(const dl_ctx* ctx, int32_t module, int32_t* idx_out, in
  * module's pass simply re-issues its own first copy). */
 int32_t dl_set_mode(dl_ctx* ctx, int32_t mode, int32_t wrap_prefetch);
 
+/* How many passes the host may have enqueued and unfinished (1..8; 0 = no limit).  Default 1: each further pass of
+ * short streamed layers in flight slowed copies and kernels on MI355X (+4 % with two, +25 % with four). */
+int32_t dl_set_run_ahead(dl_ctx* ctx, int32_t passes);
+
 /* ---- the hot path (Sec. IV-C) ------------------------------------------------------------ */
 
-/* One pass over all layers of `module`; enqueues only, returns before the GPU finishes.
+/* One pass over all layers of `module`; enqueues only, returns before the GPU finishes, except that the host
+ * never has more than dl_set_run_ahead passes (default one) unfinished: the call first waits for the pass that
+ * many calls back.
  * x_dev: device fp32 [n_tokens, d_model] input;  y_dev: device fp32 [n_tokens, d_model] output
  * (may equal x_dev).  Token t sits at absolute position pos0 + t; with a KV cache the pass appends
  * its keys/values at those positions and attends over 0 .. pos0+t.  pos0 must be 0 without a cache.
@@ -188,6 +194,9 @@ typedef struct {
     double c_exe_ms;      /* un-overlapped execution time of the layer, run right after its copy (the GPU was idle) */
     double c_exe_hot_ms;  /* execution time of the layer inside an uninterrupted run of all layers (no copies, no
                              idle gaps): what a layer costs when compute is continuous, e.g. between resident layers */
+    double c_fence_ms;    /* the two cross-stream hand-offs of a streamed layer (copy end -> its first kernel, its last
+                             kernel -> next copy start) as the sequential run shows them; charged to the compute
+                             stream per streamed layer by dl_timeline */
     uint64_t bytes;       /* bytes one copy moves */
 } dl_layer_profile;
 
@@ -242,6 +251,13 @@ int32_t dl_set_kernel_timing(dl_ctx* ctx, int32_t mask);
 /* synchronises; out: host array [DL_K_COUNT], entry i describes kind i; resets the accumulation */
 int32_t dl_collect_kernel_times(dl_ctx* ctx, dl_kernel_time* out);
 
+/* Diagnostic, not an operation of the paper: the chip's sustained BF16 matrix-core rate with operands held in
+ * registers (one workgroup of four wavefronts per compute unit, 16 independent 32x32x16 accumulator tiles each),
+ * the denominator for a measured-peak MFMA utilisation.  pattern 0: zero operands, 1: hashed values in +-[1,2)
+ * (the rate depends on operand toggling because the chip is power-limited).  Takes blocks*1024 bytes from the arena
+ * for the duration of the call, launches on the compute stream, synchronises it, writes TFLOP/s to *tflops_out. */
+int32_t dl_probe_mfma_rate(dl_ctx* ctx, int32_t pattern, int32_t iters, double* tflops_out);
+
 /* The schedule one forward pass enqueues, as data (also recorded by host-only contexts). */
 enum { DL_OP_WAIT = 0, DL_OP_RECORD = 1, DL_OP_COPY = 2, DL_OP_EXEC = 3 };
 enum { DL_EV_DMA_DONE = 0, DL_EV_COMPUTE_DONE = 1, DL_EV_PASS_DONE = 2 };
@@ -282,12 +298,13 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * layer of a pass; module_id[j] (NULL = all the same) tells passes over different stacks apart.
  * c_exe_idle_ms (NULL = same as c_exe_ms): time of invocation j when the compute queue sat idle
  * waiting for its copy right before it (a GPU that idled runs the next kernels slower than one
- * kept busy; dl_profile measures both).
+ * kept busy; dl_profile measures both).  c_fence_ms (NULL = zeros): time added on the compute queue to
+ * every streamed invocation for its two cross-stream hand-offs (dl_profile's c_fence_ms).
  * mode, wrap_prefetch: as dl_set_mode.  overhead_ms is added to every execution (fixed
  * host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
  * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
 int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
-                    const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+                    const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
                     int32_t mode, int32_t wrap_prefetch, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms);
 

@@ -103,10 +103,22 @@ def predict_linear(C_total_0, k, B_VLM, M_VLM):
 
 
 # ---- Sec. IV-C(ii) as arithmetic -----------------------------------------------
-def timeline(invocations, wrap_prefetch=False, n_slots=2):
-    """invocations: list of passes over a layer stack, each a list of layer records
-    (C_DMA, C_EXE, streamed).  One copy queue and one compute queue; the j-th streamed
-    layer uses slot j mod n_slots (ordinal among streamed layers, counted across passes).
+def _layer_terms(rec):
+    """A layer record is (C_DMA, C_EXE, streamed) or, with the measured corrections of the MI355X build,
+    (C_DMA, C_EXE, streamed, C_EXE_idle, C_fence):
+      C_EXE_idle  execution time of the layer when the compute queue had to wait for its transfer
+                  (the GPU was idle just before; the paper's profiling run measures exactly this);
+      C_fence     time the two cross-queue hand-offs of a streamed layer add on the compute queue."""
+    if len(rec) == 3:
+        C_DMA, C_EXE, streamed = rec
+        return C_DMA, C_EXE, streamed, C_EXE, 0.0
+    return rec
+
+
+def timeline(invocations, wrap_prefetch=False, n_slots=2, overhead=0.0):
+    """invocations: list of passes over a layer stack, each a list of layer records (see _layer_terms).
+    One copy queue and one compute queue; the j-th streamed layer uses slot j mod n_slots (ordinal among
+    streamed layers, counted across passes).
 
       DMA-done:      a streamed layer starts executing only after its transfer ended;
       compute-done:  a transfer into a slot starts only after the layer that last
@@ -117,6 +129,9 @@ def timeline(invocations, wrap_prefetch=False, n_slots=2):
     (after the previous pass's last layer ended) — the per-pass restart that Eq. 6
     and the "last" rows of Tables V and VI assume.  With it, the transfer is issued as soon
     as the queues allow.
+
+    A layer occupies the compute queue for C_EXE (C_EXE_idle if the queue waited for its transfer)
+    + C_fence (streamed layers only) + overhead (every layer).
 
     Returns dict(total, exposed, dma, hidden): total time, summed exposed transfer time (time
     the compute queue sat idle waiting for a transfer), summed transfer time, 1 - exposed/dma."""
@@ -129,7 +144,8 @@ def timeline(invocations, wrap_prefetch=False, n_slots=2):
     for layers in invocations:
         pass_begin = exe_end_prev
         first_streamed = True
-        for (C_DMA, C_EXE, streamed) in layers:
+        for rec in layers:
+            C_DMA, C_EXE, streamed, C_EXE_idle, C_fence = _layer_terms(rec)
             if streamed:
                 s = ordinal % n_slots
                 ordinal += 1
@@ -141,15 +157,22 @@ def timeline(invocations, wrap_prefetch=False, n_slots=2):
                 dma_end_prev = dma_end
                 dma_sum += C_DMA
                 exposed += max(0.0, dma_end - max(exe_end_prev, dma_start))
+                waited = dma_end > exe_end_prev
                 exe_start = max(exe_end_prev, dma_end)
-                exe_end_prev = exe_start + C_EXE
+                exe_end_prev = exe_start + (C_EXE_idle if waited else C_EXE) + C_fence + overhead
                 slot_free[s] = exe_end_prev
             else:
-                exe_end_prev = exe_end_prev + C_EXE
+                exe_end_prev = exe_end_prev + C_EXE + overhead
     hidden = 1.0 - exposed / dma_sum if dma_sum > 0 else 1.0
     return dict(total=exe_end_prev, exposed=exposed, dma=dma_sum, hidden=hidden)
 
 
-def sequential_time(invocations):
-    """Sequential Demand Layering (Sec. IV-B): transfer and execution strictly alternate."""
-    return sum((C_DMA if streamed else 0.0) + C_EXE for layers in invocations for (C_DMA, C_EXE, streamed) in layers)
+def sequential_time(invocations, overhead=0.0):
+    """Sequential Demand Layering (Sec. IV-B): transfer and execution strictly alternate, so every streamed
+    layer finds the compute queue waiting for it."""
+    total = 0.0
+    for layers in invocations:
+        for rec in layers:
+            C_DMA, C_EXE, streamed, C_EXE_idle, C_fence = _layer_terms(rec)
+            total += (C_DMA + C_EXE_idle + C_fence if streamed else C_EXE) + overhead
+    return total

@@ -33,7 +33,8 @@ class dl_module_desc(C.Structure):
 
 
 class dl_layer_profile(C.Structure):
-    _fields_ = [("c_dma_ms", C.c_double), ("c_exe_ms", C.c_double), ("c_exe_hot_ms", C.c_double), ("bytes", C.c_uint64)]
+    _fields_ = [("c_dma_ms", C.c_double), ("c_exe_ms", C.c_double), ("c_exe_hot_ms", C.c_double),
+                ("c_fence_ms", C.c_double), ("bytes", C.c_uint64)]
 
 
 class dl_run_stats(C.Structure):
@@ -98,6 +99,8 @@ SIGNATURES = {
     "dl_set_timing": (_i32, [_p, _i32]),
     "dl_collect_stats": (_i32, [_p, C.POINTER(dl_run_stats), C.POINTER(dl_layer_record), _i32]),
     "dl_set_kernel_timing": (_i32, [_p, _i32]),
+    "dl_set_run_ahead": (_i32, [_p, _i32]),
+    "dl_probe_mfma_rate": (_i32, [_p, _i32, _i32, C.POINTER(C.c_double)]),
     "dl_collect_kernel_times": (_i32, [_p, C.POINTER(dl_kernel_time)]),
     "dl_trace_enable": (_i32, [_p, _i32]),
     "dl_trace_read": (_i32, [_p, C.POINTER(dl_trace_op), _i32, _PI32]),
@@ -105,7 +108,7 @@ SIGNATURES = {
     "dl_benefit": (_i32, [_f64, _f64, _i32, _PF64, _PI32, _PF64]),
     "dl_consecutive_limit": (_i32, [_f64, _f64, _PI32]),
     "dl_predict_linear": (_i32, [_f64, _f64, _i32, _PF64]),
-    "dl_timeline": (_i32, [_PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
+    "dl_timeline": (_i32, [_PF64, _PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
                            _f64, _PF64, _PF64, _PF64]),
     "dl_plan": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _PI32]),
 }
@@ -282,7 +285,8 @@ class Context:
     def profile(self, module, n_layers, n_tokens, pos0, x_ptr, iters=4, ctx_ptr=None, n_ctx=0):
         out = (dl_layer_profile * n_layers)()
         self._ck(lib().dl_profile(self._h, module, n_tokens, pos0, _p(x_ptr), _p(ctx_ptr), n_ctx, iters, out))
-        return [dict(c_dma_ms=o.c_dma_ms, c_exe_ms=o.c_exe_ms, c_exe_hot_ms=o.c_exe_hot_ms, bytes=o.bytes) for o in out]
+        return [dict(c_dma_ms=o.c_dma_ms, c_exe_ms=o.c_exe_ms, c_exe_hot_ms=o.c_exe_hot_ms, c_fence_ms=o.c_fence_ms,
+                     bytes=o.bytes) for o in out]
 
     def set_timing(self, on):
         self._ck(lib().dl_set_timing(self._h, int(on)))
@@ -302,6 +306,15 @@ class Context:
         if on:
             mask = -1 if kinds is None else sum(1 << int(k) for k in kinds)
         self._ck(lib().dl_set_kernel_timing(self._h, mask))
+
+    def set_run_ahead(self, passes):
+        self._ck(lib().dl_set_run_ahead(self._h, int(passes)))
+
+    def probe_mfma_rate(self, pattern=1, iters=20000):
+        """Register-only BF16 MFMA rate of the device in TFLOP/s (diagnostic)."""
+        out = C.c_double(0.0)
+        self._ck(lib().dl_probe_mfma_rate(self._h, int(pattern), int(iters), C.byref(out)))
+        return out.value
 
     def collect_kernel_times(self):
         out = (dl_kernel_time * len(DL_K_NAMES))()
@@ -356,11 +369,12 @@ def predict_linear(c_total0_ms, slope_ms_per_layer, k):
 
 
 def timeline(c_dma_ms, c_exe_ms, streamed, pass_start, module_id=None, mode=DL_MODE_PIPELINED, wrap_prefetch=0,
-             overhead_ms=0.0, c_exe_idle_ms=None):
+             overhead_ms=0.0, c_exe_idle_ms=None, c_fence_ms=None):
     n = len(c_dma_ms)
     tot, hid, exp_ = _f64(), _f64(), _f64()
     rc = lib().dl_timeline(_arr(_f64, c_dma_ms), _arr(_f64, c_exe_ms),
                            None if c_exe_idle_ms is None else _arr(_f64, c_exe_idle_ms),
+                           None if c_fence_ms is None else _arr(_f64, c_fence_ms),
                            _arr(C.c_uint8, [1 if s else 0 for s in streamed]),
                            _arr(C.c_uint8, [1 if s else 0 for s in pass_start]),
                            None if module_id is None else _arr(_i32, module_id), n, mode, int(wrap_prefetch),

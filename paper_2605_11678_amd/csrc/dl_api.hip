@@ -61,6 +61,10 @@ struct dl_ctx {
     dl::SlotBook book;
     hipEvent_t ev_dma[2] = {nullptr, nullptr}, ev_comp[2] = {nullptr, nullptr}, ev_pass = nullptr;
     bool events_made = false;
+    static constexpr int kMaxRunAhead = 8;
+    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // end of the most recent passes on the compute stream (host throttle)
+    uint64_t n_passes = 0;
+    int32_t run_ahead = 1;                        // passes the host may have enqueued and unfinished; 0 = unlimited
     int32_t mode = DL_MODE_PIPELINED, wrap = 0;
     bool tracing = false;
     std::vector<dl_trace_op> trace;
@@ -108,6 +112,7 @@ int32_t make_events(dl_ctx* c) {
         DL_HIP(c, hipEventCreateWithFlags(&c->ev_comp[s], hipEventDisableTiming));
     }
     DL_HIP(c, hipEventCreateWithFlags(&c->ev_pass, hipEventDisableTiming));
+    for (int s = 0; s < dl_ctx::kMaxRunAhead; ++s) DL_HIP(c, hipEventCreateWithFlags(&c->ev_inflight[s], hipEventDisableTiming));
     c->events_made = true;
     return DL_OK;
 }
@@ -365,6 +370,12 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
     dl::build_pass(mi, M.d.n_layers, M.resident.data(), c->mode, c->wrap, force_all, &c->book, &ops);
     if (c->tracing || !on_gpu(c)) c->trace.insert(c->trace.end(), ops.begin(), ops.end());
     if (!on_gpu(c)) return DL_OK;
+    // Bounded run-ahead: by default the host enqueues a pass only once the previous one has finished (it still
+    // runs ahead of the GPU inside the pass: enqueuing takes a tenth of the pass time or less).  Every further pass
+    // of short streamed layers kept in flight made copies and kernels slower on MI355X (27-layer encoder, fully
+    // streamed: 15.4 ms per pass with one pass in flight, 16.0 with two, 17.7 with three, 19 with four).
+    if (c->run_ahead > 0 && c->n_passes >= uint64_t(c->run_ahead))
+        DL_HIP(c, hipEventSynchronize(c->ev_inflight[(c->n_passes - uint64_t(c->run_ahead)) % dl_ctx::kMaxRunAhead]));
     for (const dl_trace_op& o : ops) {
         hipStream_t st = o.queue == 0 ? c->s_compute : c->s_copy;
         switch (o.op) {
@@ -414,6 +425,8 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
             default: break;
         }
     }
+    DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_compute));
+    ++c->n_passes;
     return DL_OK;
 }
 
@@ -465,6 +478,7 @@ int32_t dl_destroy(dl_ctx* c) {
                 (void)hipEventDestroy(c->ev_comp[s]);
             }
             (void)hipEventDestroy(c->ev_pass);
+            for (int s = 0; s < dl_ctx::kMaxRunAhead; ++s) (void)hipEventDestroy(c->ev_inflight[s]);
         }
         for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     }
@@ -998,7 +1012,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     c->tracing = false;
     c->book = dl::SlotBook();
     const int32_t Ln = M->d.n_layers;
-    std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0), hot(size_t(Ln), 0.0);
+    std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0), hot(size_t(Ln), 0.0), fence(size_t(Ln), 0.0);
     for (int32_t it = 0; it < iters && rc == DL_OK; ++it) {
         rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
         if (rc) break;
@@ -1011,6 +1025,11 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         for (int32_t i = 0; i < Ln; ++i) {
             dma[size_t(i)] += double(recs[size_t(i)].dma_end_ms) - recs[size_t(i)].dma_start_ms;
             exe[size_t(i)] += double(recs[size_t(i)].exe_end_ms) - recs[size_t(i)].exe_start_ms;
+            // hand-offs: copy end -> first kernel, last kernel -> next copy (the last layer has no next copy: its
+            // first hand-off is counted twice)
+            const double in = double(recs[size_t(i)].exe_start_ms) - recs[size_t(i)].dma_end_ms;
+            const double outw = i + 1 < Ln ? double(recs[size_t(i + 1)].dma_start_ms) - recs[size_t(i)].exe_end_ms : in;
+            fence[size_t(i)] += std::max(0.0, in) + std::max(0.0, outw);
         }
     }
     // all layers back to back, no copies: execution time under continuous load (second of two runs)
@@ -1057,8 +1076,50 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         out[i].c_dma_ms = dma[size_t(i)] / (iters - 1);
         out[i].c_exe_ms = exe[size_t(i)] / (iters - 1);
         out[i].c_exe_hot_ms = hot[size_t(i)];
+        out[i].c_fence_ms = fence[size_t(i)] / (iters - 1);
         out[i].bytes = M->L.bytes;
     }
+    return DL_OK;
+}
+
+int32_t dl_set_run_ahead(dl_ctx* c, int32_t passes) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (passes < 0 || passes > dl_ctx::kMaxRunAhead) return fail(c, DL_ERR_INVALID_ARG, "run-ahead outside [0, 8]");
+    c->run_ahead = passes;
+    return DL_OK;
+}
+
+int32_t dl_probe_mfma_rate(dl_ctx* c, int32_t pattern, int32_t iters, double* tflops_out) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!tflops_out || iters < 1 || iters > (1 << 20) || pattern < 0 || pattern > 1) return fail(c, DL_ERR_INVALID_ARG, "bad probe arguments");
+    if (!on_gpu(c)) return fail(c, DL_ERR_BAD_STATE, "the MFMA probe needs a device context");
+    if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
+    hipDeviceProp_t prop;
+    DL_HIP(c, hipGetDeviceProperties(&prop, c->device));
+    const int blocks = prop.multiProcessorCount;
+    uint64_t off = 0;
+    if (!c->arena.alloc(uint64_t(blocks) * 1024, &off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the probe's output");
+    float* out = reinterpret_cast<float*>(c->base + off);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t he = hipEventCreate(&e0);
+    if (he == hipSuccess) he = hipEventCreate(&e1);
+    double flop = 0.0;
+    float ms = 0.0f;
+    if (he == hipSuccess) {
+        dlk::mfma_rate_probe(out, blocks, iters, pattern, c->s_compute);          // warm-up launch
+        (void)hipEventRecord(e0, c->s_compute);
+        flop = dlk::mfma_rate_probe(out, blocks, iters, pattern, c->s_compute);
+        (void)hipEventRecord(e1, c->s_compute);
+        he = hipStreamSynchronize(c->s_compute);
+        if (he == hipSuccess) he = hipEventElapsedTime(&ms, e0, e1);
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    c->arena.free(off);
+    DL_HIP(c, he);
+    *tflops_out = ms > 0.0f ? flop / (double(ms) * 1e-3) / 1e12 : 0.0;
     return DL_OK;
 }
 

@@ -412,7 +412,7 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
 }
 
 int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
-                    const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+                    const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
                     int32_t mode, int32_t wrap_prefetch, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms) {
     if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
@@ -476,7 +476,8 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
                     break;
                 }
                 case DL_OP_EXEC:
-                    t[q] += ((idled && c_exe_idle_ms) ? c_exe_idle_ms[j] : c_exe_ms[j]) + overhead_ms;
+                    t[q] += ((idled && c_exe_idle_ms) ? c_exe_idle_ms[j] : c_exe_ms[j]) + overhead_ms +
+                            ((o.slot >= 0 && c_fence_ms) ? c_fence_ms[j] : 0.0);
                     idled = false;
                     break;
                 default: break;

@@ -95,6 +95,10 @@ void axpy_f32(float* y, float alpha, const float* x, uint64_t n, hipStream_t st)
 // y[t, i] = x[t, i] + (i < d/2 ? sin : cos)(1000 * tval * 10000^(-(i mod d/2) / (d/2)))
 void add_time_embedding(const float* x, float* y, float tval, int T, int d, hipStream_t st);
 
+// ---- diagnostic: register-only BF16 MFMA loop on `blocks` workgroups of 4 wavefronts; out holds blocks*256 floats.
+// Returns the flop the launch performs.
+double mfma_rate_probe(float* out, int blocks, int iters, int pattern, hipStream_t st);
+
 // ---- head --------------------------------------------------------------------------------------------
 void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_host, float* x_out, hipStream_t st);
 void argmax_f32(const float* logits, int n, int32_t* token_dev, hipStream_t st);

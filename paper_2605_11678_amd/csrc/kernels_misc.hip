@@ -250,6 +250,53 @@ void mean_pool_rows(const float* x, float* y, int T_out, int group, int d, hipSt
     hipLaunchKernelGGL(mean_pool_kernel, dim3(T_out), dim3(256), 0, st, x, y, group, d);
 }
 
+// Register-only MFMA loop: every wavefront keeps 16 independent 32x32 accumulator tiles busy with operands that
+// never leave registers.  pattern 0: all-zero operands; 1: values in [1, 2) with hashed mantissa and sign.
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 probe_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float probe_f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t probe_u32x4;
+__global__ __launch_bounds__(256) void mfma_rate_kernel(float* out, int iters, int pattern) {
+    probe_bf16x8 a[4], b[4];
+    uint32_t s = threadIdx.x * 2654435761u + 12345u;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        probe_u32x4 w;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            s = s * 1664525u + 1013904223u;
+            const uint32_t lo = 0x3F80u | ((s >> 9) & 0x7Fu) | ((s >> 3) & 0x8000u);
+            s = s * 1664525u + 1013904223u;
+            const uint32_t hi = 0x3F80u | ((s >> 9) & 0x7Fu) | ((s >> 3) & 0x8000u);
+            w[j] = pattern ? (lo | (hi << 16)) : 0u;
+        }
+        if (i < 4) a[i] = *reinterpret_cast<probe_bf16x8*>(&w);
+        else b[i - 4] = *reinterpret_cast<probe_bf16x8*>(&w);
+    }
+    probe_f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 3], b[i >> 2], acc[i], 0, 0, 0);
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+}  // namespace
+
+double mfma_rate_probe(float* out, int blocks, int iters, int pattern, hipStream_t st) {
+    hipLaunchKernelGGL(mfma_rate_kernel, dim3(blocks), dim3(256), 0, st, out, iters, pattern);
+    return double(blocks) * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
+}
+
 void axpy_f32(float* y, float alpha, const float* x, uint64_t n, hipStream_t st) {
     if (n == 0) return;
     const uint64_t blocks = (n + 255) / 256;

@@ -121,6 +121,35 @@ def test_timeline_matches_oracle_recurrence(wrap):
         assert seq["total"] == pytest.approx(P.sequential_time(inv), rel=1e-12)
 
 
+def _flatten5(invocations):
+    dma, exe, st, ps, idle, fence = [], [], [], [], [], []
+    for layers in invocations:
+        for i, (d, e, s, ei, f) in enumerate(layers):
+            dma.append(d), exe.append(e), st.append(s), ps.append(i == 0), idle.append(ei), fence.append(f)
+    return (dma, exe, st, ps), dict(c_exe_idle_ms=idle, c_fence_ms=fence)
+
+
+@pytest.mark.parametrize("wrap", [0, 1])
+def test_timeline_with_measured_corrections_matches_oracle(wrap):
+    """idle-execution time, per-streamed-layer fence cost and per-layer overhead: library replay vs the
+    oracle's recurrence on random schedules"""
+    rnd = random.Random(23)
+    for trial in range(200):
+        L = rnd.randint(1, 7)
+        n_pass = rnd.randint(1, 4)
+        mask = [rnd.random() < 0.6 for _ in range(L)]
+        inv = [[(rnd.uniform(0.1, 5), rnd.uniform(0.1, 5), mask[i], rnd.uniform(0.1, 6), rnd.uniform(0, 0.5))
+                for i in range(L)] for _ in range(n_pass)]
+        ov = rnd.choice([0.0, 0.07])
+        pos, kw = _flatten5(inv)
+        want = P.timeline(inv, wrap_prefetch=bool(wrap), overhead=ov)
+        got = B.timeline(*pos, wrap_prefetch=wrap, overhead_ms=ov, **kw)
+        assert got["total"] == pytest.approx(want["total"], rel=1e-12)
+        assert got["exposed"] == pytest.approx(want["exposed"], rel=1e-9, abs=1e-12)
+        seq = B.timeline(*pos, mode=B.DL_MODE_SEQUENTIAL, overhead_ms=ov, **kw)
+        assert seq["total"] == pytest.approx(P.sequential_time(inv, overhead=ov), rel=1e-12)
+
+
 def test_timeline_closed_forms_eq5_eq6_eq7():
     L, R = 36, 21
     uni = lambda d, e: [(d, e, True)] * L

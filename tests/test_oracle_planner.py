@@ -216,3 +216,23 @@ def test_hidden_fraction_limits():
     tl = P.timeline([_uniform(L, 5.0, 1.0)])
     assert tl["exposed"] == pytest.approx(5.0 + (L - 1) * 4.0)
     assert P.sequential_time([_uniform(L, 5.0, 1.0)]) == pytest.approx(L * 6.0)
+
+
+def test_timeline_corrections_closed_forms():
+    """the measured corrections against hand-derived totals: one pass of L identical streamed layers"""
+    L, f, ov = 9, 0.25, 0.125
+    # execution-bound (C_EXE > C_DMA): only the first layer waits for its transfer and runs at the idle time
+    exe_bound = [[(1.0, 4.0, True, 5.0, f)] * L]
+    assert P.timeline(exe_bound, overhead=ov)["total"] == pytest.approx(1.0 + 5.0 + (L - 1) * 4.0 + L * (f + ov))
+    # transfer-bound (C_DMA > C_EXE_idle + fence + overhead): every layer waits; total = all transfers + last layer
+    dma_bound = [[(4.0, 1.0, True, 1.5, f)] * L]
+    assert P.timeline(dma_bound, overhead=ov)["total"] == pytest.approx(L * 4.0 + 1.5 + f + ov)
+    # resident layers carry neither the idle time nor the fence
+    res = [[(4.0, 1.0, False, 1.5, f)] * L]
+    assert P.timeline(res, overhead=ov)["total"] == pytest.approx(L * (1.0 + ov))
+    # sequential: transfer + idle execution + fence per streamed layer
+    assert P.sequential_time(dma_bound, overhead=ov) == pytest.approx(L * (4.0 + 1.5 + f + ov))
+    # three-field records are the five-field ones with C_EXE_idle = C_EXE and no fence
+    a = [[(2.0, 3.0, True), (1.0, 0.5, False), (2.5, 0.7, True)]] * 3
+    b = [[(d, e, s, e, 0.0) for (d, e, s) in layers] for layers in a]
+    assert P.timeline(a)["total"] == P.timeline(b)["total"]
