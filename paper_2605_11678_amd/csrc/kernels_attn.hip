@@ -6,7 +6,8 @@
 // (column l%32; rows 8*(r/4) + 4*(l/32) + r%4), so the softmax row reductions are in-lane plus one
 // exchange with lane l^32, the running max / sum / rescale are per-lane scalars, and the
 // probabilities P^T are already in B-operand position for O^T = V^T * P^T (8 consecutive
-// accumulator registers = the 8 k-values a lane supplies).  V is kept transposed in memory
+// accumulator registers = the 8 k-values a lane supplies).  The keys of a score tile are assigned to
+// MFMA rows with bits 2 and 3 of the row index swapped, which makes those 8 k-values 8 consecutive keys.  V is kept transposed in memory
 // ([feature][position]) so V^T tiles are plain row loads.
 //
 // Block: 4 wavefronts, K/V tiles of 64 positions in LDS, double-buffered; the next tile is fetched into
@@ -44,6 +45,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, g2 = lane >> 5;
+    // MFMA row lq of a score tile holds key krow: bits 2 and 3 swapped.  With that order the 8 accumulator
+    // registers a lane turns into one B-operand fragment of P^T belong to 8 CONSECUTIVE keys
+    // (16*t2 + 8*g2 + 0..7), so the matching V^T fragment is one 16-byte read.
+    const int krow = (lq & 0x13) | ((lq & 4) << 1) | ((lq & 8) >> 1);
     const int group = p.Hq / p.Hkv;
     // causal passes: the last query blocks see the most keys; launch them first so the tail of the grid is short
     const int q0 = (p.causal ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x)) * QB;
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 for (int r = 0; r < 16; ++r) accS[i][r] = 0.0f;
 #pragma unroll
                 for (int kk = 0; kk < DHP / 16; ++kk) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + lq) * KLD + 16 * kk + 8 * g2]);
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + krow) * KLD + 16 * kk + 8 * g2]);
                     accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], accS[i], 0, 0, 0);
                 }
             }
@@ -151,7 +156,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        const int kv = j0 + 32 * i + 8 * (r >> 2) + 4 * g2 + (r & 3);
+                        // accumulator row 8*(r/4) + 4*g2 + r%4 holds key 16*(r/8) + 8*g2 + r%8
+                        const int kv = j0 + 32 * i + 16 * (r >> 3) + 8 * g2 + (r & 7);
                         const bool ok = kv < p.S && (!p.causal || kv <= qpos);
                         accS[i][r] = ok ? accS[i][r] : -INFINITY;
                     }
@@ -194,12 +200,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int t2 = 0; t2 < 2; ++t2) {
-                        const bf16_t* vr = &sV[s][(32 * dt + lq) * VLD + 32 * i + 16 * t2 + 4 * g2];
-                        const u32x2 lo = *reinterpret_cast<const u32x2*>(vr);
-                        const u32x2 hi = *reinterpret_cast<const u32x2*>(vr + 8);
-                        u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
-                        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av),
-                                                                           pf[i][t2], accO[dt], 0, 0, 0);
+                        const bf16x8 av = *reinterpret_cast<const bf16x8*>(
+                            &sV[s][(32 * dt + lq) * VLD + 32 * i + 16 * t2 + 8 * g2]);
+                        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[i][t2], accO[dt], 0, 0, 0);
                     }
         }
         if (t + 1 < nt) stash(s ^ 1);
