@@ -64,6 +64,8 @@ struct QkvPostArgs {
 void qkv_post(const QkvPostArgs& a, hipStream_t st);
 
 // ---- attention (flash-style, online softmax, MFMA) ------------------------------------------------
+// The V^T rows must be readable up to S rounded up to 8 positions and hold finite numbers there (stale values are
+// fine: they meet zero probabilities); K rows and V^T rows are read in 16-byte pieces (ldk, ldv multiples of 8).
 struct AttnArgs {
     const bf16_t* q; int ldq;                         // token t, head h: q + t*ldq + h*dh
     const bf16_t* k; int ldk; uint64_t k_head_stride; // kv head g, position j: k + g*k_head_stride + j*ldk

@@ -18,8 +18,8 @@
 //   HEADS = false: the four wavefronts are four 32-query slices of one head (128 queries per block).
 // Head dims 64 / 72 / 128 run as DHP = 64 / 96 / 128 with zero padding (exact zeros contribute nothing).
 // Softmax runs on raw scores: the 1/sqrt(dh) * log2(e) scale is folded into one FMA in front of the
-// base-2 exponential, masking is skipped on tiles that cannot need it, and the running output is
-// rescaled only when some lane's running maximum moved.
+// base-2 exponential, masking is skipped on tiles that cannot need it, and the reference maximum of the
+// online softmax moves lazily (only past a 2^8 margin), so the running output is rescaled about once.
 #include "kernels.hpp"
 
 namespace dlk {
@@ -85,32 +85,24 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     const int wave_last = p.q_pos0 + min(wq0 + 31, p.T - 1);   // last query position of this wavefront
     const int nt = (kv_end + BKV - 1) / BKV;
 
+    // Loads are unconditional with clamped addresses (no branches, nothing waits on a load before the stash):
+    //  * K rows past S repeat row S-1; those keys are masked to -inf (a tile that contains them is always masked);
+    //  * feature chunks past dh (zero padding of the head dimension) re-read chunk 0: they meet zero Q features;
+    //  * V^T rows past dh repeat row dh-1 (they produce output features nobody stores); V^T position chunks that
+    //    start past S re-read the chunk at 0, and a chunk that straddles S brings along up to 7 stale positions:
+    //    their probabilities are exact zeros and the buffers hold finite numbers everywhere (zeroed when the
+    //    module is finalised, rows padded to a multiple of 64 positions).
     u32x4 rk[NKC], rv[NVC];
     auto fetch = [&](int j0) {
 #pragma unroll
         for (int i = 0; i < NKC; ++i) {
             const int c = tid + 256 * i, row = c / (DHP / 8), kc = (c % (DHP / 8)) * 8;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (j0 + row < p.S && kc < p.dh)
-                v = *reinterpret_cast<const u32x4*>(kbase + size_t(j0 + row) * p.ldk + kc);
-            rk[i] = v;
+            rk[i] = *reinterpret_cast<const u32x4*>(kbase + size_t(min(j0 + row, p.S - 1)) * p.ldk + (kc < p.dh ? kc : 0));
         }
 #pragma unroll
         for (int i = 0; i < NVC; ++i) {
             const int c = tid + 256 * i, e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (e < p.dh && j0 + jc < p.S) {
-                v = *reinterpret_cast<const u32x4*>(vbase + size_t(e) * p.ldv + j0 + jc);
-                const int nvalid = p.S - (j0 + jc);    // > 0; positions >= S hold stale memory: zero them
-                if (nvalid < 8) {
-#pragma unroll
-                    for (int w = 0; w < 4; ++w) {
-                        if (2 * w >= nvalid) v[w] = 0u;
-                        else if (2 * w + 1 >= nvalid) v[w] &= 0x0000FFFFu;
-                    }
-                }
-            }
-            rv[i] = v;
+            rv[i] = *reinterpret_cast<const u32x4*>(vbase + size_t(min(e, p.dh - 1)) * p.ldv + (j0 + jc < p.S ? j0 + jc : 0));
         }
     };
     auto stash = [&](int s) {
@@ -167,17 +159,25 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, accS[i][r]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-            if (__any(m_new != m_run)) {
-                const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2);
+            {
+                // exchange with lane l^32 (the other 16 keys of the same query) without going through the LDS
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+                mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
+            // Lazy reference maximum: m_run moves only when the tile maximum exceeds it by more than 2^LAZY in the
+            // exponent, so probabilities stay below 2^LAZY (no overflow in bf16 / fp32) and the running output is
+            // rescaled on the first tile and almost never again.  Any reference gives the same softmax.
+            constexpr float LAZY = 8.0f;
+            const bool move = (mx - m_run) * scale_log2 > LAZY;   // false for NaN (-inf minus -inf: nothing visible yet)
+            const float m_use = move ? mx : (m_run == -INFINITY ? 0.0f : m_run);
+            if (__any(move)) {
+                const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2) : 1.0f;
                 l_run *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < DHP / 32; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) accO[dt][r] *= alpha;
-                m_run = m_new;
+                m_run = move ? mx : m_run;
             }
             const float ms = m_use * scale_log2;
             float psum = 0.0f;
