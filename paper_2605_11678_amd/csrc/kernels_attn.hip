@@ -67,6 +67,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
             const int e = 16 * kk + 8 * g2;
             u32x4 v = {0u, 0u, 0u, 0u};
             if (tq < p.T && e < p.dh) v = *reinterpret_cast<const u32x4*>(qrow + e);
+            // pass the loaded words through a register move: inside the tile loop the fragments are then results of
+            // vector instructions, and the compiler does not put a wait for ALL outstanding loads (the prefetch of
+            // the next K/V tile included) in front of the first MFMA that reads them
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                uint32_t y;
+                asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(v[w]));
+                v[w] = y;
+            }
             qf[kk] = *reinterpret_cast<bf16x8*>(&v);
         }
     }
@@ -129,17 +138,36 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         // a wavefront whose queries all lie before this tile has nothing to add (causal)
         const bool active = !p.causal || j0 <= wave_last;
         if (active) {
-            // S^T tile: 64 keys x 32 queries
+            // S^T tile: 64 keys x 32 queries.  LDS fragments are requested AHEAD MFMAs early so that an MFMA does
+            // not wait for the read issued right in front of it.
+            constexpr int NS = 2 * (DHP / 16), AHEAD = 3;
             f32x16 accS[2];
+            {
+                bf16x8 fr[NS];
+                auto kfrag = [&](int n) {
+                    const int i = n / (DHP / 16), kk = n % (DHP / 16);
+                    return *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + krow) * KLD + 16 * kk + 8 * g2]);
+                };
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+                for (int n = 0; n < AHEAD; ++n) fr[n] = kfrag(n);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) accS[i][r] = 0.0f;
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int kk = 0; kk < DHP / 16; ++kk) {
-                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + krow) * KLD + 16 * kk + 8 * g2]);
-                    accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], accS[i], 0, 0, 0);
+                    for (int r = 0; r < 16; ++r) accS[i][r] = 0.0f;
+#pragma unroll
+                for (int n = 0; n < NS; ++n) {
+                    if (n + AHEAD < NS) fr[n + AHEAD] = kfrag(n + AHEAD);
+                    const int i = n / (DHP / 16), kk = n % (DHP / 16);
+                    accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n], qf[kk], accS[i], 0, 0, 0);
                 }
+                // keep that order: AHEAD reads, then one read per MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+#pragma unroll
+                for (int n = 0; n < NS; ++n) {
+                    if (n + AHEAD < NS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             // masking only where it can bite: the diagonal tiles of a causal pass and the ragged last tile
             const bool need_mask = (j0 + BKV > p.S) || (p.causal && j0 + BKV - 1 > p.q_pos0 + wq0);
@@ -194,16 +222,29 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                     }
             l_run += psum;
             // O^T += V^T * P^T
+            {
+                constexpr int NP = (DHP / 32) * 4;
+                bf16x8 fr[NP];
+                auto vfrag = [&](int n) {
+                    const int dt = n / 4, i = (n / 2) % 2, t2 = n % 2;
+                    return *reinterpret_cast<const bf16x8*>(&sV[s][(32 * dt + lq) * VLD + 32 * i + 16 * t2 + 8 * g2]);
+                };
 #pragma unroll
-            for (int dt = 0; dt < DHP / 32; ++dt)
+                for (int n = 0; n < AHEAD; ++n) fr[n] = vfrag(n);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
+                for (int n = 0; n < NP; ++n) {
+                    if (n + AHEAD < NP) fr[n + AHEAD] = vfrag(n + AHEAD);
+                    const int dt = n / 4, i = (n / 2) % 2, t2 = n % 2;
+                    accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n], pf[i][t2], accO[dt], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
 #pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2) {
-                        const bf16x8 av = *reinterpret_cast<const bf16x8*>(
-                            &sV[s][(32 * dt + lq) * VLD + 32 * i + 16 * t2 + 8 * g2]);
-                        accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, pf[i][t2], accO[dt], 0, 0, 0);
-                    }
+                for (int n = 0; n < NP; ++n) {
+                    if (n + AHEAD < NP) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
         if (t + 1 < nt) stash(s ^ 1);
         __syncthreads();
