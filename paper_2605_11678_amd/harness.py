@@ -19,7 +19,10 @@ def desc_fields(c: CFG.ModuleConfig, max_tokens: int, max_ctx: int = 0):
 class Engine:
     """One context on one device (device=-1: host-only accounting context, no GPU)."""
 
-    def __init__(self, cap_bytes: int, device: int = 0):
+    def __init__(self, cap_bytes: int, device: int = 0, fence_slack_bytes: int = 3 << 30):
+        """cap_bytes: the emulated VRAM cap = size of the arena every byte of the path is carved from.
+        fence_slack_bytes: second fence around the cap: PyTorch's caching allocator may not hold more than
+        cap + slack on this device (slack covers measurement buffers that are not part of the path); None: no fence."""
         self.device = device
         self.cap_bytes = int(cap_bytes)
         self.ctx = B.Context(device)
@@ -29,6 +32,9 @@ class Engine:
             self.torch = torch
             self.dev = torch.device("cuda", device)
             torch.cuda.set_device(self.dev)
+            if fence_slack_bytes is not None:
+                total = torch.cuda.get_device_properties(self.dev).total_memory
+                torch.cuda.set_per_process_memory_fraction(min(1.0, (self.cap_bytes + fence_slack_bytes) / total), self.dev)
             self.arena = torch.empty(self.cap_bytes, dtype=torch.uint8, device=self.dev)
             self.ctx.set_arena(self.arena.data_ptr(), self.cap_bytes, keep=self.arena)
             self.s_compute = torch.cuda.Stream(device=self.dev)
