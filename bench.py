@@ -352,7 +352,7 @@ def main():
     T, L = args.tokens, c.n_layers
     cap = int(args.cap)
     t0 = time.time()
-    eng = Engine(cap, device=0)
+    eng = Engine(cap, device=0, fence_slack_bytes=3 << 30)     # allocator limit as a second fence around the cap
     mid = eng.add_module(c, max_tokens=T)
     packed, params = eng.ctx.module_layer_bytes(mid)
     log("setup: %d layers x %.1f MiB packed (%.1f MiB parameters) in %.1f s" % (L, packed / 2 ** 20, params / 2 ** 20, time.time() - t0))

@@ -19,10 +19,11 @@ def desc_fields(c: CFG.ModuleConfig, max_tokens: int, max_ctx: int = 0):
 class Engine:
     """One context on one device (device=-1: host-only accounting context, no GPU)."""
 
-    def __init__(self, cap_bytes: int, device: int = 0, fence_slack_bytes: int = 3 << 30):
+    def __init__(self, cap_bytes: int, device: int = 0, fence_slack_bytes=None):
         """cap_bytes: the emulated VRAM cap = size of the arena every byte of the path is carved from.
         fence_slack_bytes: second fence around the cap: PyTorch's caching allocator may not hold more than
-        cap + slack on this device (slack covers measurement buffers that are not part of the path); None: no fence."""
+        cap + slack on this device (slack covers measurement buffers that are not part of the path) until close().
+        The limit is per process, so only one fenced engine can be alive at a time; None (default): no fence."""
         self.device = device
         self.cap_bytes = int(cap_bytes)
         self.ctx = B.Context(device)
@@ -32,7 +33,8 @@ class Engine:
             self.torch = torch
             self.dev = torch.device("cuda", device)
             torch.cuda.set_device(self.dev)
-            if fence_slack_bytes is not None:
+            self.fenced = fence_slack_bytes is not None
+            if self.fenced:
                 total = torch.cuda.get_device_properties(self.dev).total_memory
                 torch.cuda.set_per_process_memory_fraction(min(1.0, (self.cap_bytes + fence_slack_bytes) / total), self.dev)
             self.arena = torch.empty(self.cap_bytes, dtype=torch.uint8, device=self.dev)
@@ -47,6 +49,9 @@ class Engine:
     def close(self):
         self.ctx.destroy()
         self.arena = None
+        if self.torch is not None and getattr(self, "fenced", False):
+            self.torch.cuda.set_per_process_memory_fraction(1.0, self.dev)
+            self.fenced = False
 
     # ---- registration ----
     def add_module(self, c: CFG.ModuleConfig, max_tokens: int, max_ctx: int = 0, weights=None, head=None):
