@@ -51,7 +51,8 @@ __device__ __forceinline__ float block_sum_256(float v, float* red) {
     return red[0] + red[1] + red[2] + red[3];
 }
 
-constexpr int UNITS_PER_WAVE = 2;
+// rows a wavefront streams together: 4 (two SwiGLU units = 2 gate + 2 up rows, or four plain units)
+constexpr int ROWS_PER_WAVE = 4;
 
 // a "unit" is one output element; for SwiGLU it needs two weight rows (gate and up)
 template <int EPI>
@@ -60,34 +61,11 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
     __shared__ float red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunk = p.K >> 3;
-    if (p.xf) {
-        // fused normalisation: every workgroup normalises the (small) input vector for itself
-        float mean = 0.0f;
-        if (p.norm_kind == 1) {
-            float s = 0.0f;
-            for (int i = tid; i < p.K; i += 256) s += p.xf[i];
-            mean = block_sum_256(s, red) / float(p.K);
-        }
-        float ss = 0.0f;
-        for (int i = tid; i < p.K; i += 256) {
-            const float c = p.xf[i] - mean;
-            ss += c * c;
-        }
-        const float inv = rsqrtf(block_sum_256(ss, red) / float(p.K) + p.eps);
-        for (int i = tid; i < p.K; i += 256) {
-            float v = (p.xf[i] - mean) * inv * bf16_to_f(p.ng[i]);
-            if (p.norm_kind == 1) v += bf16_to_f(p.nb[i]);
-            sx[i] = f_to_bf16(v);
-        }
-    } else {
-        for (int c = tid; c < nchunk; c += 256)
-            reinterpret_cast<u32x4*>(sx)[c] = reinterpret_cast<const u32x4*>(p.x)[c];
-    }
-    __syncthreads();
 
     const int n_units = (EPI == EPI_SWIGLU_BF16) ? p.N / 2 : p.N;
+    constexpr int ROWS = ROWS_PER_WAVE;
+    constexpr int UNITS_PER_WAVE = (EPI == EPI_SWIGLU_BF16) ? ROWS / 2 : ROWS;
     const int u0 = (blockIdx.x * 4 + wave) * UNITS_PER_WAVE;
-    constexpr int ROWS = (EPI == EPI_SWIGLU_BF16) ? 2 * UNITS_PER_WAVE : UNITS_PER_WAVE;
     const bf16_t* rows[ROWS];
     bool valid[UNITS_PER_WAVE];
 #pragma unroll
@@ -103,19 +81,100 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
             rows[u] = p.B + size_t(uu) * p.ldb;
         }
     }
+    // Weight pieces are fetched 4 rows x CU pieces (of 64 chunks = 1 KB) at a time = 16 independent 16-byte loads
+    // per lane, double-buffered, and the FIRST group is requested before the input vector is prepared: all
+    // workgroups of a launch are resident together, so without that the memory system would idle while every one
+    // of them normalises the input.  Wavefronts start at different pieces of their rows (rotation).
+    constexpr int CU = 4;
+    const int n_it = nchunk >> 6;
+    const bool piped = (nchunk & 63) == 0 && (n_it % CU) == 0;
+    const int rot = piped ? (blockIdx.x * 4 + wave) % n_it : 0;
+    auto chunk_of = [&](int it) {
+        int idx = it + rot;
+        idx = idx >= n_it ? idx - n_it : idx;
+        return lane + 64 * idx;
+    };
+    auto load_group = [&](int it, u32x4 (&w)[ROWS][CU]) {
+#pragma unroll
+        for (int u = 0; u < CU; ++u) {
+            const int c = chunk_of(it + u);
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) w[r][u] = reinterpret_cast<const u32x4*>(rows[r])[c];
+        }
+    };
+    u32x4 wA[ROWS][CU], wB[ROWS][CU];
+    if (piped) load_group(0, wA);
+
+    float post_scale = 1.0f;                            // factor applied to the dot products (RMS fusion)
+    if (p.xf && p.norm_kind == 0) {
+        // Fused RMSNorm in ONE pass and one barrier: the vector goes to LDS as bf16(x * g) while its sum of squares
+        // is gathered, and the scalar 1/rms, which is common to all elements, multiplies the finished dot
+        // products instead of every element (W (x g / rms) = (W (x g)) / rms).
+        float ss = 0.0f;
+        for (int i = tid; i < p.K; i += 256) {
+            const float v = p.xf[i];
+            ss += v * v;
+            sx[i] = f_to_bf16(v * bf16_to_f(p.ng[i]));
+        }
+        ss = wave_sum(ss);
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        post_scale = rsqrtf((red[0] + red[1] + red[2] + red[3]) / float(p.K) + p.eps);
+    } else if (p.xf) {
+        // fused LayerNorm: every workgroup normalises the (small) input vector for itself
+        float s1 = 0.0f;
+        for (int i = tid; i < p.K; i += 256) s1 += p.xf[i];
+        const float mean = block_sum_256(s1, red) / float(p.K);
+        float ss = 0.0f;
+        for (int i = tid; i < p.K; i += 256) {
+            const float c = p.xf[i] - mean;
+            ss += c * c;
+        }
+        const float inv = rsqrtf(block_sum_256(ss, red) / float(p.K) + p.eps);
+        for (int i = tid; i < p.K; i += 256)
+            sx[i] = f_to_bf16((p.xf[i] - mean) * inv * bf16_to_f(p.ng[i]) + bf16_to_f(p.nb[i]));
+        __syncthreads();
+    } else {
+        for (int c = tid; c < nchunk; c += 256)
+            reinterpret_cast<u32x4*>(sx)[c] = reinterpret_cast<const u32x4*>(p.x)[c];
+        __syncthreads();
+    }
+
     float acc[ROWS];
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) acc[r] = 0.0f;
-    for (int c = lane; c < nchunk; c += 64) {
-        const u32x4 xv = reinterpret_cast<const u32x4*>(sx)[c];
+    auto consume = [&](int it, const u32x4 (&w)[ROWS][CU]) {
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) {
-            const u32x4 w = reinterpret_cast<const u32x4*>(rows[r])[c];
-            acc[r] += dot8(w, xv);
+        for (int u = 0; u < CU; ++u) {
+            const u32x4 xv = reinterpret_cast<const u32x4*>(sx)[chunk_of(it + u)];
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) acc[r] += dot8(w[r][u], xv);
+        }
+    };
+    if (piped) {
+        int it = 0;
+        while (true) {
+            if (it + CU < n_it) load_group(it + CU, wB);
+            consume(it, wA);
+            it += CU;
+            if (it >= n_it) break;
+            if (it + CU < n_it) load_group(it + CU, wA);
+            consume(it, wB);
+            it += CU;
+            if (it >= n_it) break;
+        }
+    } else {
+        for (int c = lane; c < nchunk; c += 64) {
+            const u32x4 xv = reinterpret_cast<const u32x4*>(sx)[c];
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                const u32x4 w = reinterpret_cast<const u32x4*>(rows[r])[c];
+                acc[r] += dot8(w, xv);
+            }
         }
     }
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) acc[r] = wave_sum(acc[r]);
+    for (int r = 0; r < ROWS; ++r) acc[r] = wave_sum(acc[r]) * post_scale;
     if (lane != 0) return;
 #pragma unroll
     for (int u = 0; u < UNITS_PER_WAVE; ++u) {
@@ -141,45 +200,67 @@ typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 // One wavefront = one KV head x one 64-position tile.  Transposed formulation as in the prefill kernel:
 // S^T = K Q^T with the query heads of the group as MFMA columns (columns >= group are zero),
 // O^T = V^T P^T.  Every K / V element is used by exactly one wavefront, so operands are loaded from global
-// memory straight into MFMA fragment layout; no LDS.
+// memory straight into MFMA fragment layout; no LDS.  All loads of the tile (K and V) are issued before the
+// first MFMA and nothing tests a loaded value before it is used, so the wavefront pays one memory latency,
+// not one per fragment.  Key rows sit on MFMA rows with bits 2 and 3 swapped (as in the prefill kernel), which
+// makes every V^T fragment one 16-byte load.  Addresses are clamped instead of predicated: K rows past S
+// repeat row S-1 and are masked to -inf; V^T positions past S are stale but finite (the cache is zeroed when
+// the module is finalised and its rows are padded to whole tiles) and meet zero probabilities.
 template <int DHP>
 __global__ __launch_bounds__(64) void decode_attn_partial(DecodeAttnArgs p, float scale_log2, int n_tiles) {
     const int lane = threadIdx.x, lq = lane & 31, g2 = lane >> 5;
+    const int krow = (lq & 0x13) | ((lq & 4) << 1) | ((lq & 8) >> 1);
     const int tile = blockIdx.x, kvh = blockIdx.y;
     const int group = p.Hq / p.Hkv;
     const int j0 = tile * 64;
     const int h = kvh * group + lq;                    // this lane's query head (valid if lq < group)
+    const bf16_t* kbase = p.k + size_t(kvh) * p.k_head_stride;
+    const bf16_t* vbase = p.vt + size_t(kvh) * p.v_head_stride;
+    u32x4 kf[2][DHP / 16], vf[DHP / 32][4], qv[DHP / 16];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const bf16_t* kr = kbase + size_t(min(j0 + 32 * i + krow, p.S - 1)) * p.ldk;
+#pragma unroll
+        for (int kk = 0; kk < DHP / 16; ++kk) {
+            const int e = 16 * kk + 8 * g2;
+            kf[i][kk] = *reinterpret_cast<const u32x4*>(kr + (e < p.dh ? e : 0));
+        }
+    }
+#pragma unroll
+    for (int kk = 0; kk < DHP / 16; ++kk) {
+        const int e = 16 * kk + 8 * g2;
+        qv[kk] = *reinterpret_cast<const u32x4*>(p.q + size_t(min(h, p.Hq - 1)) * p.dh + (e < p.dh ? e : 0));
+    }
+#pragma unroll
+    for (int dt = 0; dt < DHP / 32; ++dt) {
+        const bf16_t* vr = vbase + size_t(min(32 * dt + lq, p.dh - 1)) * p.ldv + j0 + 8 * g2;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) vf[dt][q] = *reinterpret_cast<const u32x4*>(vr + 16 * q);   // q = 2*i + t2
+    }
     bf16x8 qf[DHP / 16];
 #pragma unroll
     for (int kk = 0; kk < DHP / 16; ++kk) {
         const int e = 16 * kk + 8 * g2;
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (lq < group && e < p.dh) v = *reinterpret_cast<const u32x4*>(p.q + size_t(h) * p.dh + e);
-        qf[kk] = *reinterpret_cast<bf16x8*>(&v);
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        const u32x4 v = (lq < group && e < p.dh) ? qv[kk] : z;     // padding columns and padding features are zero
+        qf[kk] = *reinterpret_cast<const bf16x8*>(&v);
     }
-    const bf16_t* kbase = p.k + size_t(kvh) * p.k_head_stride;
-    const bf16_t* vbase = p.vt + size_t(kvh) * p.v_head_stride;
     f32x16 accS[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) accS[i][r] = 0.0f;
-        const int row = j0 + 32 * i + lq;
-        const bf16_t* krow = kbase + size_t(min(row, p.S - 1)) * p.ldk;
 #pragma unroll
-        for (int kk = 0; kk < DHP / 16; ++kk) {
-            const int e = 16 * kk + 8 * g2;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (row < p.S && e < p.dh) v = *reinterpret_cast<const u32x4*>(krow + e);
-            accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&v), qf[kk], accS[i], 0, 0, 0);
-        }
+        for (int kk = 0; kk < DHP / 16; ++kk)
+            accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&kf[i][kk]), qf[kk], accS[i], 0, 0, 0);
     }
     float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int kv = j0 + 32 * i + 8 * (r >> 2) + 4 * g2 + (r & 3);
+            // accumulator row 8*(r/4) + 4*g2 + r%4 holds key 16*(r/8) + 8*g2 + r%8
+            const int kv = j0 + 32 * i + 16 * (r >> 3) + 8 * g2 + (r & 7);
             accS[i][r] = kv < p.S ? accS[i][r] : -INFINITY;
             mx = fmaxf(mx, accS[i][r]);
         }
@@ -203,25 +284,10 @@ __global__ __launch_bounds__(64) void decode_attn_partial(DecodeAttnArgs p, floa
     for (int dt = 0; dt < DHP / 32; ++dt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[dt][r] = 0.0f;
-        const int e = 32 * dt + lq;
-        const bf16_t* vrow = vbase + size_t(min(e, p.dh - 1)) * p.ldv + j0;
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                const int o = 32 * i + 16 * t2 + 4 * g2;
-                u32x2 lo = {0u, 0u}, hi = {0u, 0u};
-                if (e < p.dh) {                        // rows of the cache are padded to whole tiles: in bounds
-                    lo = *reinterpret_cast<const u32x2*>(vrow + o);
-                    hi = *reinterpret_cast<const u32x2*>(vrow + o + 8);
-                    // positions >= S hold stale memory: zero them (their probabilities are zero, but 0 * NaN is not)
-                    const int n_lo = p.S - (j0 + o), n_hi = n_lo - 8;
-                    if (n_lo < 4) { if (n_lo <= 0) lo[0] = 0u; else if (n_lo == 1) lo[0] &= 0xFFFFu; if (n_lo <= 2) lo[1] = 0u; else if (n_lo == 3) lo[1] &= 0xFFFFu; }
-                    if (n_hi < 4) { if (n_hi <= 0) hi[0] = 0u; else if (n_hi == 1) hi[0] &= 0xFFFFu; if (n_hi <= 2) hi[1] = 0u; else if (n_hi == 3) hi[1] &= 0xFFFFu; }
-                }
-                u32x4 av = {lo[0], lo[1], hi[0], hi[1]};
-                accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&av), pf[i][t2], accO[dt], 0, 0, 0);
-            }
+        for (int q = 0; q < 4; ++q)
+            accO[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&vf[dt][q]), pf[q >> 1][q & 1],
+                                                               accO[dt], 0, 0, 0);
     }
     if (lq >= group) return;
     float* dst = p.partial + (size_t(h) * n_tiles + tile) * (p.dh + 2);
@@ -235,20 +301,38 @@ __global__ __launch_bounds__(64) void decode_attn_partial(DecodeAttnArgs p, floa
         }
 }
 
-// merges the tiles of one head: out[e] = sum_t w_t o_t[e] / sum_t w_t l_t, w_t = 2^((m_t - M) * scale)
-__global__ __launch_bounds__(128) void decode_attn_merge(DecodeAttnArgs p, float scale_log2, int n_tiles) {
-    const int h = blockIdx.x, e = threadIdx.x;
+// merges the tiles of one head: out[e] = sum_t w_t o_t[e] / sum_t w_t l_t, w_t = 2^((m_t - M) * scale).
+// 4 x 128 threads: thread (e, part) folds the tiles t = part, part + 4, ... with a running maximum (its loads do
+// not depend on one another, so they are in flight together), then the four parts are folded through LDS in
+// fixed order.  Every tile holds at least one valid position, so every m_t is finite.
+__global__ __launch_bounds__(512) void decode_attn_merge(DecodeAttnArgs p, float scale_log2, int n_tiles) {
+    __shared__ float s_m[4], s_l[4], s_o[4][128];
+    const int h = blockIdx.x, e = threadIdx.x & 127, part = threadIdx.x >> 7;
     const float* src = p.partial + size_t(h) * n_tiles * (p.dh + 2);
-    float M = -INFINITY;
-    for (int t = 0; t < n_tiles; ++t) M = fmaxf(M, src[size_t(t) * (p.dh + 2)]);
-    float l = 0.0f, o = 0.0f;
-    for (int t = 0; t < n_tiles; ++t) {
+    float M = -INFINITY, l = 0.0f, o = 0.0f;
+#pragma unroll 4
+    for (int t = part; t < n_tiles; t += 4) {
         const float* s = src + size_t(t) * (p.dh + 2);
-        const float w = __builtin_amdgcn_exp2f((s[0] - M) * scale_log2);
-        l += w * s[1];
-        if (e < p.dh) o += w * s[2 + e];
+        const float m = s[0], lt = s[1], ot = e < p.dh ? s[2 + e] : 0.0f;
+        const float Mn = fmaxf(M, m);
+        const float a = __builtin_amdgcn_exp2f((M - Mn) * scale_log2), b = __builtin_amdgcn_exp2f((m - Mn) * scale_log2);
+        l = l * a + lt * b;
+        o = o * a + ot * b;
+        M = Mn;
     }
-    if (e < p.dh) p.out[size_t(h) * p.dh + e] = f_to_bf16(o / l);
+    if (e == 0) { s_m[part] = M; s_l[part] = l; }
+    s_o[part][e] = o;
+    __syncthreads();
+    if (part != 0 || e >= p.dh) return;
+    float Mt = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float L = 0.0f, O = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float w = __builtin_amdgcn_exp2f((s_m[k] - Mt) * scale_log2);   // a part without tiles has m = -inf: w = 0
+        L += w * s_l[k];
+        O += w * s_o[k][e];
+    }
+    p.out[size_t(h) * p.dh + e] = f_to_bf16(O / L);
 }
 
 }  // namespace
@@ -256,7 +340,7 @@ __global__ __launch_bounds__(128) void decode_attn_merge(DecodeAttnArgs p, float
 void gemv(const GemvArgs& a, hipStream_t st) {
     if (a.N <= 0) return;
     const int n_units = (a.epi == EPI_SWIGLU_BF16) ? a.N / 2 : a.N;
-    const int per_block = 4 * UNITS_PER_WAVE;
+    const int per_block = 4 * ((a.epi == EPI_SWIGLU_BF16) ? ROWS_PER_WAVE / 2 : ROWS_PER_WAVE);
     dim3 grid((n_units + per_block - 1) / per_block), block(256);
     const size_t lds = size_t(a.K) * 2;
     switch (a.epi) {
@@ -281,7 +365,7 @@ void decode_attention(const DecodeAttnArgs& a, hipStream_t st) {
     if (a.dh <= 64) hipLaunchKernelGGL(decode_attn_partial<64>, grid, block, 0, st, a, scale_log2, n_tiles);
     else if (a.dh <= 96) hipLaunchKernelGGL(decode_attn_partial<96>, grid, block, 0, st, a, scale_log2, n_tiles);
     else hipLaunchKernelGGL(decode_attn_partial<128>, grid, block, 0, st, a, scale_log2, n_tiles);
-    hipLaunchKernelGGL(decode_attn_merge, dim3(a.Hq), dim3(128), 0, st, a, scale_log2, n_tiles);
+    hipLaunchKernelGGL(decode_attn_merge, dim3(a.Hq), dim3(512), 0, st, a, scale_log2, n_tiles);
 }
 
 }  // namespace dlk

@@ -131,12 +131,22 @@ __global__ __launch_bounds__(256) void time_embed_kernel(const float* __restrict
 
 // Rotary embedding of q (in place) and k (to the cache, or in place): one workgroup per token.  The angle
 // depends on (position, i) only, so each thread evaluates one sin/cos pair and reuses it for every head.
+// FUSE_V (single-token passes): the block also scatters its token's V row into the transposed cache, which
+// saves the second launch where there is nothing to tile.
+template <bool FUSE_V>
 __global__ __launch_bounds__(256) void rope_kernel(QkvPostArgs p) {
     const int t = blockIdx.x, pos = p.pos0 + t;
     bf16_t* row = p.qkv + size_t(t) * p.n_qkv;
     const int half = p.dh >> 1;
     const int lanes = half < 256 ? half : 256;            // threads that own a frequency index
     const int i = threadIdx.x % lanes, hg = threadIdx.x / lanes, n_hg = 256 / lanes;
+    if (FUSE_V) {
+        const int ncol = p.Hkv * p.dh;
+        for (int col = threadIdx.x; col < ncol; col += 256) {
+            const int g = col / p.dh, e = col % p.dh;
+            p.vt_out[size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + pos] = row[p.v_off + col];
+        }
+    }
     float sn = 0.0f, cs = 1.0f;
     if (p.theta > 0.0f) {
         const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * log2f(p.theta));
@@ -310,7 +320,11 @@ void add_time_embedding(const float* x, float* y, float tval, int T, int d, hipS
 
 void qkv_post(const QkvPostArgs& a, hipStream_t st) {
     if (a.T <= 0) return;
-    hipLaunchKernelGGL(rope_kernel, dim3(a.T), dim3(256), 0, st, a);
+    if (a.T <= 4) {
+        hipLaunchKernelGGL(rope_kernel<true>, dim3(a.T), dim3(256), 0, st, a);
+        return;
+    }
+    hipLaunchKernelGGL(rope_kernel<false>, dim3(a.T), dim3(256), 0, st, a);
     hipLaunchKernelGGL(v_transpose_kernel, dim3((a.T + 63) / 64, (a.Hkv * a.dh + 63) / 64), dim3(256), 0, st, a);
 }
 
