@@ -330,6 +330,7 @@ def main():
     ap.add_argument("--sweep", type=str, default="0,9,18,27,33,35,36")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode, ViT and pipeline legs")
+    ap.add_argument("--extras", default="decode,vit,vla", help="which of the extra legs to run (comma list)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE), then "
                          "the timed steps at full residency; no sweep, no extras, no CPU leg")
@@ -552,7 +553,8 @@ def main():
 
     # ---- decode leg (configs[3]): same stack, KV cache from the 3072-token prefill, greedy steps ----
     extras = {}
-    if not args.no_extras:
+    legs = set() if args.no_extras else {x.strip() for x in args.extras.split(",") if x.strip()}
+    if "decode" in legs:
         try:
             extras["decode"] = decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log)
         except B.DLError as e:
@@ -605,11 +607,12 @@ def main():
         "extras": extras,
     }
     eng.close()
-    if not args.no_extras:
+    if "vit" in legs:
         try:
             out["extras"]["vit"] = vit_leg(B, CFG, Engine, torch, log)
         except B.DLError as e:
             out["extras"]["vit"] = {"error": str(e)}
+    if "vla" in legs:
         try:
             out["extras"]["vla"] = vla_leg(B, CFG, Engine, torch, log, cap)
         except B.DLError as e:
