@@ -153,7 +153,8 @@ int32_t dl_set_run_ahead(dl_ctx* ctx, int32_t passes);
  * (may equal x_dev).  Token t sits at absolute position pos0 + t; with a KV cache the pass appends
  * its keys/values at those positions and attends over 0 .. pos0+t.  pos0 must be 0 without a cache.
  * ctx_dev: device fp32 [n_ctx, d_ctx] (cross-attention source) or NULL.
- * n_tokens <= 4 takes the decode kernels (weight-streaming GEMV), otherwise the MFMA GEMM path. */
+ * n_tokens == 1 takes the decode kernels (weight-streaming matrix-vector products, split-key attention over the
+ * KV cache), otherwise the MFMA GEMM / tiled attention path. */
 int32_t dl_forward(dl_ctx* ctx, int32_t module, const void* x_dev, void* y_dev, int32_t n_tokens,
                    int32_t pos0, const void* ctx_dev, int32_t n_ctx);
 /* x_dev[d_model] (fp32) = embedding row `token`, on the compute stream. */

@@ -205,7 +205,7 @@ using dlk::bf16_t;
 void linear(hipStream_t st, int T, const bf16_t* A, int lda, const bf16_t* B, int K, int N, const bf16_t* bias,
             int epi, void* out, int ldo, const float* resid, int ldr) {
     if (T == 1) {
-        dlk::GemvArgs g{A, B, K, bias, out, resid, N, K, epi, nullptr, nullptr, nullptr, 0, 0.0f};
+        dlk::GemvArgs g{A, B, K, bias, out, resid, N, K, epi};
         dlk::gemv(g, st);
     } else {
         dlk::GemmArgs g{A, lda, B, K, bias, out, ldo, resid, ldr, T, N, K, epi};
@@ -250,25 +250,13 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     };
     double fl, by;
 
-    // single-token passes: the normalisation is folded into the matrix-vector kernel that consumes it
-    const bool fuse_norm = (T == 1);
-    auto gemv_normed = [&](const float* xin, uint64_t g_off, uint64_t b_off, uint64_t w_off, uint64_t bias_off, int N_,
-                           int epi, void* dst) {
-        dlk::GemvArgs g{nullptr, P(w_off), dm, P(bias_off), dst, nullptr, N_, dm, epi, xin, P(g_off), P(b_off), d.norm,
-                        d.norm_eps};
-        dlk::gemv(g, st);
-    };
-
     // attention sub-block
-    if (!fuse_norm) {
-        kbegin(DL_K_NORM, 0, Td * dm * 6.0);
-        dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
-        kend();
-    }
+    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
+    dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
+    kend();
     lin_work(Td, L.n_qkv, dm, &fl, &by);
     kbegin(DL_K_GEMM_QKV, fl, by);
-    if (fuse_norm) gemv_normed(in, L.norm1_g, L.norm1_b, L.w_qkv, L.b_qkv, L.n_qkv, dlk::EPI_BF16, qkv);
-    else linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
+    linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
     kend();
     bf16_t* kc = nullptr;
     bf16_t* vt;
@@ -335,17 +323,12 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     }
 
     // feed-forward sub-block
-    if (!fuse_norm) {
-        kbegin(DL_K_NORM, 0, Td * dm * 6.0);
-        dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
-        kend();
-    }
+    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
+    dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
+    kend();
     lin_work(Td, L.n_up, dm, &fl, &by);
     kbegin(DL_K_GEMM_UP, fl, 2.0 * (Td * dm + double(L.n_up) * dm + Td * d.d_ff));
-    if (fuse_norm)
-        gemv_normed(out, L.norm2_g, L.norm2_b, L.w_up, d.act == DL_ACT_SWIGLU ? PackLayout::kNone : L.b_up, L.n_up,
-                    d.act == DL_ACT_SWIGLU ? dlk::EPI_SWIGLU_BF16 : dlk::EPI_GELU_BF16, mid);
-    else if (d.act == DL_ACT_SWIGLU)
+    if (d.act == DL_ACT_SWIGLU)
         linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, L.ffp, nullptr, 0);
     else
         linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, L.ffp, nullptr, 0);
@@ -769,7 +752,7 @@ static int32_t head_common(dl_ctx* c, Module* M, const void* h) {
                    M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr,
                    nbuf, false, 1, M->d.d_model, M->d.norm_eps, st);
     dlk::GemvArgs g{nbuf, reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_HEAD]), M->d.d_model, nullptr,
-                    logits, nullptr, M->d.vocab, M->d.d_model, dlk::EPI_F32, nullptr, nullptr, nullptr, 0, 0.0f};
+                    logits, nullptr, M->d.vocab, M->d.d_model, dlk::EPI_F32};
     dlk::gemv(g, st);
     dlk::argmax_f32(logits, M->d.vocab, tok, st);
     DL_HIP(c, hipGetLastError());

@@ -30,15 +30,13 @@ void gemm(const GemmArgs& a, hipStream_t st);
 
 // ---- matrix-vector for single-token passes: out[N] = B[N,K] * x[K], same epilogues ----------
 struct GemvArgs {
-    const bf16_t* x;              // [K] bf16 (used when xf == nullptr)
+    const bf16_t* x;              // [K] bf16
     const bf16_t* B; int ldb;     // [N,K]
     const bf16_t* bias;
     void* out;
     const float* resid;
     int N, K;
     int epi;
-    // optional fused normalisation of the input: x = Norm(xf) rounded to bf16 (norm_kind 0 RMS, 1 LayerNorm)
-    const float* xf; const bf16_t* ng; const bf16_t* nb; int norm_kind; float eps;
 };
 void gemv(const GemvArgs& a, hipStream_t st);
 

@@ -41,29 +41,17 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// sum over a 256-thread block; every thread gets the result
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
-    v = wave_sum(v);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __syncthreads();
-    if (lane == 0) red[wave] = v;
-    __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
-}
-
-// rows a wavefront streams together: 4 (two SwiGLU units = 2 gate + 2 up rows, or four plain units)
-constexpr int ROWS_PER_WAVE = 4;
 
 // a "unit" is one output element; for SwiGLU it needs two weight rows (gate and up)
-template <int EPI>
+// ROWS: rows a wavefront streams together (4: two SwiGLU units = 2 gate + 2 up rows, or four plain units; 2 for
+// matrices with so few rows that 4 would leave compute units without a workgroup)
+template <int EPI, int ROWS>
 __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
     extern __shared__ __attribute__((aligned(16))) bf16_t sx[];
-    __shared__ float red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunk = p.K >> 3;
 
     const int n_units = (EPI == EPI_SWIGLU_BF16) ? p.N / 2 : p.N;
-    constexpr int ROWS = ROWS_PER_WAVE;
     constexpr int UNITS_PER_WAVE = (EPI == EPI_SWIGLU_BF16) ? ROWS / 2 : ROWS;
     const int u0 = (blockIdx.x * 4 + wave) * UNITS_PER_WAVE;
     const bf16_t* rows[ROWS];
@@ -82,9 +70,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
         }
     }
     // Weight pieces are fetched 4 rows x CU pieces (of 64 chunks = 1 KB) at a time = 16 independent 16-byte loads
-    // per lane, double-buffered, and the FIRST group is requested before the input vector is prepared: all
-    // workgroups of a launch are resident together, so without that the memory system would idle while every one
-    // of them normalises the input.  Wavefronts start at different pieces of their rows (rotation).
+    // per lane, double-buffered, and the FIRST group is requested before the input vector is copied to LDS.  Wavefronts start at different pieces of their rows (rotation).
     constexpr int CU = 4;
     const int n_it = nchunk >> 6;
     const bool piped = (nchunk & 63) == 0 && (n_it % CU) == 0;
@@ -105,40 +91,9 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
     u32x4 wA[ROWS][CU], wB[ROWS][CU];
     if (piped) load_group(0, wA);
 
-    float post_scale = 1.0f;                            // factor applied to the dot products (RMS fusion)
-    if (p.xf && p.norm_kind == 0) {
-        // Fused RMSNorm in ONE pass and one barrier: the vector goes to LDS as bf16(x * g) while its sum of squares
-        // is gathered, and the scalar 1/rms, which is common to all elements, multiplies the finished dot
-        // products instead of every element (W (x g / rms) = (W (x g)) / rms).
-        float ss = 0.0f;
-        for (int i = tid; i < p.K; i += 256) {
-            const float v = p.xf[i];
-            ss += v * v;
-            sx[i] = f_to_bf16(v * bf16_to_f(p.ng[i]));
-        }
-        ss = wave_sum(ss);
-        if (lane == 0) red[wave] = ss;
-        __syncthreads();
-        post_scale = rsqrtf((red[0] + red[1] + red[2] + red[3]) / float(p.K) + p.eps);
-    } else if (p.xf) {
-        // fused LayerNorm: every workgroup normalises the (small) input vector for itself
-        float s1 = 0.0f;
-        for (int i = tid; i < p.K; i += 256) s1 += p.xf[i];
-        const float mean = block_sum_256(s1, red) / float(p.K);
-        float ss = 0.0f;
-        for (int i = tid; i < p.K; i += 256) {
-            const float c = p.xf[i] - mean;
-            ss += c * c;
-        }
-        const float inv = rsqrtf(block_sum_256(ss, red) / float(p.K) + p.eps);
-        for (int i = tid; i < p.K; i += 256)
-            sx[i] = f_to_bf16((p.xf[i] - mean) * inv * bf16_to_f(p.ng[i]) + bf16_to_f(p.nb[i]));
-        __syncthreads();
-    } else {
-        for (int c = tid; c < nchunk; c += 256)
-            reinterpret_cast<u32x4*>(sx)[c] = reinterpret_cast<const u32x4*>(p.x)[c];
-        __syncthreads();
-    }
+    for (int c = tid; c < nchunk; c += 256)
+        reinterpret_cast<u32x4*>(sx)[c] = reinterpret_cast<const u32x4*>(p.x)[c];
+    __syncthreads();
 
     float acc[ROWS];
 #pragma unroll
@@ -174,7 +129,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
         }
     }
 #pragma unroll
-    for (int r = 0; r < ROWS; ++r) acc[r] = wave_sum(acc[r]) * post_scale;
+    for (int r = 0; r < ROWS; ++r) acc[r] = wave_sum(acc[r]);
     if (lane != 0) return;
 #pragma unroll
     for (int u = 0; u < UNITS_PER_WAVE; ++u) {
@@ -337,18 +292,28 @@ __global__ __launch_bounds__(512) void decode_attn_merge(DecodeAttnArgs p, float
 
 }  // namespace
 
+template <int EPI>
+void launch_gemv(const GemvArgs& a, int n_units, hipStream_t st) {
+    const size_t lds = size_t(a.K) * 2;
+    constexpr bool SW = EPI == EPI_SWIGLU_BF16;
+    // 4 rows per wavefront unless that gives fewer than two workgroups per compute unit
+    const int blocks4 = (n_units + (SW ? 8 : 16) - 1) / (SW ? 8 : 16);
+    if (SW || blocks4 >= 512) {
+        hipLaunchKernelGGL((gemv_kernel<EPI, 4>), dim3(blocks4), dim3(256), lds, st, a);
+    } else {
+        hipLaunchKernelGGL((gemv_kernel<EPI, 2>), dim3((n_units + 7) / 8), dim3(256), lds, st, a);
+    }
+}
+
 void gemv(const GemvArgs& a, hipStream_t st) {
     if (a.N <= 0) return;
     const int n_units = (a.epi == EPI_SWIGLU_BF16) ? a.N / 2 : a.N;
-    const int per_block = 4 * ((a.epi == EPI_SWIGLU_BF16) ? ROWS_PER_WAVE / 2 : ROWS_PER_WAVE);
-    dim3 grid((n_units + per_block - 1) / per_block), block(256);
-    const size_t lds = size_t(a.K) * 2;
     switch (a.epi) {
-        case EPI_BF16: hipLaunchKernelGGL(gemv_kernel<EPI_BF16>, grid, block, lds, st, a); break;
-        case EPI_RESID_F32: hipLaunchKernelGGL(gemv_kernel<EPI_RESID_F32>, grid, block, lds, st, a); break;
-        case EPI_SWIGLU_BF16: hipLaunchKernelGGL(gemv_kernel<EPI_SWIGLU_BF16>, grid, block, lds, st, a); break;
-        case EPI_GELU_BF16: hipLaunchKernelGGL(gemv_kernel<EPI_GELU_BF16>, grid, block, lds, st, a); break;
-        default: hipLaunchKernelGGL(gemv_kernel<EPI_F32>, grid, block, lds, st, a); break;
+        case EPI_BF16: launch_gemv<EPI_BF16>(a, n_units, st); break;
+        case EPI_RESID_F32: launch_gemv<EPI_RESID_F32>(a, n_units, st); break;
+        case EPI_SWIGLU_BF16: launch_gemv<EPI_SWIGLU_BF16>(a, n_units, st); break;
+        case EPI_GELU_BF16: launch_gemv<EPI_GELU_BF16>(a, n_units, st); break;
+        default: launch_gemv<EPI_F32>(a, n_units, st); break;
     }
 }
 
