@@ -62,9 +62,9 @@ struct dl_ctx {
     hipEvent_t ev_dma[2] = {nullptr, nullptr}, ev_comp[2] = {nullptr, nullptr}, ev_pass = nullptr;
     bool events_made = false;
     static constexpr int kMaxRunAhead = 8;
-    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // end of the most recent passes on the compute stream (host throttle)
-    uint64_t n_passes = 0;
-    int32_t run_ahead = 1;                        // passes the host may have enqueued and unfinished; 0 = unlimited
+    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // copy-stream end of the most recent streaming passes (host throttle)
+    uint64_t n_passes = 0;                       // streaming passes enqueued so far
+    int32_t run_ahead = 1;                        // streaming passes whose copies may be outstanding; 0 = unlimited
     int32_t mode = DL_MODE_PIPELINED, wrap = 0;
     bool tracing = false;
     std::vector<dl_trace_op> trace;
@@ -353,11 +353,14 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
     dl::build_pass(mi, M.d.n_layers, M.resident.data(), c->mode, c->wrap, force_all, &c->book, &ops);
     if (c->tracing || !on_gpu(c)) c->trace.insert(c->trace.end(), ops.begin(), ops.end());
     if (!on_gpu(c)) return DL_OK;
-    // Bounded run-ahead: by default the host enqueues a pass only once the previous one has finished (it still
-    // runs ahead of the GPU inside the pass: enqueuing takes a tenth of the pass time or less).  Every further pass
-    // of short streamed layers kept in flight made copies and kernels slower on MI355X (27-layer encoder, fully
-    // streamed: 15.4 ms per pass with one pass in flight, 16.0 with two, 17.7 with three, 19 with four).
-    if (c->run_ahead > 0 && c->n_passes >= uint64_t(c->run_ahead))
+    // Bounded run-ahead for passes that stream: by default the host enqueues such a pass only once the copies of
+    // the previous streaming pass have all landed (its last layers may still be executing, which covers the
+    // host's wake-up and enqueue latency).  Every further pass of short streamed layers kept in flight made copies
+    // and kernels slower on MI355X (27-layer encoder, fully streamed: 15.4 ms per pass with one pass in flight,
+    // 16.0 with two, 17.7 with three, 19 with four).  Passes without copies are never held back.
+    bool has_copy = false;
+    for (const dl_trace_op& o : ops) has_copy = has_copy || o.op == DL_OP_COPY;
+    if (has_copy && c->run_ahead > 0 && c->n_passes >= uint64_t(c->run_ahead))
         DL_HIP(c, hipEventSynchronize(c->ev_inflight[(c->n_passes - uint64_t(c->run_ahead)) % dl_ctx::kMaxRunAhead]));
     for (const dl_trace_op& o : ops) {
         hipStream_t st = o.queue == 0 ? c->s_compute : c->s_copy;
@@ -408,8 +411,10 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
             default: break;
         }
     }
-    DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_compute));
-    ++c->n_passes;
+    if (has_copy) {
+        DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_copy));
+        ++c->n_passes;
+    }
     return DL_OK;
 }
 
@@ -1015,15 +1020,38 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
             fence[size_t(i)] += std::max(0.0, in) + std::max(0.0, outw);
         }
     }
-    // all layers back to back, no copies: execution time under continuous load (second of two runs)
-    for (int32_t rep = 0; rep < 2 && rc == DL_OK; ++rep) {
+    // all layers back to back, no copies: execution time under continuous load.  The last of kHotReps runs counts:
+    // the chip is power-limited, and the first passes after an idle spell still run at a higher clock than a
+    // sustained sequence of passes does.
+    // Resident layers read weights that have long left the caches (a whole stack is far larger than the 256 MB
+    // memory-side cache), so the run must not keep re-reading one slot: the layers rotate through the two slots plus
+    // as many temporary copies as it takes to exceed that cache (or as the arena can spare).
+    std::vector<uint64_t> rot = {c->slot_off[0], c->slot_off[1]};
+    std::vector<uint64_t> rot_tmp;
+    {
+        const uint64_t want = (320ull << 20) / M->L.bytes + 1;
+        for (uint64_t j = 0; j < want && j < 16 && int64_t(j) + 2 < Ln; ++j) {
+            uint64_t off = 0;
+            if (!c->arena.alloc(M->L.bytes, &off)) break;
+            if (hipMemcpyAsync(c->base + off, M->store + size_t(j % uint64_t(Ln)) * M->L.bytes, M->L.bytes,
+                               hipMemcpyHostToDevice, c->s_compute) != hipSuccess) {
+                c->arena.free(off);
+                rc = fail(c, DL_ERR_DEVICE, "copy of a temporary weight block failed");
+                break;
+            }
+            rot_tmp.push_back(off);
+            rot.push_back(off);
+        }
+    }
+    constexpr int32_t kHotReps = 4;
+    for (int32_t rep = 0; rep < kHotReps && rc == DL_OK; ++rep) {
         for (int32_t i = 0; i < Ln && rc == DL_OK; ++i) {
             TimedOp t{nullptr, nullptr, module, i, -1, -1};
             rc = timing_event(c, &t.e0);
             if (rc == DL_OK) rc = timing_event(c, &t.e1);
             if (rc) break;
             if (hipEventRecord(t.e0, c->s_compute) != hipSuccess) { rc = fail(c, DL_ERR_DEVICE, "event record failed"); break; }
-            run_layer(c, *M, i, c->base + c->slot_off[0], i == 0 ? static_cast<const float*>(x) : scratch, scratch, T, pos0,
+            run_layer(c, *M, i, c->base + rot[size_t(i) % rot.size()], i == 0 ? static_cast<const float*>(x) : scratch, scratch, T, pos0,
                       static_cast<const float*>(ctx), n_ctx);
             if (hipEventRecord(t.e1, c->s_compute) != hipSuccess) { rc = fail(c, DL_ERR_DEVICE, "event record failed"); break; }
             c->execs.push_back(t);
@@ -1033,7 +1061,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         std::vector<dl_layer_record> recs;
         recs.resize(size_t(Ln));
         rc = dl_collect_stats(c, &st, recs.data(), Ln);
-        if (rc == DL_OK && rep == 1) {
+        if (rc == DL_OK && rep == kHotReps - 1) {
             // start-to-start spacing, so that launch gaps between layers are part of the figure
             double gap = 0;
             for (int32_t i = 0; i + 1 < Ln; ++i) {
@@ -1044,12 +1072,35 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
                                   (Ln > 1 ? gap / (Ln - 1) : 0.0);
         }
     }
+    // The event pairs between the layers drain the queue (a few microseconds per layer, which is percents for short
+    // layers): one more run with events only around the whole stack gives the true total, and the per-layer figures
+    // are scaled to it.
+    if (rc == DL_OK) {
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        rc = timing_event(c, &e0);
+        if (rc == DL_OK) rc = timing_event(c, &e1);
+        if (rc == DL_OK) {
+            (void)hipEventRecord(e0, c->s_compute);
+            for (int32_t i = 0; i < Ln; ++i)
+                run_layer(c, *M, i, c->base + rot[size_t(i) % rot.size()], i == 0 ? static_cast<const float*>(x) : scratch,
+                          scratch, T, pos0, static_cast<const float*>(ctx), n_ctx);
+            (void)hipEventRecord(e1, c->s_compute);
+            float total = 0.0f;
+            if (hipStreamSynchronize(c->s_compute) != hipSuccess || hipEventElapsedTime(&total, e0, e1) != hipSuccess)
+                rc = fail(c, DL_ERR_DEVICE, "timing the uninterrupted run failed");
+            double sum = 0.0;
+            for (int32_t i = 0; i < Ln; ++i) sum += hot[size_t(i)];
+            if (rc == DL_OK && sum > 0.0 && total > 0.0f)
+                for (int32_t i = 0; i < Ln; ++i) hot[size_t(i)] *= double(total) / sum;
+        }
+    }
     c->mode = mode0;
     c->wrap = wrap0;
     c->timing = timing0;
     c->tracing = tracing0;
     c->book = dl::SlotBook();
     sync_streams(c);
+    for (uint64_t off : rot_tmp) c->arena.free(off);
     c->copies.clear();
     c->execs.clear();
     if (c->krecs.empty()) c->ev_next = 0;

@@ -35,10 +35,14 @@ namespace {
 constexpr int BM = 128, BN = 128, BK = 64;
 constexpr int LDS_LD = BK + 8;   // row stride in elements: 144 bytes keeps 16-byte alignment and staggers banks
 
-__device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
+// x * sigmoid(x); the quotient is a multiplication with the hardware reciprocal (1 ulp), not an IEEE division
+__device__ __forceinline__ float silu_f(float x) { return x * __frcp_rn(1.0f + __expf(-x)); }
+// tanh form of GELU: 0.5 x (1 + tanh u) = x * sigmoid(2u), u = sqrt(2/pi) (x + 0.044715 x^3): one exponential and
+// one reciprocal instead of a library tanh (which dominated the epilogue of the encoder's MLP GEMM)
 __device__ __forceinline__ float gelu_tanh_f(float x) {
-    const float c = 0.7978845608028654f;   // sqrt(2/pi)
-    return 0.5f * x * (1.0f + tanhf(c * (x + 0.044715f * x * x * x)));
+    const float c2 = 2.0f * 0.7978845608028654f;
+    const float u2 = c2 * (x + 0.044715f * x * x * x);
+    return x * __frcp_rn(1.0f + __expf(-u2));
 }
 __device__ __forceinline__ float bf16_to_f(bf16_t v) { return __uint_as_float(uint32_t(v) << 16); }
 __device__ __forceinline__ bf16_t f_to_bf16(float f) {
@@ -395,18 +399,24 @@ void launch_fast(const GemmArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((gemm_fast<BM, BN, EPI>), dim3(grid), dim3(256), 0, st, a);
 }
 
-// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192.  Fewest rounds of 256
-// workgroups weighted by tile area; the smaller tiles are a little less efficient per flop.
-int pick_tile(int M, int N, bool need_even_cols) {
-    const int bm[4] = {256, 192, 256, 192}, bn[4] = {256, 256, 192, 192};
-    const double eff[4] = {1.0, 0.93, 0.93, 0.86};
+// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192, 4 = 128x192.  Cost of a shape =
+// rounds of workgroup slots x tile area / relative efficiency, the efficiencies fitted to measured launch times.
+// Shapes 0-3 hold one workgroup per compute unit (256 slots).  128x192 needs 80 KB of LDS, so two workgroups share a
+// compute unit (512 slots at half speed each, but one's prologue and epilogue hide under the other's main loop); it is
+// considered only for short reductions or narrow outputs (the encoder's K = 1152 and N = 1152 GEMMs), where the
+// large tiles leave compute units idle or spend their time outside the main loop.
+int pick_tile(int M, int N, int K, bool need_even_cols) {
+    const int bm[5] = {256, 192, 256, 192, 128}, bn[5] = {256, 256, 192, 192, 192};
+    const double eff[5] = {1.0, 0.93, 0.93, 0.86, 1.34};
+    const int n_cand = (!need_even_cols && (K <= 2048 || N <= 1536)) ? 5 : 4;
     int best = 0;
     double best_cost = 1e300;
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 0; c < n_cand; ++c) {
         if (need_even_cols && bn[c] != 256) continue;
         const long tiles = long((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
-        const double rounds = tiles >= 768 ? double(tiles) / 256.0 : double((tiles + 255) / 256);
-        const double cost = rounds * bm[c] * bn[c] / eff[c];
+        const long slots = c == 4 ? 512 : 256;
+        const double rounds = tiles >= 3 * slots ? double(tiles) / double(slots) : double((tiles + slots - 1) / slots);
+        const double cost = rounds * (c == 4 ? 2.0 : 1.0) * bm[c] * bn[c] / eff[c];
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
     return best;
@@ -414,13 +424,14 @@ int pick_tile(int M, int N, bool need_even_cols) {
 
 template <int EPI>
 void dispatch_fast(const GemmArgs& a, hipStream_t st) {
-    const int t = pick_tile(a.M, a.N, EPI == EPI_SWIGLU_BF16);
+    const int t = pick_tile(a.M, a.N, a.K, EPI == EPI_SWIGLU_BF16);
     if (t == 0) launch_fast<256, 256, EPI>(a, st);
     else if (t == 1) launch_fast<192, 256, EPI>(a, st);
     else if (EPI != EPI_SWIGLU_BF16) {
         // odd numbers of 32-wide tile columns per wavefront cannot pair gate/up rows: never chosen for SwiGLU
         if (t == 2) launch_fast<256, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
-        else launch_fast<192, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+        else if (t == 3) launch_fast<192, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+        else launch_fast<128, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
     }
 }
 
