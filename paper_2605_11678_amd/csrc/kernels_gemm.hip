@@ -258,23 +258,17 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int* 
 #define DL_WAIT_VM(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 #define DL_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0x0 << 8))
 
+// One output tile with its top-left corner at (m0, n0).  S0..S3 are the four LDS stages; they must be four distinct
+// __shared__ arrays of at least (BM + BN) * 32 elements each.
 template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
+__device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf16_t* S0, bf16_t* S1, bf16_t* S2, bf16_t* S3) {
     constexpr int BK = 32;
     constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;
     constexpr int JA = BM / 64, JB = BN / 64;            // 1 KB copy blocks (16 rows x 64 B) per wavefront and k-tile
     constexpr int NL = JA + JB;
     static_assert(3 * NL < 64, "outstanding copies must fit the vmcnt field");
-    __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * BK];
-    __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * BK];
-    __shared__ __attribute__((aligned(1024))) bf16_t S2[(BM + BN) * BK];
-    __shared__ __attribute__((aligned(1024))) bf16_t S3[(BM + BN) * BK];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
-    int tm, tn;
-    if (!tile_of(blockIdx.x, tiles_m, tiles_n, &tm, &tn)) return;
-    const int m0 = tm * BM, n0 = tn * BN;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -393,8 +387,52 @@ __global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
 }
 
 template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
+    __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S2[(BM + BN) * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S3[(BM + BN) * 32];
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    int tm, tn;
+    if (!tile_of(blockIdx.x, tiles_m, tiles_n, &tm, &tn)) return;
+    fast_tile<BM, BN, EPI>(p, tm * BM, tn * BN, S0, S1, S2, S3);
+}
+
+// 256x256 tiles whose count is r full rounds of 256 workgroups plus a remainder of at most half a round: the last
+// `n_split` tiles are computed as two 128x256 halves each, so the final round holds twice as many workgroups of
+// half the work and ends in half the time instead of leaving most compute units idle for a whole tile time.
+// Block b < n_big computes whole tile b (in the XCD-aware order), block n_big + 2 j + h half h of tile n_big + j.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_fast_split_tail(GemmArgs p, int n_big) {
+    __shared__ __attribute__((aligned(1024))) bf16_t S0[512 * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S1[512 * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S2[512 * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S3[512 * 32];
+    const int tiles_m = (p.M + 255) / 256, tiles_n = (p.N + 255) / 256;
+    const int b = blockIdx.x;
+    const int v = b < n_big ? b : n_big + ((b - n_big) >> 1);
+    int tm, tn;
+    if (!tile_of(v, tiles_m, tiles_n, &tm, &tn)) return;
+    if (b < n_big) {
+        fast_tile<256, 256, EPI>(p, tm * 256, tn * 256, S0, S1, S2, S3);
+    } else {
+        const int m0 = tm * 256 + 128 * ((b - n_big) & 1);
+        if (m0 < p.M) fast_tile<128, 256, EPI>(p, m0, tn * 256, S0, S1, S2, S3);
+    }
+}
+
+template <int BM, int BN, int EPI>
 void launch_fast(const GemmArgs& a, hipStream_t st) {
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    if (BM == 256 && BN == 256) {
+        // tile_of deals tiles to 8 XCDs in equal shares: the split needs every virtual index below `tiles` to be valid
+        const int rem = tiles % 256;
+        if (tiles > 256 && tiles % 8 == 0 && rem > 0 && rem <= 128) {
+            const int n_big = tiles - rem;
+            hipLaunchKernelGGL((gemm_fast_split_tail<EPI>), dim3(n_big + 2 * rem), dim3(256), 0, st, a, n_big);
+            return;
+        }
+    }
     const int grid = (tiles + 7) / 8 * 8;
     hipLaunchKernelGGL((gemm_fast<BM, BN, EPI>), dim3(grid), dim3(256), 0, st, a);
 }
