@@ -445,7 +445,7 @@ def main():
     tj = os.path.join(ROOT, "profiles", "traffic_gemm_up_decoder8b_prefill.json")
     if os.path.exists(tj) and L == 36 and T == 3072:
         traffic = round(json.load(open(tj))["bytes_per_launch"])
-    roofline = {"bound": "mfma", "kernel": "gemm_fast<256,256,SwiGLU> (gate/up projection, M=%d N=%d K=%d)" % (T, 2 * c.d_ff, c.d_model),
+    roofline = {"bound": "mfma", "kernel": "gemm_fast_split_tail<SwiGLU>: 256x256 tiles, last half round as 128x256 (gate/up projection, M=%d N=%d K=%d)" % (T, 2 * c.d_ff, c.d_model),
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic, "launches": dom["launches"],
                 "avg_launch_ms": round(dom["total_ms"] / max(dom["launches"], 1), 4),

@@ -324,7 +324,9 @@ void qkv_post(const QkvPostArgs& a, hipStream_t st) {
         hipLaunchKernelGGL(rope_kernel<true>, dim3(a.T), dim3(256), 0, st, a);
         return;
     }
-    hipLaunchKernelGGL(rope_kernel<false>, dim3(a.T), dim3(256), 0, st, a);
+    // without a rotary embedding and without a cache to append K to there is nothing for the first kernel to do
+    if (a.theta > 0.0f || a.k_out)
+        hipLaunchKernelGGL(rope_kernel<false>, dim3(a.T), dim3(256), 0, st, a);
     hipLaunchKernelGGL(v_transpose_kernel, dim3((a.T + 63) / 64, (a.Hkv * a.dh + 63) / 64), dim3(256), 0, st, a);
 }
 
