@@ -50,9 +50,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     // (16*t2 + 8*g2 + 0..7), so the matching V^T fragment is one 16-byte read.
     const int krow = (lq & 0x13) | ((lq & 4) << 1) | ((lq & 8) >> 1);
     const int group = p.Hq / p.Hkv;
-    // causal passes: the last query blocks see the most keys; launch them first so the tail of the grid is short
-    const int q0 = (p.causal ? int(gridDim.x) - 1 - int(blockIdx.x) : int(blockIdx.x)) * QB;
-    const int h = HEADS ? blockIdx.y * 4 + wave : blockIdx.y;
+    // Workgroups are dispatched in blockIdx order, x fastest.  x is the head (group) and y the query block, taken
+    // from the last one down in causal passes: the whole launch runs its longest jobs (most visible keys) first, in
+    // every head at once, so the tail of the launch is made of the shortest ones.  (With the query block in x, each
+    // head's short blocks were dispatched before the next head's long ones.)  Consecutive workgroups go to
+    // consecutive XCDs, so with 8 heads (groups) a head's K and V stay in one XCD's L2.
+    const int q0 = (p.causal ? int(gridDim.y) - 1 - int(blockIdx.y) : int(blockIdx.y)) * QB;
+    const int h = HEADS ? blockIdx.x * 4 + wave : blockIdx.x;
     const int kvh = h / group;
     const int wq0 = HEADS ? q0 : q0 + 32 * wave;       // first query of this wavefront
     const int tq = wq0 + lq;                           // this lane's query (token index)
@@ -272,10 +276,10 @@ template <int DHP>
 void launch_attn(const AttnArgs& a, float scale_log2, hipStream_t st) {
     const int group = a.Hq / a.Hkv;
     if (group % 4 == 0) {
-        dim3 grid((a.T + 31) / 32, a.Hq / 4), block(256);
+        dim3 grid(a.Hq / 4, (a.T + 31) / 32), block(256);
         hipLaunchKernelGGL((attn_kernel<DHP, true>), grid, block, 0, st, a, scale_log2);
     } else {
-        dim3 grid((a.T + 127) / 128, a.Hq), block(256);
+        dim3 grid(a.Hq, (a.T + 127) / 128), block(256);
         hipLaunchKernelGGL((attn_kernel<DHP, false>), grid, block, 0, st, a, scale_log2);
     }
 }
