@@ -7,8 +7,8 @@
 // exchange with lane l^32, the running max / sum / rescale are per-lane scalars, and the
 // probabilities P^T are already in B-operand position for O^T = V^T * P^T (8 consecutive
 // accumulator registers = the 8 k-values a lane supplies).  The keys of a score tile are assigned to
-// MFMA rows with bits 2 and 3 of the row index swapped, which makes those 8 k-values 8 consecutive keys.  V is kept transposed in memory
-// ([feature][position]) so V^T tiles are plain row loads.
+// MFMA rows with bits 2 and 3 of the row index swapped, which makes those 8 k-values 8 consecutive keys.
+// V is kept transposed in memory ([feature][position]) so V^T tiles are plain row loads.
 //
 // Block: 4 wavefronts, K/V tiles of 64 positions in LDS, double-buffered; the next tile is fetched into
 // registers while the current one is multiplied.  Two work splits:
