@@ -152,7 +152,6 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 // One wavefront = one KV head x one 64-position tile.  Transposed formulation as in the prefill kernel:
 // S^T = K Q^T with the query heads of the group as MFMA columns (columns >= group are zero),
