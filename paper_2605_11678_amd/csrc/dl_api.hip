@@ -254,10 +254,6 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     kbegin(DL_K_NORM, 0, Td * dm * 6.0);
     dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
     kend();
-    lin_work(Td, L.n_qkv, dm, &fl, &by);
-    kbegin(DL_K_GEMM_QKV, fl, by);
-    linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
-    kend();
     bf16_t* kc = nullptr;
     bf16_t* vt;
     uint64_t k_hs, v_hs;
@@ -278,9 +274,20 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
         v_hs = uint64_t(dh) * ldv;
     }
     dlk::QkvPostArgs qp{qkv, L.n_qkv, T, pos0, Hq, Hkv, dh, d.rope_theta, kc, k_hs, vt, v_hs, ldv, 0, dq, dq + dkv};
-    kbegin(DL_K_QKV_POST, 0, Td * L.n_qkv * 4.0);
-    dlk::qkv_post(qp, st);
-    kend();
+    lin_work(Td, L.n_qkv, dm, &fl, &by);
+    kbegin(DL_K_GEMM_QKV, fl, by);
+    if (T == 1) {
+        // single token: rotary embedding and the append to the K / V^T caches happen in the product's epilogue
+        dlk::GemvArgs g{nbuf, P(L.w_qkv), dm, P(L.b_qkv), qkv, nullptr, L.n_qkv, dm, dlk::EPI_QKV_POST, qp};
+        dlk::gemv(g, st);
+        kend();
+    } else {
+        linear(st, T, nbuf, dm, P(L.w_qkv), dm, L.n_qkv, P(L.b_qkv), dlk::EPI_BF16, qkv, L.n_qkv, nullptr, 0);
+        kend();
+        kbegin(DL_K_QKV_POST, 0, Td * L.n_qkv * 4.0);
+        dlk::qkv_post(qp, st);
+        kend();
+    }
     dlk::AttnArgs aa{qkv, L.n_qkv, cache ? kc : qkv + dq, ldk, k_hs, vt, ldv, v_hs, attn, dq,
                      T, pos0 + T, pos0, Hq, Hkv, dh, d.causal};
     {

@@ -15,7 +15,8 @@ enum GemmEpilogue {
     EPI_RESID_F32 = 1,   // out f32  [M,N]           = resid + acc + bias         (out may alias resid)
     EPI_SWIGLU_BF16 = 2, // out bf16 [M,N/2]: B rows interleave gate/up in groups of 32; out = silu(gate) * up
     EPI_GELU_BF16 = 3,   // out bf16 [M,N]           = gelu_tanh(acc + bias)
-    EPI_F32 = 4          // out f32  [M,N]           = acc + bias
+    EPI_F32 = 4,         // out f32  [M,N]           = acc + bias
+    EPI_QKV_POST = 5     // matrix-vector only: QKV projection of ONE token followed by what qkv_post does for it
 };
 struct GemmArgs {
     const bf16_t* A; int lda;     // [M,K], row stride lda (elements); 16-byte aligned rows
@@ -27,25 +28,6 @@ struct GemmArgs {
     int epi;
 };
 void gemm(const GemmArgs& a, hipStream_t st);
-
-// ---- matrix-vector for single-token passes: out[N] = B[N,K] * x[K], same epilogues ----------
-struct GemvArgs {
-    const bf16_t* x;              // [K] bf16
-    const bf16_t* B; int ldb;     // [N,K]
-    const bf16_t* bias;
-    void* out;
-    const float* resid;
-    int N, K;
-    int epi;
-};
-void gemv(const GemvArgs& a, hipStream_t st);
-
-// ---- normalisation: fp32 rows in, bf16 (or fp32) rows out -------------------------------------
-// kind: 0 RMSNorm (g), 1 LayerNorm (g, b).  x [T, d] fp32, row stride d.
-void norm_rows(int kind, const float* x, const bf16_t* g, const bf16_t* b, void* out, bool out_f32,
-               int T, int d, float eps, hipStream_t st);
-// fp32 -> bf16 elementwise (cross-attention source)
-void cast_f32_bf16(const float* x, bf16_t* out, uint64_t n, hipStream_t st);
 
 // ---- after the QKV projection: rotary embedding and scatter -------------------------------------
 // qkv bf16 [T, n_qkv] = [q | k | v] per token.  Rotates q in place (if theta > 0); writes k (rotated)
@@ -60,6 +42,28 @@ struct QkvPostArgs {
     int q_off, k_off, v_off;      // column offsets of q, k, v inside a qkv row (q_off < 0: no q part)
 };
 void qkv_post(const QkvPostArgs& a, hipStream_t st);
+
+// ---- matrix-vector for single-token passes: out[N] = B[N,K] * x[K], same epilogues ----------
+struct GemvArgs {
+    const bf16_t* x;              // [K] bf16
+    const bf16_t* B; int ldb;     // [N,K]
+    const bf16_t* bias;
+    void* out;
+    const float* resid;
+    int N, K;
+    int epi;
+    // EPI_QKV_POST: `out` is the token's qkv row (= post.qkv, T = 1); q and k are rotated, k goes to the cache (or
+    // stays in the row), v goes to the transposed cache, exactly as qkv_post would do after an EPI_BF16 product
+    QkvPostArgs post;
+};
+void gemv(const GemvArgs& a, hipStream_t st);
+
+// ---- normalisation: fp32 rows in, bf16 (or fp32) rows out -------------------------------------
+// kind: 0 RMSNorm (g), 1 LayerNorm (g, b).  x [T, d] fp32, row stride d.
+void norm_rows(int kind, const float* x, const bf16_t* g, const bf16_t* b, void* out, bool out_f32,
+               int T, int d, float eps, hipStream_t st);
+// fp32 -> bf16 elementwise (cross-attention source)
+void cast_f32_bf16(const float* x, bf16_t* out, uint64_t n, hipStream_t st);
 
 // ---- attention (flash-style, online softmax, MFMA) ------------------------------------------------
 // The V^T rows must be readable up to S rounded up to 8 positions and hold finite numbers there (stale values are

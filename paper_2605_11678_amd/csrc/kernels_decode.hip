@@ -53,8 +53,9 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunk = p.K >> 3;
 
-    const int n_units = (EPI == EPI_SWIGLU_BF16) ? p.N / 2 : p.N;
-    constexpr int UNITS_PER_WAVE = (EPI == EPI_SWIGLU_BF16) ? ROWS / 2 : ROWS;
+    constexpr bool PAIRED = EPI == EPI_SWIGLU_BF16 || EPI == EPI_QKV_POST;     // a unit needs two weight rows
+    const int n_units = PAIRED ? p.N / 2 : p.N;
+    constexpr int UNITS_PER_WAVE = PAIRED ? ROWS / 2 : ROWS;
     const int u0 = (blockIdx.x * 4 + wave) * UNITS_PER_WAVE;
     const bf16_t* rows[ROWS];
     bool valid[UNITS_PER_WAVE];
@@ -67,6 +68,11 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
             const int pr = (uu / 32) * 64 + (uu % 32);
             rows[2 * u] = p.B + size_t(pr) * p.ldb;
             rows[2 * u + 1] = p.B + size_t(pr + 32) * p.ldb;
+        } else if (EPI == EPI_QKV_POST) {
+            // unit = rotary pair: features i and i + dh/2 of one head
+            const int half = p.post.dh >> 1, r0 = (uu / half) * p.post.dh + (uu % half);
+            rows[2 * u] = p.B + size_t(r0) * p.ldb;
+            rows[2 * u + 1] = p.B + size_t(r0 + half) * p.ldb;
         } else {
             rows[u] = p.B + size_t(uu) * p.ldb;
         }
@@ -139,6 +145,27 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
         const int n = u0 + u;
         if (EPI == EPI_SWIGLU_BF16) {
             static_cast<bf16_t*>(p.out)[n] = f_to_bf16(silu_f(acc[2 * u]) * acc[2 * u + 1]);
+        } else if (EPI == EPI_QKV_POST) {
+            const QkvPostArgs& q = p.post;
+            const int half = q.dh >> 1, hh = n / half, i = n % half, r0 = hh * q.dh + i, r1 = r0 + half;
+            // the projection is rounded to bf16 first, like the stand-alone product whose output the rotary kernel reads
+            const float a = bf16_to_f(f_to_bf16(acc[2 * u] + (p.bias ? bf16_to_f(p.bias[r0]) : 0.0f)));
+            const float b = bf16_to_f(f_to_bf16(acc[2 * u + 1] + (p.bias ? bf16_to_f(p.bias[r1]) : 0.0f)));
+            bf16_t* row = static_cast<bf16_t*>(p.out);
+            const int pos = q.pos0, dq = q.Hq * q.dh, dkv = q.Hkv * q.dh;
+            if (r0 >= dq + dkv) {                         // V: into the transposed cache, no rotation
+                const int g = (r0 - dq - dkv) / q.dh;
+                bf16_t* dst = q.vt_out + size_t(g) * q.vt_head_stride + pos;
+                dst[size_t(i) * q.vt_ld] = f_to_bf16(a);
+                dst[size_t(i + half) * q.vt_ld] = f_to_bf16(b);
+            } else {
+                float sn = 0.0f, cs = 1.0f;
+                if (q.theta > 0.0f) sincosf(float(pos) * exp2f(-2.0f * float(i) / float(q.dh) * log2f(q.theta)), &sn, &cs);
+                bf16_t* dst = row + r0;                   // Q (q_off = 0) or K kept in the row
+                if (r0 >= dq && q.k_out) dst = q.k_out + size_t((r0 - dq) / q.dh) * q.k_head_stride + size_t(pos) * q.dh + i;
+                dst[0] = f_to_bf16(a * cs - b * sn);
+                dst[half] = f_to_bf16(a * sn + b * cs);
+            }
         } else {
             const float v = acc[u] + (p.bias ? bf16_to_f(p.bias[n]) : 0.0f);
             if (EPI == EPI_BF16) static_cast<bf16_t*>(p.out)[n] = f_to_bf16(v);
@@ -296,20 +323,21 @@ __global__ __launch_bounds__(512) void decode_attn_merge(DecodeAttnArgs p, float
 template <int EPI>
 void launch_gemv(const GemvArgs& a, int n_units, hipStream_t st) {
     const size_t lds = size_t(a.K) * 2;
-    constexpr bool SW = EPI == EPI_SWIGLU_BF16;
+    constexpr bool SW = EPI == EPI_SWIGLU_BF16 || EPI == EPI_QKV_POST;     // two rows per unit
     // 4 rows per wavefront unless that gives fewer than two workgroups per compute unit
     const int blocks4 = (n_units + (SW ? 8 : 16) - 1) / (SW ? 8 : 16);
-    if (SW || blocks4 >= 512) {
+    if (EPI == EPI_SWIGLU_BF16 || blocks4 >= 512) {
         hipLaunchKernelGGL((gemv_kernel<EPI, 4>), dim3(blocks4), dim3(256), lds, st, a);
     } else {
-        hipLaunchKernelGGL((gemv_kernel<EPI, 2>), dim3((n_units + 7) / 8), dim3(256), lds, st, a);
+        hipLaunchKernelGGL((gemv_kernel<EPI, 2>), dim3((n_units + (SW ? 4 : 8) - 1) / (SW ? 4 : 8)), dim3(256), lds, st, a);
     }
 }
 
 void gemv(const GemvArgs& a, hipStream_t st) {
     if (a.N <= 0) return;
-    const int n_units = (a.epi == EPI_SWIGLU_BF16) ? a.N / 2 : a.N;
+    const int n_units = (a.epi == EPI_SWIGLU_BF16 || a.epi == EPI_QKV_POST) ? a.N / 2 : a.N;
     switch (a.epi) {
+        case EPI_QKV_POST: launch_gemv<EPI_QKV_POST>(a, n_units, st); break;
         case EPI_BF16: launch_gemv<EPI_BF16>(a, n_units, st); break;
         case EPI_RESID_F32: launch_gemv<EPI_RESID_F32>(a, n_units, st); break;
         case EPI_SWIGLU_BF16: launch_gemv<EPI_SWIGLU_BF16>(a, n_units, st); break;
