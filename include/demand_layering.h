@@ -140,7 +140,7 @@ int32_t dl_get_residency(const dl_ctx* ctx, int32_t module, int32_t* idx_out, in
  * module's pass simply re-issues its own first copy). */
 int32_t dl_set_mode(dl_ctx* ctx, int32_t mode, int32_t wrap_prefetch);
 
-/* How many streaming passes (passes that copy at least one layer) may have copies outstanding when the next one is
+/* How many streaming passes (passes that copy at least one layer) may be unfinished when the next one is
  * enqueued (1..8; 0 = no limit).  Default 1: each further pass of short streamed layers in flight slowed copies and
  * kernels on MI355X (+4 % with two, +25 % with four).  Passes of resident layers only are never held back. */
 int32_t dl_set_run_ahead(dl_ctx* ctx, int32_t passes);
@@ -148,8 +148,8 @@ int32_t dl_set_run_ahead(dl_ctx* ctx, int32_t passes);
 /* ---- the hot path (Sec. IV-C) ------------------------------------------------------------ */
 
 /* One pass over all layers of `module`; enqueues only, returns before the GPU finishes, except that a pass
- * which streams at least one layer first waits until the copies of the streaming pass dl_set_run_ahead (default
- * one) passes back have landed.
+ * which streams at least one layer first waits until the streaming pass dl_set_run_ahead (default one) passes
+ * back has finished.
  * x_dev: device fp32 [n_tokens, d_model] input;  y_dev: device fp32 [n_tokens, d_model] output
  * (may equal x_dev).  Token t sits at absolute position pos0 + t; with a KV cache the pass appends
  * its keys/values at those positions and attends over 0 .. pos0+t.  pos0 must be 0 without a cache.

@@ -62,9 +62,9 @@ struct dl_ctx {
     hipEvent_t ev_dma[2] = {nullptr, nullptr}, ev_comp[2] = {nullptr, nullptr}, ev_pass = nullptr;
     bool events_made = false;
     static constexpr int kMaxRunAhead = 8;
-    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // copy-stream end of the most recent streaming passes (host throttle)
+    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // end of the most recent streaming passes on the compute stream (host throttle)
     uint64_t n_passes = 0;                       // streaming passes enqueued so far
-    int32_t run_ahead = 1;                        // streaming passes whose copies may be outstanding; 0 = unlimited
+    int32_t run_ahead = 1;                        // streaming passes that may be unfinished; 0 = unlimited
     int32_t mode = DL_MODE_PIPELINED, wrap = 0;
     bool tracing = false;
     std::vector<dl_trace_op> trace;
@@ -360,11 +360,12 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
     dl::build_pass(mi, M.d.n_layers, M.resident.data(), c->mode, c->wrap, force_all, &c->book, &ops);
     if (c->tracing || !on_gpu(c)) c->trace.insert(c->trace.end(), ops.begin(), ops.end());
     if (!on_gpu(c)) return DL_OK;
-    // Bounded run-ahead for passes that stream: by default the host enqueues such a pass only once the copies of
-    // the previous streaming pass have all landed (its last layers may still be executing, which covers the
-    // host's wake-up and enqueue latency).  Every further pass of short streamed layers kept in flight made copies
-    // and kernels slower on MI355X (27-layer encoder, fully streamed: 15.4 ms per pass with one pass in flight,
-    // 16.0 with two, 17.7 with three, 19 with four).  Passes without copies are never held back.
+    // Bounded run-ahead for passes that stream: by default the host enqueues such a pass only once the previous
+    // streaming pass has finished (inside the pass it still runs far ahead of the GPU: enqueuing takes a tenth of
+    // the pass time or less).  Every further pass of short streamed layers kept in flight made copies and kernels
+    // slower on MI355X (27-layer encoder, fully streamed: 15.4 ms per pass with one pass in flight, 16.0 with two,
+    // 17.7 with three, 19 with four; waiting only for the previous pass's copies instead of its end cost 5 % on
+    // the five-stage pipeline).  Passes without copies are never held back.
     bool has_copy = false;
     for (const dl_trace_op& o : ops) has_copy = has_copy || o.op == DL_OP_COPY;
     if (has_copy && c->run_ahead > 0 && c->n_passes >= uint64_t(c->run_ahead))
@@ -419,7 +420,7 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
         }
     }
     if (has_copy) {
-        DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_copy));
+        DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_compute));
         ++c->n_passes;
     }
     return DL_OK;
@@ -1030,14 +1031,14 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     // all layers back to back, no copies: execution time under continuous load.  The last of kHotReps runs counts:
     // the chip is power-limited, and the first passes after an idle spell still run at a higher clock than a
     // sustained sequence of passes does.
-    // Resident layers read weights that have long left the caches (a whole stack is far larger than the 256 MB
-    // memory-side cache), so the run must not keep re-reading one slot: the layers rotate through the two slots plus
-    // as many temporary copies as it takes to exceed that cache (or as the arena can spare).
+    // Resident layers read weights that have long left the caches and whose pages have left the TLBs (a whole stack is
+    // far larger than the 256 MB memory-side cache), so the run must not keep re-reading one slot: the layers rotate
+    // through the two slots plus temporary copies, one buffer per layer if the arena can spare that much (re-reading
+    // three 386 MB buffers made single-token passes look 7 % faster than passes over 36 resident layers are).
     std::vector<uint64_t> rot = {c->slot_off[0], c->slot_off[1]};
     std::vector<uint64_t> rot_tmp;
     {
-        const uint64_t want = (320ull << 20) / M->L.bytes + 1;
-        for (uint64_t j = 0; j < want && j < 16 && int64_t(j) + 2 < Ln; ++j) {
+        for (uint64_t j = 0; int64_t(j) + 2 < Ln; ++j) {
             uint64_t off = 0;
             if (!c->arena.alloc(M->L.bytes, &off)) break;
             if (hipMemcpyAsync(c->base + off, M->store + size_t(j % uint64_t(Ln)) * M->L.bytes, M->L.bytes,
