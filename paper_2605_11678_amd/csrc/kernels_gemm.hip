@@ -183,28 +183,45 @@ __device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM]
         return;
     }
     if (EPI == EPI_RESID_F32) {
-        // out may be the same buffer as resid: every element is read and then written by the same lane only,
-        // so the pointers are declared non-aliasing to let all loads of a tile be issued ahead of its stores
+        // out may be the same buffer as resid: every element is read and then written by the same lane only, so the
+        // pointers are declared non-aliasing.  The residual values of a batch of accumulator tiles are all requested
+        // before the first one is used - unpredicated, rows and columns clamped into the matrix - so that the
+        // wavefront pays one memory round trip per batch instead of one per tile; only the stores are predicated.
         const float* __restrict__ resid = p.resid;
         float* __restrict__ out = static_cast<float*>(p.out);
+        // column tiles per batch: what fits next to the accumulators without spilling (TM = 3: all of them)
+        constexpr int JFIT = (352 - TM * TN * 16) / (TM * 16);
+        constexpr int JB = TM == 3 ? TN : (JFIT < 1 ? 1 : (JFIT > TN ? TN : JFIT));
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = nw + 32 * j + col_in;
-            if (n >= p.N) continue;
-            const float bias = p.bias ? bf16_to_f(p.bias[n]) : 0.0f;
+        for (int j0 = 0; j0 < TN; j0 += JB) {
+            float rv[JB][TM][16];
+            float bias[JB];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                float rv[16];
+            for (int jj = 0; jj < JB; ++jj) {
+                const int j = j0 + jj;
+                if (j >= TN) continue;
+                const int nc = min(nw + 32 * j + col_in, p.N - 1);
+                bias[jj] = p.bias ? bf16_to_f(p.bias[nc]) : 0.0f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
-                    rv[r] = m < p.M ? resid[size_t(m) * p.ldr + n] : 0.0f;
-                }
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
-                    if (m < p.M) out[size_t(m) * p.ldo + n] = rv[r] + acc[i][j][r] + bias;
-                }
+                    for (int r = 0; r < 16; ++r) {
+                        const int mc = min(mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3), p.M - 1);
+                        rv[jj][i][r] = resid[uint32_t(mc) * uint32_t(p.ldr) + uint32_t(nc)];   // < 2^31 elements (host checks)
+                    }
+            }
+#pragma unroll
+            for (int jj = 0; jj < JB; ++jj) {
+                const int j = j0 + jj;
+                if (j >= TN) continue;
+                const int n = nw + 32 * j + col_in;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
+                        if (m < p.M && n < p.N) out[uint32_t(m) * uint32_t(p.ldo) + uint32_t(n)] = rv[jj][i][r] + acc[i][j][r] + bias[jj];
+                    }
             }
         }
         return;
@@ -477,6 +494,20 @@ void dispatch_fast(const GemmArgs& a, hipStream_t st) {
 
 void gemm(const GemmArgs& a, hipStream_t st) {
     if (a.M <= 0 || a.N <= 0) return;
+    // the residual epilogue addresses out and resid with 32-bit element offsets: split the rows of larger outputs
+    if (a.epi == EPI_RESID_F32 && a.M > 1 &&
+        (size_t(a.M) * size_t(a.ldo) >= (1ull << 31) || size_t(a.M) * size_t(a.ldr) >= (1ull << 31))) {
+        const int m1 = a.M / 2;
+        GemmArgs lo = a, hi = a;
+        lo.M = m1;
+        hi.M = a.M - m1;
+        hi.A = a.A + size_t(m1) * a.lda;
+        hi.out = static_cast<float*>(a.out) + size_t(m1) * a.ldo;
+        hi.resid = a.resid + size_t(m1) * a.ldr;
+        gemm(lo, st);
+        gemm(hi, st);
+        return;
+    }
     // fast path: K in whole pairs of 64-wide steps, 16-byte aligned rows, enough rows to fill a tile
     const bool fast = a.K >= 128 && a.K % 128 == 0 && a.lda % 8 == 0 && a.ldb % 8 == 0 && a.M >= 96 && a.N >= 128 &&
                       a.epi != EPI_F32 &&
