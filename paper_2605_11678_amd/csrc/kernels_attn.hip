@@ -61,25 +61,16 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     const int tq = wq0 + lq;                           // this lane's query (token index)
     const int qpos = p.q_pos0 + tq;
 
-    // Q fragments (B operand): 8 consecutive features per lane and k-step
-    bf16x8 qf[DHP / 16];
+    // Q fragments (B operand): 8 consecutive features per lane and k-step.  All of them are requested here, with
+    // clamped addresses and no predicate, and turned into fragments only after the first K/V tile has been requested
+    // as well: the wavefront pays one memory round trip for Q and the first tile together, not one per fragment.
+    u32x4 qv[DHP / 16];
     {
         const bf16_t* qrow = p.q + size_t(min(tq, p.T - 1)) * p.ldq + size_t(h) * p.dh;
 #pragma unroll
         for (int kk = 0; kk < DHP / 16; ++kk) {
             const int e = 16 * kk + 8 * g2;
-            u32x4 v = {0u, 0u, 0u, 0u};
-            if (tq < p.T && e < p.dh) v = *reinterpret_cast<const u32x4*>(qrow + e);
-            // pass the loaded words through a register move: inside the tile loop the fragments are then results of
-            // vector instructions, and the compiler does not put a wait for ALL outstanding loads (the prefetch of
-            // the next K/V tile included) in front of the first MFMA that reads them
-#pragma unroll
-            for (int w = 0; w < 4; ++w) {
-                uint32_t y;
-                asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(v[w]));
-                v[w] = y;
-            }
-            qf[kk] = *reinterpret_cast<bf16x8*>(&v);
+            qv[kk] = *reinterpret_cast<const u32x4*>(qrow + (e < p.dh ? e : 0));
         }
     }
 
@@ -130,10 +121,25 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         }
     };
 
-    if (nt > 0) {
-        fetch(0);
-        stash(0);
+    fetch(0);                                          // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
+    bf16x8 qf[DHP / 16];
+#pragma unroll
+    for (int kk = 0; kk < DHP / 16; ++kk) {
+        const int e = 16 * kk + 8 * g2;
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        u32x4 v = (tq < p.T && e < p.dh) ? qv[kk] : z;      // queries past T and padding features are zero
+        // pass the words through a register move: inside the tile loop the fragments are then results of vector
+        // instructions, and the compiler does not put a wait for ALL outstanding loads (the prefetch of the next
+        // K/V tile included) in front of the first MFMA that reads them
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            uint32_t y;
+            asm volatile("v_mov_b32 %0, %1" : "=v"(y) : "v"(v[w]));
+            v[w] = y;
+        }
+        qf[kk] = *reinterpret_cast<bf16x8*>(&v);
     }
+    stash(0);
     __syncthreads();
     for (int t = 0; t < nt; ++t) {
         const int j0 = t * BKV, s = t & 1;
