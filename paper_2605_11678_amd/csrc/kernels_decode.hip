@@ -11,11 +11,11 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 namespace {
 
 // same forms as in the GEMM epilogues, so that a single-token pass rounds like a multi-token one
-__device__ __forceinline__ float silu_f(float x) { return x * __frcp_rn(1.0f + __expf(-x)); }
+__device__ __forceinline__ float silu_f(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 __device__ __forceinline__ float gelu_tanh_f(float x) {
     const float c2 = 2.0f * 0.7978845608028654f;
     const float u2 = c2 * (x + 0.044715f * x * x * x);
-    return x * __frcp_rn(1.0f + __expf(-u2));
+    return x * __builtin_amdgcn_rcpf(1.0f + __expf(-u2));
 }
 __device__ __forceinline__ float bf16_to_f(bf16_t v) { return __uint_as_float(uint32_t(v) << 16); }
 __device__ __forceinline__ bf16_t f_to_bf16(float f) {
