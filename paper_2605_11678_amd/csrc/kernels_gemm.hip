@@ -276,6 +276,38 @@ __device__ __forceinline__ void store_tiles_full(const GemmArgs& p, f32x16 (&acc
     float bias[TN];
 #pragma unroll
     for (int j = 0; j < TN; ++j) bias[j] = p.bias ? bf16_to_f(p.bias[nw + 32 * j + col_in]) : 0.0f;
+    if (EPI == EPI_RESID_F32) {
+        // one base pointer each for resid and out, per-lane 32-bit element offsets that advance row by row with
+        // additions (no scalar pointer per row: 48-64 of them next to the accumulators made the loads slower)
+        const float* __restrict__ resid = p.resid + size_t(mw) * p.ldr + nw;
+        float* __restrict__ out = static_cast<float*>(p.out) + size_t(mw) * p.ldo + nw;
+        const uint32_t lane_r = row_in * uint32_t(p.ldr) + col_in;
+        constexpr int JFIT = (352 - TM * TN * 16) / (TM * 16);
+        constexpr int JB = TM == 3 ? TN : (JFIT < 1 ? 1 : (JFIT > TN ? TN : JFIT));
+#pragma unroll
+        for (int j0 = 0; j0 < TN; j0 += JB) {
+            float rv[JB][TM][16];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t ro = lane_r + uint32_t(32 * i + 8 * (r >> 2) + (r & 3)) * uint32_t(p.ldr);
+#pragma unroll
+                    for (int jj = 0; jj < JB; ++jj)
+                        if (j0 + jj < TN) rv[jj][i][r] = resid[ro + 32 * (j0 + jj)];
+                }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const uint32_t oo = lane_o + uint32_t(32 * i + 8 * (r >> 2) + (r & 3)) * uint32_t(p.ldo);
+#pragma unroll
+                    for (int jj = 0; jj < JB; ++jj)
+                        if (j0 + jj < TN) out[oo + 32 * (j0 + jj)] = rv[jj][i][r] + acc[i][j0 + jj][r] + bias[j0 + jj];
+                }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -447,9 +479,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
 
     // wavefront tile wholly inside the matrix (SwiGLU: inside the packed gate/up columns): unpredicated epilogue
     const int mw = m0 + (BM / 2) * wm, nw = n0 + (BN / 2) * wn;
-    // (not for the residual epilogue: with a scalar pointer per row in front of every load its batched loads came out
-    // slower than the clamped per-lane addresses of store_tiles: O projection 4.9 instead of 3.8 ms per pass)
-    constexpr bool kFull = EPI != EPI_RESID_F32;
+    constexpr bool kFull = true;
     if (kFull && mw + BM / 2 <= p.M && nw + BN / 2 <= p.N) store_tiles_full<EPI, TM, TN>(p, acc, mw, nw, lane);
     else store_tiles<EPI, TM, TN>(p, acc, mw, nw, lane);
 }
