@@ -177,24 +177,43 @@ __global__ __launch_bounds__(256) void rope_kernel(QkvPostArgs p) {
 }
 
 // V -> V^T: a 64-token x 64-feature tile goes through LDS so that both the reads (token rows) and the
-// writes (feature rows of the transposed cache, 64 consecutive positions = 128 bytes) are contiguous.
+// writes (feature rows of the transposed cache, 64 consecutive positions = 128 bytes) are contiguous.  Both sides move
+// 16 bytes per thread and instruction: two unpredicated loads per thread (token and column clamped into the matrix, so
+// nothing waits between them), and one store of 8 consecutive positions gathered from LDS; positions past T and a
+// destination that is not 16-byte aligned (pos0 not a multiple of 8) fall back to 2-byte stores.
 __global__ __launch_bounds__(256) void v_transpose_kernel(QkvPostArgs p) {
-    __shared__ bf16_t tile[64][66];
+    __shared__ __attribute__((aligned(16))) bf16_t tile[64][72];     // 144-byte rows: 16-byte aligned, staggered banks
     const int t0 = blockIdx.x * 64, c0 = blockIdx.y * 64;          // first token / first column of V (= g*dh + e)
-    const int ncol = p.Hkv * p.dh;
-    for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-        const int r = idx >> 6, c = idx & 63;
-        bf16_t v = 0;
-        if (t0 + r < p.T && c0 + c < ncol) v = p.qkv[size_t(t0 + r) * p.n_qkv + p.v_off + c0 + c];
-        tile[r][c] = v;
+    const int ncol = p.Hkv * p.dh;                                  // a multiple of 8
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    u32x4 v[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int idx = threadIdx.x + 256 * k, r = idx >> 3, cc = (idx & 7) * 8;
+        const int tr = min(t0 + r, p.T - 1), col = c0 + cc < ncol ? c0 + cc : 0;
+        v[k] = *reinterpret_cast<const u32x4*>(p.qkv + size_t(tr) * p.n_qkv + p.v_off + col);
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int idx = threadIdx.x + 256 * k, r = idx >> 3, cc = (idx & 7) * 8;
+        *reinterpret_cast<u32x4*>(&tile[r][cc]) = v[k];
     }
     __syncthreads();
-    for (int idx = threadIdx.x; idx < 64 * 64; idx += 256) {
-        const int c = idx >> 6, r = idx & 63;                       // consecutive threads -> consecutive positions
+    const bool aligned = (p.pos0 & 7) == 0 && (p.vt_ld & 7) == 0 && (p.vt_head_stride & 7) == 0;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int idx = threadIdx.x + 256 * k, c = idx >> 3, rc = (idx & 7) * 8;   // feature, first of 8 positions
         const int col = c0 + c;
-        if (t0 + r < p.T && col < ncol) {
-            const int g = col / p.dh, e = col % p.dh;
-            p.vt_out[size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + p.pos0 + t0 + r] = tile[r][c];
+        if (col >= ncol || t0 + rc >= p.T) continue;
+        const int g = col / p.dh, e = col % p.dh;
+        bf16_t* dst = p.vt_out + size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + p.pos0 + t0 + rc;
+        if (aligned && t0 + rc + 8 <= p.T) {
+            u32x4 o;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) o[w] = uint32_t(tile[rc + 2 * w][c]) | (uint32_t(tile[rc + 2 * w + 1][c]) << 16);
+            *reinterpret_cast<u32x4*>(dst) = o;
+        } else {
+            for (int j = 0; j < 8 && t0 + rc + j < p.T; ++j) dst[j] = tile[rc + j][c];
         }
     }
 }
