@@ -147,6 +147,49 @@ __global__ __launch_bounds__(256) void rope_kernel(QkvPostArgs p) {
             p.vt_out[size_t(g) * p.vt_head_stride + size_t(e) * p.vt_ld + pos] = row[p.v_off + col];
         }
     }
+    if (!FUSE_V && (half & 7) == 0 && half <= 128) {
+        // multi-token passes: the token's sin/cos table goes to LDS once (one evaluation per frequency), then every
+        // thread rotates 8 pairs per step with 16-byte loads and stores: (i..i+7) and (i+half..i+half+7) of one head
+        typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+        __shared__ float s_cs[128], s_sn[128];
+        if (int(threadIdx.x) < half) {
+            float sn = 0.0f, cs = 1.0f;
+            if (p.theta > 0.0f)
+                sincosf(float(pos) * exp2f(-2.0f * float(threadIdx.x) / float(p.dh) * log2f(p.theta)), &sn, &cs);
+            s_cs[threadIdx.x] = cs;
+            s_sn[threadIdx.x] = sn;
+        }
+        __syncthreads();
+        const int per_head = half >> 3;
+        const int nq = (p.theta > 0.0f && p.q_off >= 0) ? p.Hq : 0;
+        const int nk = (p.k_out || p.theta > 0.0f) ? p.Hkv : 0;
+        for (int task = threadIdx.x; task < (nq + nk) * per_head; task += 256) {
+            const int hh = task / per_head, c = (task - hh * per_head) * 8;
+            const bf16_t* src;
+            bf16_t* dst;
+            if (hh < nq) {
+                dst = row + p.q_off + hh * p.dh;
+                src = dst;
+            } else {
+                const int g = hh - nq;
+                src = row + p.k_off + g * p.dh;
+                dst = p.k_out ? p.k_out + size_t(g) * p.k_head_stride + size_t(pos) * p.dh : row + p.k_off + g * p.dh;
+            }
+            const u32x4 lo = *reinterpret_cast<const u32x4*>(src + c), hi = *reinterpret_cast<const u32x4*>(src + c + half);
+            u32x4 olo, ohi;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float a0 = __uint_as_float(lo[w] << 16), a1 = __uint_as_float(lo[w] & 0xFFFF0000u);
+                const float b0 = __uint_as_float(hi[w] << 16), b1 = __uint_as_float(hi[w] & 0xFFFF0000u);
+                const float c0 = s_cs[c + 2 * w], c1 = s_cs[c + 2 * w + 1], n0 = s_sn[c + 2 * w], n1 = s_sn[c + 2 * w + 1];
+                olo[w] = uint32_t(f_to_bf16(a0 * c0 - b0 * n0)) | (uint32_t(f_to_bf16(a1 * c1 - b1 * n1)) << 16);
+                ohi[w] = uint32_t(f_to_bf16(a0 * n0 + b0 * c0)) | (uint32_t(f_to_bf16(a1 * n1 + b1 * c1)) << 16);
+            }
+            *reinterpret_cast<u32x4*>(dst + c) = olo;
+            *reinterpret_cast<u32x4*>(dst + c + half) = ohi;
+        }
+        return;
+    }
     float sn = 0.0f, cs = 1.0f;
     if (p.theta > 0.0f) {
         const float ang = float(pos) * exp2f(-2.0f * float(i) / float(p.dh) * log2f(p.theta));
