@@ -38,12 +38,20 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
     const float4* row = reinterpret_cast<const float4*>(x + size_t(blockIdx.x) * d);
     const int tid = threadIdx.x, nv = d >> 2;
     constexpr int KEEP = 4;                       // float4 per thread held in registers
+    // the row pieces and their gains (and biases) are all requested before anything is used, with the index clamped
+    // instead of a predicate: one memory round trip for the whole workgroup's share of the row
     float4 v[KEEP];
+    uint2 gk[KEEP], bk[KEEP];
 #pragma unroll
     for (int j = 0; j < KEEP; ++j) {
-        const int i = tid + 256 * j;
-        v[j] = i < nv ? row[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int i = tid + 256 * j, ic = i < nv ? i : 0;
+        v[j] = row[ic];
+        gk[j] = reinterpret_cast<const uint2*>(g)[ic];
+        if (KIND == 1) bk[j] = reinterpret_cast<const uint2*>(b)[ic];
     }
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j)
+        if (tid + 256 * j >= nv) v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
     float mean = 0.0f;
     if (KIND == 1) {
         float s = 0.0f;
@@ -69,14 +77,12 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
         ss += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
     }
     const float inv = rsqrtf(block_sum_256(ss, red) / float(d) + eps);
-    auto emit = [&](int i, const float4& t) {
-        const uint2 gg = reinterpret_cast<const uint2*>(g)[i];
+    auto emit = [&](int i, const float4& t, const uint2& gg, const uint2& bb) {
         float o0 = (t.x - mean) * inv * __uint_as_float(gg.x << 16);
         float o1 = (t.y - mean) * inv * __uint_as_float(gg.x & 0xFFFF0000u);
         float o2 = (t.z - mean) * inv * __uint_as_float(gg.y << 16);
         float o3 = (t.w - mean) * inv * __uint_as_float(gg.y & 0xFFFF0000u);
         if (KIND == 1) {
-            const uint2 bb = reinterpret_cast<const uint2*>(b)[i];
             o0 += __uint_as_float(bb.x << 16);
             o1 += __uint_as_float(bb.x & 0xFFFF0000u);
             o2 += __uint_as_float(bb.y << 16);
@@ -93,8 +99,12 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
     };
 #pragma unroll
     for (int j = 0; j < KEEP; ++j)
-        if (tid + 256 * j < nv) emit(tid + 256 * j, v[j]);
-    for (int i = tid + 256 * KEEP; i < nv; i += 256) emit(i, row[i]);
+        if (tid + 256 * j < nv) emit(tid + 256 * j, v[j], gk[j], bk[j]);
+    for (int i = tid + 256 * KEEP; i < nv; i += 256) {
+        uint2 bb = make_uint2(0u, 0u);
+        if (KIND == 1) bb = reinterpret_cast<const uint2*>(b)[i];
+        emit(i, row[i], reinterpret_cast<const uint2*>(g)[i], bb);
+    }
 }
 
 __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, uint64_t n) {
