@@ -220,6 +220,9 @@ __global__ __launch_bounds__(64) void decode_attn_partial(DecodeAttnArgs p, floa
 #pragma unroll
         for (int q = 0; q < 4; ++q) vf[dt][q] = *reinterpret_cast<const u32x4*>(vr + 16 * q);   // q = 2*i + t2
     }
+    // keep every load above this line: left alone, the scheduler sinks the V^T loads below the score MFMAs and the
+    // wavefront pays a second memory latency for them
+    __builtin_amdgcn_sched_barrier(0);
     bf16x8 qf[DHP / 16];
 #pragma unroll
     for (int kk = 0; kk < DHP / 16; ++kk) {
