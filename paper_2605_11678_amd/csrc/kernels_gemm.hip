@@ -352,6 +352,24 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int* 
 #define DL_WAIT_VM(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 #define DL_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0x0 << 8))
 
+// scheduling request for one phase of a K step: groups of PM MFMAs followed by PD LDS reads (and one global->LDS copy
+// while copies remain) until the NR reads are out, then the remaining copies and MFMAs
+template <int PM, int PD, int NR, int NM, int NC, int G>
+struct SchedBursts {
+    static __device__ __forceinline__ void run() {
+        constexpr int d = (G + 1) * PD <= NR ? PD : (NR - G * PD > 0 ? NR - G * PD : 0);
+        if constexpr (d > 0) {
+            __builtin_amdgcn_sched_group_barrier(0x008, PM, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, d, 0);
+            if constexpr (G < NC) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            SchedBursts<PM, PD, NR, NM, NC, G + 1>::run();
+        } else {
+            if constexpr (NC > G) __builtin_amdgcn_sched_group_barrier(0x020, NC - G, 0);
+            if constexpr (NM > G * PM) __builtin_amdgcn_sched_group_barrier(0x008, NM - G * PM, 0);
+        }
+    }
+};
+
 // One output tile with its top-left corner at (m0, n0).  S0..S3 are the four LDS stages; they must be four distinct
 // __shared__ arrays of at least (BM + BN) * 32 elements each.
 template <int BM, int BN, int EPI>
@@ -420,13 +438,21 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     };
-    // ask the scheduler for: 2 MFMA, 1 LDS read, and for the first ncopy groups 1 global->LDS copy
-    auto interleave = [&](int ncopy) {
+    // ask the scheduler for: 2 MFMA, 1 LDS read, and for the first ncopy groups 1 global->LDS copy.  The 4x4-tile
+    // wavefront (16 MFMAs, 8 fragment reads per phase) does better with its reads in two bursts of four after six
+    // MFMAs each, which leaves the last four MFMAs of a phase to cover the latency of the last read (+4 % on the
+    // gate/up shape; the 3x4 and 3x3 wavefront tiles showed no difference between the patterns tried).
+    auto interleave = [&](auto ncopy_c) {
+        constexpr int ncopy = decltype(ncopy_c)::value;
+        if constexpr (TM * TN == 16) {
+            SchedBursts<6, 4, TM + TN, TM * TN, ncopy, 0>::run();
+        } else {
 #pragma unroll
-        for (int g = 0; g < TM * TN / 2; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            if (g < ncopy) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            for (int g = 0; g < TM * TN / 2; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                if (g < ncopy) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
     };
@@ -451,7 +477,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
         ldfrag(a1, b1, cur, 1);
         if (AHEAD == 3) copyA(fill, kt + 3);
         mma(a0, b0);
-        interleave(AHEAD == 3 ? JA : 0);
+        interleave(std::integral_constant<int, (AHEAD == 3 ? JA : 0)>{});
         if (AHEAD >= 1) {
             // k-tile kt+1 must have landed; younger copies may stay in flight: A and B of kt+2, A of kt+3
             if (AHEAD == 3) DL_WAIT_VM_LGKM0(JA + NL);
@@ -463,7 +489,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
         }
         if (AHEAD == 3) copyB(fill, kt + 3);
         mma(a1, b1);
-        interleave(AHEAD == 3 ? JB : 0);
+        interleave(std::integral_constant<int, (AHEAD == 3 ? JB : 0)>{});
     };
     int kt = 0;
     for (; kt + 4 < nk; kt += 4) {
