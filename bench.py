@@ -235,8 +235,12 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     st = ctx.arena_stats()
     budget = st["capacity"] - st["used"] - (128 << 20)      # head-room for 256-byte rounding and first-fit holes
     k_plan = B.plan(Ls, sizes, [list(b) for b in b3], budget)
-    log("vla benefit (ms/MiB) first/mid/last: vit %s, decoder %s, action %s; budget %.2f GB -> k = %s" %
-        (np.round(b3[0], 4).tolist(), np.round(b3[1], 4).tolist(), np.round(b3[2], 4).tolist(), budget / 1e9, k_plan))
+    # the same ranking when the budget also covers the slots and these are sized by the modules that still stream:
+    # a fully resident decoder shrinks the pair from 2 x 386 MB to the small stacks' layers
+    k_shared = B.plan_shared_slots(Ls, sizes, [list(b) for b in b3], budget + 2 * max(sizes))
+    log("vla benefit (ms/MiB) first/mid/last: vit %s, decoder %s, action %s; budget %.2f GB -> k = %s (slots fixed at 2 x M_max), "
+        "%s (slots sized by the streaming modules)" %
+        (np.round(b3[0], 4).tolist(), np.round(b3[1], 4).tolist(), np.round(b3[2], 4).tolist(), budget / 1e9, k_plan, k_shared))
 
     # benefit per MiB as a function of the decode length N and of the number of Euler steps (Sec. IV-D: the
     # ranking of the modules, and with it the plan, depends on how often each module's layers are invoked)
@@ -249,7 +253,8 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     for n_dec, n_eul in [(0, 10), (1, 10), (4, 10), (15, 10), (21, 10), (64, 10), (256, 10), (1024, 10), (64, 1), (64, 4), (64, 20), (64, 50)]:
         bb = b3_for(n_dec, n_eul)
         crossover.append({"n_decode": n_dec, "n_euler": n_eul, "b_mid_ms_per_MiB_vit_dec_act": [round(float(b[1]), 5) for b in bb],
-                          "k_vit_dec_act": B.plan(Ls, sizes, [list(b) for b in bb], budget)})
+                          "k_vit_dec_act": B.plan_shared_slots(Ls, sizes, [list(b) for b in bb], budget + 2 * max(sizes)),
+                          "k_with_slots_2x_largest_layer": B.plan(Ls, sizes, [list(b) for b in bb], budget)})
 
     # greedy head per token (resident, outside the layer passes)
     ctx.sync()
@@ -258,6 +263,14 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
         ctx.greedy_step(pipe.m_dec, pipe.p_y1, pipe.p_tok, pipe.p_x1)
     ctx.sync()
     head_ms = (time.perf_counter() - t) * 1e3 / 30
+
+    # the launches that belong to no layer (projector, pooling, final norm, Euler updates, output projection)
+    ctx.sync()
+    t = time.perf_counter()
+    for _ in range(10):
+        pipe.enqueue_glue()
+    ctx.sync()
+    glue_ms = (time.perf_counter() - t) * 1e3 / 10
 
     def predict(ks, wrap):
         dma, hot, idle, fence, streamed, starts, mids = [], [], [], [], [], [], []
@@ -274,7 +287,7 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
             add_pass(2, P["action"], rs[2])
         return B.timeline(dma, hot, streamed, starts, module_id=mids, wrap_prefetch=wrap, c_exe_idle_ms=idle,
                           c_fence_ms=fence)["total"] \
-            + head_ms * n_decode
+            + head_ms * n_decode + glue_ms
 
     def measure(ks, wrap, reps):
         for m in range(3):
@@ -297,7 +310,8 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     # second policy of the comparison: small modules fully resident first, the decoder gets what is left
     left = budget - Ls[0] * sizes[0] - Ls[2] * sizes[2]
     k_alt = [Ls[0], max(0, min(Ls[1], int(left // sizes[1]))), Ls[2]]
-    for name, ks, reps in (("planner", k_plan, 3), ("vit_and_action_resident_first", k_alt, 3), ("all_streamed", [0, 0, 0], 1)):
+    for name, ks, reps in (("planner_slots_sized_by_streaming_modules", k_shared, 3), ("planner_slots_2x_largest_layer", k_plan, 3),
+                           ("vit_and_action_resident_first", k_alt, 3), ("all_streamed", [0, 0, 0], 1)):
         try:
             ms, out = measure(ks, 1, reps)
         except B.DLError as e:
@@ -317,7 +331,7 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     res = {"workload": "configs[4]: ViT 27L T=4096 -> merger -> 8B decoder prefill 3072 + %d decode steps -> action head 8L x 10 Euler "
                        "steps on 64 tokens; cap %.3g B" % (n_decode, cap),
            "layer_bytes": sizes, "profile": prof, "benefit_ms_per_MiB": [np.round(b, 5).tolist() for b in b3],
-           "budget_gb": round(budget / 1e9, 3), "head_ms": round(head_ms, 4), "runs": rows,
+           "budget_gb": round(budget / 1e9, 3), "head_ms": round(head_ms, 4), "glue_ms": round(glue_ms, 4), "runs": rows,
            "benefit_vs_decode_length_and_euler_steps": crossover,
            "trajectory_finite": bool(np.all(np.isfinite(ref["trajectory"]))) if ref else None}
     eng.close()

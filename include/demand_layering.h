@@ -119,9 +119,9 @@ int32_t dl_layer_set_tensor(dl_ctx* ctx, int32_t module, int32_t layer, int32_t 
                             const void* host_bf16, uint64_t n_elems);
 /* host_bf16 -> arena (device-resident for the module's lifetime). Needs the arena. */
 int32_t dl_set_resident_tensor(dl_ctx* ctx, int32_t module, int32_t which, const void* host_bf16, uint64_t n_elems);
-/* All tensors of all layers must have been set.  Sizes the two shared slots to the largest
- * layer over all finalized modules (Sec. IV-C(i): 2 x M_max) and carves the module's KV
- * cache and activation workspace out of the arena. */
+/* All tensors of all layers must have been set.  Sizes the two shared slots (Sec. IV-C(i): 2 x M_max, M_max
+ * taken over the finalized modules that stream at least one layer: a fully resident module never uses a slot)
+ * and carves the module's KV cache and activation workspace out of the arena. */
 int32_t dl_module_finalize(dl_ctx* ctx, int32_t module);
 /* packed_bytes: bytes of one layer's blob (what one copy moves); param_bytes: 2 * parameter count. */
 int32_t dl_module_layer_bytes(const dl_ctx* ctx, int32_t module, uint64_t* packed_bytes, uint64_t* param_bytes);
@@ -129,8 +129,9 @@ int32_t dl_module_layer_bytes(const dl_ctx* ctx, int32_t module, uint64_t* packe
 /* ---- residency (Sec. IV-D) ------------------------------------------------------------- */
 
 /* layer_idx: host array of n distinct layer indices that stay device-resident; the rest stream.
- * Uploads newly resident layers, releases dropped ones.  n == n_layers for every module
- * releases the two slots.  Synchronises both streams.  DL_ERR_BUDGET_EXCEEDED: nothing changed. */
+ * Uploads newly resident layers, releases dropped ones.  The slot pair is re-sized to the largest layer of the
+ * modules that still stream something (making the module with the largest layers fully resident shrinks it);
+ * n == n_layers for every module releases it.  Synchronises both streams.  DL_ERR_BUDGET_EXCEEDED: nothing changed. */
 int32_t dl_set_residency(dl_ctx* ctx, int32_t module, const int32_t* layer_idx, int32_t n);
 /* idx_out: host array of capacity n_layers; *n_out = count */
 int32_t dl_get_residency(const dl_ctx* ctx, int32_t module, int32_t* idx_out, int32_t* n_out);
@@ -316,6 +317,18 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
  * k_out[m] = resident count for module m (indices then come from dl_place_interleaved). */
 int32_t dl_plan(int32_t n_modules, const int32_t* n_layers, const uint64_t* layer_bytes,
                 const double* b3, uint64_t budget_bytes, int32_t* k_out);
+
+/* The same choice when the budget also has to hold the slots (Sec. IV-C(i)) and these are sized by the modules that
+ * still stream: budget_bytes is what is left for resident layers AND slots.  A residency (k_m) costs
+ * sum_m k_m * layer_bytes[m] + n_slots * max{ layer_bytes[m] : k_m < n_layers[m] } bytes, which is not monotone: the
+ * last layer of the module with the largest layers gives slot memory back.  Every set F of fully resident modules is
+ * tried: F's layers and the slots of the rest are paid first, the remaining bytes go to the other modules by dl_plan's
+ * ranking with their last layer excluded; the candidate with the largest total benefit
+ * (sum over resident layers of B * layer MiB, Tables IV-VI) wins, ties to the fewer resident bytes, then to the
+ * smaller set F (as a bit mask).  n_modules <= 12.  DL_ERR_BUDGET_EXCEEDED if not even the slots of the all-streamed
+ * case fit. */
+int32_t dl_plan_shared_slots(int32_t n_modules, const int32_t* n_layers, const uint64_t* layer_bytes,
+                             const double* b3, uint64_t budget_bytes, int32_t n_slots, int32_t* k_out);
 
 #ifdef __cplusplus
 }

@@ -12,6 +12,8 @@ from it.  Plain Python floats (float64), the paper's notation:
 Functions follow, in the paper's order: Eq. 1, Eq. 2, Eq. 3 (Sec. II-C, III-A);
 Eq. 4 and the per-position Tables IV, V, VI with the module times Eq. 5, 6, 7
 (Sec. IV-D); the consecutive residency limit; the interleaved placement Eq. 8;
+the value and the device bytes of a residency over several modules that share
+the slots, with an exhaustive search for the best one (small stacks);
 the linear prediction model Eq. 9 (Sec. IV-E).  `timeline` is the two-event
 protocol of Sec. IV-C(ii) written as arithmetic: every closed form above is
 a special case of it, which is how it is pinned
@@ -94,6 +96,53 @@ def interleaved_placement(k, L=36):
         return list(range(L))
     assert 1 <= k <= L - 1
     return [(i * (L - 1)) // k for i in range(k)]
+
+
+# ---- Sec. IV-D over several modules that share the slots (Sec. IV-C(i)) ------------------
+def residency_value(k, L, M_bytes, b3):
+    """Time saved (ms) by keeping k of a module's L layers resident, taken in the order the per-position tables
+    rank them (first, then the middle layers, the last one last): sum of B * M over those layers, B in ms/MiB,
+    middle and last capped by the ranks before them as the ranking requires."""
+    b_first, b_mid, b_last = b3
+    b_mid = min(b_mid, b_first)
+    b_last = min(b_last, b_mid)
+    mib = M_bytes / 1048576.0
+    v = 0.0
+    for j in range(k):                       # j-th layer taken
+        if j == 0:
+            v += b_first * mib
+        elif j == L - 1:
+            v += b_last * mib
+        else:
+            v += b_mid * mib
+    return v
+
+
+def residency_bytes(k, L, M_bytes, n_slots=2):
+    """Device bytes of a residency (k_m) over modules with L_m layers of M_m bytes: the resident copies plus
+    n_slots slots of the largest layer among the modules that still stream one (none if nothing streams)."""
+    streaming = [M_bytes[m] for m in range(len(k)) if k[m] < L[m]]
+    return sum(k[m] * M_bytes[m] for m in range(len(k))) + (n_slots * max(streaming) if streaming else 0)
+
+
+def plan_shared_slots_exhaustive(L, M_bytes, b3, budget_bytes, n_slots=2):
+    """The residency (k_m) with the largest total residency_value among all that fit the budget, found by trying every
+    vector of counts (small stacks only).  Ties: fewer resident bytes.  Returns (k, value) or None if nothing fits."""
+    best = None
+    def rec(m, k):
+        nonlocal best
+        if m == len(L):
+            if residency_bytes(k, L, M_bytes, n_slots) > budget_bytes:
+                return
+            v = sum(residency_value(k[i], L[i], M_bytes[i], b3[i]) for i in range(len(L)))
+            by = sum(k[i] * M_bytes[i] for i in range(len(L)))
+            if best is None or v > best[1] + 1e-12 or (abs(v - best[1]) <= 1e-12 and by < best[2]):
+                best = (list(k), v, by)
+            return
+        for j in range(L[m] + 1):
+            rec(m + 1, k + [j])
+    rec(0, [])
+    return None if best is None else (best[0], best[1])
 
 
 # ---- Sec. IV-E ---------------------------------------------------------------

@@ -111,6 +111,7 @@ SIGNATURES = {
     "dl_timeline": (_i32, [_PF64, _PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
                            _f64, _PF64, _PF64, _PF64]),
     "dl_plan": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _PI32]),
+    "dl_plan_shared_slots": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _i32, _PI32]),
 }
 
 _LIB = None
@@ -382,6 +383,19 @@ def timeline(c_dma_ms, c_exe_ms, streamed, pass_start, module_id=None, mode=DL_M
     if rc != DL_OK:
         raise DLError(rc, "dl_timeline: invalid argument")
     return dict(total=tot.value, hidden=hid.value, exposed=exp_.value)
+
+
+def plan_shared_slots(n_layers, layer_bytes, b3, budget_bytes, n_slots=2):
+    """dl_plan_shared_slots: budget_bytes covers resident layers AND the slots, which are sized by the modules that
+    still stream a layer."""
+    m = len(n_layers)
+    flat = [v for row in b3 for v in row]
+    out = (_i32 * m)()
+    rc = lib().dl_plan_shared_slots(m, _arr(_i32, n_layers), _arr(_u64, layer_bytes), _arr(_f64, flat), int(budget_bytes),
+                                    int(n_slots), out)
+    if rc != DL_OK:
+        raise DLError(rc, "dl_plan_shared_slots: " + ("budget cannot hold the slots" if rc == DL_ERR_BUDGET_EXCEEDED else "invalid argument"))
+    return list(out)
 
 
 def plan(n_layers, layer_bytes, b3, budget_bytes):

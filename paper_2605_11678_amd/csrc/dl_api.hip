@@ -145,15 +145,19 @@ int32_t rebalance(dl_ctx* c, int32_t mi, const std::vector<uint8_t>* new_res) {
     // 1. release copies of layers that stop being resident
     for (int32_t i = 0; i < M.d.n_layers; ++i)
         if (M.resident[size_t(i)] && !res[size_t(i)]) A.free(off[size_t(i)]);
-    // 2. slots: two buffers of the largest layer over all modules, needed while anything streams
+    // 2. slots: two buffers of the largest layer that may be copied into one, i.e. over the modules that stream at
+    // least one layer (a fully resident module never touches a slot, so it does not size them: with the 8B decoder
+    // resident the pair shrinks from 2 x 386 MB to what the small stacks need); none while nothing streams
     uint64_t need_bytes = 0;
     bool any_streamed = false;
     for (size_t m = 0; m < c->mods.size(); ++m) {
         const Module& X = c->mods[m];
         if (!X.finalized && int32_t(m) != mi) continue;
-        need_bytes = std::max(need_bytes, X.L.bytes);
         const std::vector<uint8_t>& r = (int32_t(m) == mi) ? res : X.resident;
-        for (uint8_t v : r) any_streamed |= !v;
+        bool streams = false;
+        for (uint8_t v : r) streams |= !v;
+        if (streams) need_bytes = std::max(need_bytes, X.L.bytes);
+        any_streamed |= streams;
     }
     bool slots_alloc = c->slots_alloc;
     uint64_t slot_off[2] = {c->slot_off[0], c->slot_off[1]};
@@ -992,7 +996,8 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         rc = check_forward_args(c, M, x, const_cast<void*>(x), T, pos0, ctx, n_ctx);
         if (rc) return rc;
     }
-    if (!c->slots_alloc) return fail(c, DL_ERR_BAD_STATE, "no slots: every layer is resident, nothing to profile through");
+    if (!c->slots_alloc || c->slot_bytes < M->L.bytes)
+        return fail(c, DL_ERR_BAD_STATE, "the slots cannot hold this module's layers (it is fully resident): profile with at least one of its layers streamed");
     rc = sync_streams(c);
     if (rc) return rc;
     if (!c->copies.empty() || !c->execs.empty()) return fail(c, DL_ERR_BAD_STATE, "collect pending statistics first");

@@ -530,4 +530,87 @@ int32_t dl_plan(int32_t n_modules, const int32_t* n_layers, const uint64_t* laye
     return DL_OK;
 }
 
+int32_t dl_plan_shared_slots(int32_t n_modules, const int32_t* n_layers, const uint64_t* layer_bytes, const double* b3,
+                             uint64_t budget_bytes, int32_t n_slots, int32_t* k_out) {
+    if (n_modules < 1 || n_modules > 12 || !n_layers || !layer_bytes || !b3 || !k_out || n_slots < 1) return DL_ERR_INVALID_ARG;
+    for (int32_t m = 0; m < n_modules; ++m) {
+        if (n_layers[m] < 1 || layer_bytes[m] == 0) return DL_ERR_INVALID_ARG;
+        const double* b = b3 + 3 * m;
+        if (!(b[0] >= 0) || !(b[1] >= 0) || !(b[2] >= 0)) return DL_ERR_INVALID_ARG;
+    }
+    const double MiB = 1048576.0;
+    // benefit (ms) of the first j resident layers of module m in dl_plan's order: first, middles, last
+    auto value_of = [&](int32_t m, int32_t j) {
+        const double* b = b3 + 3 * m;
+        const double mib = double(layer_bytes[m]) / MiB;
+        const int32_t L = n_layers[m];
+        double v = 0.0;
+        if (j >= 1) v += b[0] * mib;
+        if (L > 2) v += std::min(b[1], b[0]) * mib * double(std::min(std::max(j - 1, 0), L - 2));
+        if (L >= 2 && j >= L) v += std::min(b[2], std::min(b[1], b[0])) * mib;
+        return v;
+    };
+    bool found = false;
+    double best_v = -1.0;
+    uint64_t best_bytes = 0;
+    std::vector<int32_t> best(size_t(n_modules), 0), cur(size_t(n_modules), 0);
+    std::vector<int32_t> sub_layers;
+    std::vector<uint64_t> sub_bytes;
+    std::vector<double> sub_b3;
+    std::vector<int32_t> sub_index, sub_k;
+    for (uint32_t F = 0; F < (1u << n_modules); ++F) {
+        uint64_t fixed = 0, slot = 0;
+        bool overflow = false;
+        for (int32_t m = 0; m < n_modules; ++m) {
+            if ((F >> m) & 1u) {
+                fixed += uint64_t(n_layers[m]) * layer_bytes[m];
+                if (fixed > budget_bytes) { overflow = true; break; }
+            } else {
+                slot = std::max(slot, layer_bytes[m]);
+            }
+        }
+        if (overflow) continue;
+        fixed += uint64_t(n_slots) * slot;
+        if (fixed > budget_bytes) continue;
+        // the modules outside F keep at least their last layer streamed: hand dl_plan a stack without it
+        sub_layers.clear(); sub_bytes.clear(); sub_b3.clear(); sub_index.clear();
+        for (int32_t m = 0; m < n_modules; ++m) {
+            if ((F >> m) & 1u) { cur[size_t(m)] = n_layers[m]; continue; }
+            cur[size_t(m)] = 0;
+            if (n_layers[m] < 2) continue;                 // its only layer is the streamed one
+            sub_index.push_back(m);
+            sub_layers.push_back(n_layers[m] - 1);
+            sub_bytes.push_back(layer_bytes[m]);
+            // a stack of L - 1 layers whose "last" group is one more middle layer (or the first, if L == 2)
+            const double* b = b3 + 3 * m;
+            const double mid = std::min(b[1], b[0]);
+            sub_b3.push_back(b[0]);
+            sub_b3.push_back(mid);
+            sub_b3.push_back(n_layers[m] - 1 >= 2 ? mid : b[0]);
+        }
+        if (!sub_index.empty()) {
+            sub_k.assign(sub_index.size(), 0);
+            const int32_t rc = dl_plan(int32_t(sub_index.size()), sub_layers.data(), sub_bytes.data(), sub_b3.data(),
+                                       budget_bytes - fixed, sub_k.data());
+            if (rc != DL_OK) return rc;
+            for (size_t i = 0; i < sub_index.size(); ++i) cur[size_t(sub_index[i])] = sub_k[i];
+        }
+        double v = 0.0;
+        uint64_t bytes = 0;
+        for (int32_t m = 0; m < n_modules; ++m) {
+            v += value_of(m, cur[size_t(m)]);
+            bytes += uint64_t(cur[size_t(m)]) * layer_bytes[m];
+        }
+        if (!found || v > best_v || (v == best_v && bytes < best_bytes)) {
+            found = true;
+            best_v = v;
+            best_bytes = bytes;
+            best = cur;
+        }
+    }
+    if (!found) return DL_ERR_BUDGET_EXCEEDED;
+    for (int32_t m = 0; m < n_modules; ++m) k_out[m] = best[size_t(m)];
+    return DL_OK;
+}
+
 }  // extern "C"

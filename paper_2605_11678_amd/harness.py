@@ -187,6 +187,19 @@ class VlaPipeline:
             ctx.axpy(self.p_a, 1.0 / n_euler, self.p_vel, self.n_actions * da)
         ctx.mlp_forward(self.mlp_out, self.p_a, self.p_traj, self.n_actions)
 
+    def enqueue_glue(self, n_euler: int = 10):
+        """Only the launches of `enqueue` that belong to no layer and not to the greedy head: projector, pooling,
+        final norm, time embeddings, Euler updates, output projection (what a latency model has to add as a constant)."""
+        ctx = self.eng.ctx
+        d, da = self.dec.d_model, self.act.d_model
+        ctx.mlp_forward(self.mlp_proj, self.p_vit, self.p_proj, self.n_patches)
+        ctx.mean_pool(self.p_proj, self.p_seq, self.n_vis, self.pool, d)
+        ctx.final_norm(self.m_dec, self.p_h, self.p_ctx, self.n_prefill)
+        for s in range(n_euler):
+            ctx.add_time_embedding(self.p_a, self.p_ain, s / n_euler, self.n_actions, da)
+            ctx.axpy(self.p_a, 1.0 / n_euler, self.p_vel, self.n_actions * da)
+        ctx.mlp_forward(self.mlp_out, self.p_a, self.p_traj, self.n_actions)
+
     def results(self, n_decode: int):
         e = self.eng
         toks = e.download(self.v_tok[:min(n_decode, 64)]).view(np.int32).tolist() if n_decode else []

@@ -290,6 +290,83 @@ def test_all_resident_releases_slots_and_bigger_module_resizes_them():
     eng.close()
 
 
+def test_fully_resident_module_does_not_size_the_slots():
+    """Sec. IV-C(i) with several modules: the slot pair holds the largest layer that can still be copied into it."""
+    small, big = small_cfg(3), small_cfg(2, d_ff=1536)
+    eng, m_small = _host_engine_with_module(small, cap=1 << 30)
+    p_small, _ = eng.ctx.module_layer_bytes(m_small)
+    rng = np.random.default_rng(1)
+    m_big = eng.add_module(big, 8, weights=tiny_weights(big, rng))
+    p_big, _ = eng.ctx.module_layer_bytes(m_big)
+    assert p_big > p_small
+    used_all_streamed = eng.ctx.arena_stats()["used"]
+    fixed = used_all_streamed - 2 * p_big                      # workspaces and KV caches of both modules
+    # the big module fully resident: its two copies, and the pair shrinks to the small module's layers
+    eng.ctx.set_residency(m_big, [0, 1])
+    assert eng.ctx.arena_stats()["used"] == fixed + 2 * p_big + 2 * p_small
+    eng.ctx.trace_read()                                       # drop what has been recorded so far
+    eng.ctx.forward(m_small, 0, 0, 1, 0)                       # still streams, through the smaller slots
+    assert sum(o["op"] == B.DL_OP_COPY for o in eng.ctx.trace_read()) == 3
+    eng.ctx.forward(m_big, 0, 0, 1, 0)
+    # one layer of the big module streams again: the pair grows back before anything else is placed
+    eng.ctx.set_residency(m_big, [1])
+    assert eng.ctx.arena_stats()["used"] == fixed + p_big + 2 * p_big
+    # both fully resident: no slots at all
+    eng.ctx.set_residency(m_big, [0, 1])
+    eng.ctx.set_residency(m_small, [0, 1, 2])
+    assert eng.ctx.arena_stats()["used"] == fixed + 2 * p_big + 3 * p_small
+    eng.close()
+
+
+def _fits(k, L, M, budget, n_slots=2):
+    return P.residency_bytes(k, L, M, n_slots) <= budget
+
+
+def test_plan_shared_slots_against_exhaustive_search():
+    rng = np.random.default_rng(5)
+    for trial in range(60):
+        n = int(rng.integers(1, 4))
+        L = [int(rng.integers(1, 7)) for _ in range(n)]
+        equal = trial % 2 == 0
+        M = [4096 * int(rng.integers(1, 9))] * n if equal else [4096 * int(rng.integers(1, 9)) for _ in range(n)]
+        b3 = []
+        for _ in range(n):
+            first = float(rng.uniform(0.0, 2.0))
+            mid = first * float(rng.uniform(0.3, 1.0))
+            b3.append([first, mid, mid * float(rng.uniform(0.0, 1.0))])
+        total = sum(L[m] * M[m] for m in range(n))
+        budget = int(rng.integers(2 * max(M), total + 2 * max(M) + 1))
+        k = B.plan_shared_slots(L, M, b3, budget)
+        assert all(0 <= k[m] <= L[m] for m in range(n)) and _fits(k, L, M, budget)
+        v = sum(P.residency_value(k[m], L[m], M[m], b3[m]) for m in range(n))
+        k_best, v_best = P.plan_shared_slots_exhaustive(L, M, b3, budget)
+        assert v <= v_best + 1e-9
+        if equal:
+            # equal layer sizes: ranking by benefit per MiB is ranking by benefit, the greedy choice is optimal
+            assert v == pytest.approx(v_best, rel=1e-12, abs=1e-12)
+        # never worse than planning with the slots fixed at the largest layer of all modules
+        k_fixed = B.plan(L, M, b3, budget - 2 * max(M))
+        assert v >= sum(P.residency_value(k_fixed[m], L[m], M[m], b3[m]) for m in range(n)) - 1e-9
+
+
+def test_plan_shared_slots_special_cases():
+    M = 1 << 20
+    b = [[1.0, 1.0, 0.5]]
+    assert B.plan_shared_slots([10], [M], b, 10 * M) == [10]              # everything fits once the slots are gone
+    assert B.plan_shared_slots([10], [M], b, 10 * M - 1) == [7]            # else two slots come off the budget
+    assert B.plan_shared_slots([10], [M], b, 2 * M) == [0]
+    with pytest.raises(B.DLError) as e:
+        B.plan_shared_slots([10], [M], b, 2 * M - 1)
+    assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED
+    # the module with the large layers goes fully resident and the pair shrinks to the small module's layers
+    L, Ms, b3 = [4, 6], [1 * M, 8 * M], [[0.2, 0.2, 0.1], [1.0, 1.0, 0.9]]
+    assert B.plan_shared_slots(L, Ms, b3, 6 * 8 * M + 2 * M + 1 * M) == [1, 6]
+    assert B.plan(L, Ms, b3, 6 * 8 * M + 3 * M - 2 * 8 * M) == [3, 4]      # with fixed 2 x 8 MiB slots: two big layers less
+    assert B.plan_shared_slots(L, Ms, b3, 6 * 8 * M + 4 * M) == [4, 6]     # everything resident, no slots
+    # a benefit of zero buys nothing
+    assert B.plan_shared_slots([3], [M], [[0.0, 0.0, 0.0]], 100 * M) == [0]
+
+
 def test_error_paths():
     c = small_cfg(2)
     eng = Engine(1 << 30, device=-1)

@@ -236,3 +236,36 @@ def test_timeline_corrections_closed_forms():
     a = [[(2.0, 3.0, True), (1.0, 0.5, False), (2.5, 0.7, True)]] * 3
     b = [[(d, e, s, e, 0.0) for (d, e, s) in layers] for layers in a]
     assert P.timeline(a)["total"] == P.timeline(b)["total"]
+
+
+def test_shared_slot_residency_bytes_and_value_closed_forms():
+    M = [3 << 20, 7 << 20]
+    L = [4, 5]
+    # bytes: copies + two slots of the largest layer that still streams; none when nothing streams
+    assert P.residency_bytes([0, 0], L, M) == 2 * M[1]
+    assert P.residency_bytes([4, 2], L, M) == 4 * M[0] + 2 * M[1] + 2 * M[1]
+    assert P.residency_bytes([1, 5], L, M) == M[0] + 5 * M[1] + 2 * M[0]
+    assert P.residency_bytes([4, 5], L, M) == 4 * M[0] + 5 * M[1]
+    assert P.residency_bytes([1, 5], L, M, n_slots=3) == M[0] + 5 * M[1] + 3 * M[0]
+    # value: Table VI's positions, first + middles + last, in MiB
+    b3 = P.benefit_hybrid(N=21, C_DMA=11.0, C_decode=0.9, M=7.0)
+    full = P.residency_value(5, 5, M[1], b3)
+    assert full == pytest.approx((b3[0] + 3 * b3[1] + b3[2]) * 7.0)
+    # all resident removes exactly what Eq. 7 pays for transfers beyond the last decode's trailing execution
+    assert full == pytest.approx((21 + 1) * 11.0 + 3 * 21 * 11.0 + 21 * (11.0 - 0.9))
+    assert P.residency_value(0, 5, M[1], b3) == 0.0
+    assert P.residency_value(3, 5, M[1], b3) == pytest.approx((b3[0] + 2 * b3[1]) * 7.0)
+
+
+def test_shared_slot_exhaustive_search_single_module_closed_form():
+    M = 1 << 20
+    b3 = [(1.0, 0.8, 0.3)]
+    for L in (1, 2, 5):
+        for budget in range(0, (L + 3) * M + 1, M // 2):
+            got = P.plan_shared_slots_exhaustive([L], [M], b3, budget)
+            if budget >= L * M:
+                assert got[0] == [L]                 # no slots once everything is resident
+            elif budget < 2 * M:
+                assert got is None                   # not even the two slots fit
+            else:
+                assert got[0] == [min(L - 1, (budget - 2 * M) // M)]
