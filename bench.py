@@ -90,11 +90,11 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
         ctx.set_timing(False)
         return ms, st
 
-    def predict(resident, steps, wrap):
+    def predict(resident, steps, wrap, n_slots=2):
         rs = set(resident)
         streamed = [i not in rs for i in range(L)] * steps
         starts = [i == 0 for i in range(L)] * steps
-        return B.timeline(c_dma * steps, c_hot * steps, streamed, starts, wrap_prefetch=wrap,
+        return B.timeline(c_dma * steps, c_hot * steps, streamed, starts, wrap_prefetch=wrap, n_slots=n_slots,
                           c_exe_idle_ms=c_exe * steps, c_fence_ms=c_fence * steps)["total"] / steps + head_ms
 
     def fit_count():
@@ -112,16 +112,26 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
         ballast = ctx.arena_alloc(ballast_bytes) if ballast_bytes else None
         try:
             kfit = fit_count()
-            policies = [("none", []), ("interleaved_eq8", B.place_interleaved(L, kfit))]
+            policies = [("none", [], 2), ("interleaved_eq8", B.place_interleaved(L, kfit), 2)]
             if 0 < kfit < L:
-                policies.append(("first_k_consecutive", list(range(kfit))))
-            for name, resident in policies:
+                policies.append(("first_k_consecutive", list(range(kfit)), 2))
+                # a copy takes ~60 x longer than a single-token layer executes: the overlap a second slot buys is worth
+                # less than the resident layer its memory holds
+                ctx.set_residency(mid, [])
+                ctx.set_slot_count(1)
+                kfit1 = fit_count()
+                ctx.set_residency(mid, [])
+                ctx.set_slot_count(2)
+                policies.append(("interleaved_eq8_one_slot", B.place_interleaved(L, kfit1), 1))
+            for name, resident, n_slots in policies:
                 streamed_n = L - len(resident)
                 steps = 64 if streamed_n * float(np.mean(c_dma)) < 40 else 6
+                ctx.set_residency(mid, [])
+                ctx.set_slot_count(n_slots)
                 for wrap in ((0, 1) if streamed_n else (0,)):
                     ms, st = run(resident, steps, wrap)
-                    pred = predict(resident, steps, wrap)
-                    row = {"cap": cap_name, "policy": name, "k": len(resident), "wrap_prefetch": wrap, "steps": steps,
+                    pred = predict(resident, steps, wrap, n_slots)
+                    row = {"cap": cap_name, "policy": name, "k": len(resident), "slots": n_slots, "wrap_prefetch": wrap, "steps": steps,
                            "ms_per_token": round(ms, 3), "predicted_ms_per_token": round(pred, 3),
                            "pred_err_pct": round((pred - ms) / ms * 100, 2), "hidden_frac": round(st["hidden_frac"], 4),
                            "h2d_gbps": round(st["h2d_gbps"], 2),
@@ -133,6 +143,7 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
                         (cap_name, name, len(resident), wrap, ms, pred, row["pred_err_pct"], st["hidden_frac"]))
         finally:
             ctx.set_residency(mid, [])
+            ctx.set_slot_count(2)
             if ballast:
                 ctx.arena_free(ballast)
     return res

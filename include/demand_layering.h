@@ -141,6 +141,14 @@ int32_t dl_get_residency(const dl_ctx* ctx, int32_t module, int32_t* idx_out, in
  * module's pass simply re-issues its own first copy). */
 int32_t dl_set_mode(dl_ctx* ctx, int32_t mode, int32_t wrap_prefetch);
 
+/* Number of device slots the streamed layers go through: 2 (default: the Double Flat Buffer of Sec. IV-C(i), the copy
+ * of the next streamed layer overlaps the execution of the current one) or 1 (the copy of the next streamed layer
+ * starts when the current one has executed and overlaps only the resident layers in between).  One slot gives a whole
+ * layer of memory back: where a layer's copy takes far longer than its execution (single-token passes: ~60 x) the
+ * overlap lost is worth less than one more resident layer.  Synchronises both streams and re-sizes the slots;
+ * DL_ERR_BUDGET_EXCEEDED: nothing changed. */
+int32_t dl_set_slot_count(dl_ctx* ctx, int32_t n_slots);
+
 /* How many streaming passes (passes that copy at least one layer) may be unfinished when the next one is
  * enqueued (1..8; 0 = no limit).  Default 1: each further pass of short streamed layers in flight slowed copies and
  * kernels on MI355X (+4 % with two, +25 % with four).  Passes of resident layers only are never held back. */
@@ -303,12 +311,12 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * waiting for its copy right before it (a GPU that idled runs the next kernels slower than one
  * kept busy; dl_profile measures both).  c_fence_ms (NULL = zeros): time added on the compute queue to
  * every streamed invocation for its two cross-stream hand-offs (dl_profile's c_fence_ms).
- * mode, wrap_prefetch: as dl_set_mode.  overhead_ms is added to every execution (fixed
- * host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
+ * mode, wrap_prefetch: as dl_set_mode; n_slots: as dl_set_slot_count (1 or 2).  overhead_ms is added to every
+ * execution (fixed host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
  * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
 int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
                     const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
-                    int32_t mode, int32_t wrap_prefetch, double overhead_ms,
+                    int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms);
 
 /* Budgeted choice of resident layers over several modules from one profiling run (Sec. IV-D).

@@ -109,7 +109,8 @@ SIGNATURES = {
     "dl_consecutive_limit": (_i32, [_f64, _f64, _PI32]),
     "dl_predict_linear": (_i32, [_f64, _f64, _i32, _PF64]),
     "dl_timeline": (_i32, [_PF64, _PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
-                           _f64, _PF64, _PF64, _PF64]),
+                           _i32, _f64, _PF64, _PF64, _PF64]),
+    "dl_set_slot_count": (_i32, [_p, _i32]),
     "dl_plan": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _PI32]),
     "dl_plan_shared_slots": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _i32, _PI32]),
 }
@@ -311,6 +312,10 @@ class Context:
     def set_run_ahead(self, passes):
         self._ck(lib().dl_set_run_ahead(self._h, int(passes)))
 
+    def set_slot_count(self, n_slots):
+        """1 or 2 device slots for the streamed layers (re-sizes them)."""
+        self._ck(lib().dl_set_slot_count(self._h, int(n_slots)))
+
     def probe_mfma_rate(self, pattern=1, iters=20000):
         """Register-only BF16 MFMA rate of the device in TFLOP/s (diagnostic)."""
         out = C.c_double(0.0)
@@ -370,7 +375,7 @@ def predict_linear(c_total0_ms, slope_ms_per_layer, k):
 
 
 def timeline(c_dma_ms, c_exe_ms, streamed, pass_start, module_id=None, mode=DL_MODE_PIPELINED, wrap_prefetch=0,
-             overhead_ms=0.0, c_exe_idle_ms=None, c_fence_ms=None):
+             overhead_ms=0.0, c_exe_idle_ms=None, c_fence_ms=None, n_slots=2):
     n = len(c_dma_ms)
     tot, hid, exp_ = _f64(), _f64(), _f64()
     rc = lib().dl_timeline(_arr(_f64, c_dma_ms), _arr(_f64, c_exe_ms),
@@ -379,7 +384,7 @@ def timeline(c_dma_ms, c_exe_ms, streamed, pass_start, module_id=None, mode=DL_M
                            _arr(C.c_uint8, [1 if s else 0 for s in streamed]),
                            _arr(C.c_uint8, [1 if s else 0 for s in pass_start]),
                            None if module_id is None else _arr(_i32, module_id), n, mode, int(wrap_prefetch),
-                           overhead_ms, C.byref(tot), C.byref(hid), C.byref(exp_))
+                           int(n_slots), overhead_ms, C.byref(tot), C.byref(hid), C.byref(exp_))
     if rc != DL_OK:
         raise DLError(rc, "dl_timeline: invalid argument")
     return dict(total=tot.value, hidden=hid.value, exposed=exp_.value)

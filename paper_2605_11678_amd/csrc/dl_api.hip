@@ -57,6 +57,8 @@ struct dl_ctx {
     std::vector<Mlp> mlps;
     uint64_t slot_bytes = 0;
     uint64_t slot_off[2] = {0, 0};
+    int32_t n_slots = 2;          // device slots in use: 1 or 2
+    int32_t slots_held = 0;       // how many of slot_off[] are allocated right now
     bool slots_alloc = false;
     dl::SlotBook book;
     hipEvent_t ev_dma[2] = {nullptr, nullptr}, ev_comp[2] = {nullptr, nullptr}, ev_pass = nullptr;
@@ -162,15 +164,17 @@ int32_t rebalance(dl_ctx* c, int32_t mi, const std::vector<uint8_t>* new_res) {
     bool slots_alloc = c->slots_alloc;
     uint64_t slot_off[2] = {c->slot_off[0], c->slot_off[1]};
     uint64_t slot_bytes = c->slot_bytes;
-    if (slots_alloc && (!any_streamed || slot_bytes != need_bytes)) {
-        A.free(slot_off[0]);
-        A.free(slot_off[1]);
+    int32_t slots_held = c->slots_held;
+    if (slots_alloc && (!any_streamed || slot_bytes != need_bytes || slots_held != c->n_slots)) {
+        for (int32_t k = 0; k < slots_held; ++k) A.free(slot_off[k]);
         slots_alloc = false;
+        slots_held = 0;
     }
     if (any_streamed && !slots_alloc) {
-        if (!A.alloc(need_bytes, &slot_off[0]) || !A.alloc(need_bytes, &slot_off[1]))
-            return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the two layer slots");
+        for (int32_t k = 0; k < c->n_slots; ++k)
+            if (!A.alloc(need_bytes, &slot_off[k])) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the layer slots");
         slots_alloc = true;
+        slots_held = c->n_slots;
         slot_bytes = need_bytes;
     }
     // 3. copies of newly resident layers
@@ -192,9 +196,11 @@ int32_t rebalance(dl_ctx* c, int32_t mi, const std::vector<uint8_t>* new_res) {
     c->slot_off[0] = slot_off[0];
     c->slot_off[1] = slot_off[1];
     c->slot_bytes = slot_bytes;
+    c->slots_held = slots_held;
     M.resident = res;
     M.res_off = off;
     c->book = dl::SlotBook();
+    c->book.n_slots = c->n_slots;
     if (on_gpu(c)) {
         for (int32_t i : to_upload)
             DL_HIP(c, hipMemcpy(c->base + off[size_t(i)], M.store + size_t(i) * M.L.bytes, M.L.bytes,
@@ -544,6 +550,7 @@ int32_t dl_set_streams(dl_ctx* c, void* compute_stream, void* copy_stream) {
     c->s_copy = static_cast<hipStream_t>(copy_stream);
     c->streams_set = true;
     c->book = dl::SlotBook();
+    c->book.n_slots = c->n_slots;
     return make_events(c);
 }
 
@@ -1012,6 +1019,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     c->timing = true;
     c->tracing = false;
     c->book = dl::SlotBook();
+    c->book.n_slots = c->n_slots;
     const int32_t Ln = M->d.n_layers;
     std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0), hot(size_t(Ln), 0.0), fence(size_t(Ln), 0.0);
     for (int32_t it = 0; it < iters && rc == DL_OK; ++it) {
@@ -1040,7 +1048,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     // far larger than the 256 MB memory-side cache), so the run must not keep re-reading one slot: the layers rotate
     // through the two slots plus temporary copies, one buffer per layer if the arena can spare that much (re-reading
     // three 386 MB buffers made single-token passes look 7 % faster than passes over 36 resident layers are).
-    std::vector<uint64_t> rot = {c->slot_off[0], c->slot_off[1]};
+    std::vector<uint64_t> rot(c->slot_off, c->slot_off + c->slots_held);
     std::vector<uint64_t> rot_tmp;
     {
         for (uint64_t j = 0; int64_t(j) + 2 < Ln; ++j) {
@@ -1112,6 +1120,7 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     c->timing = timing0;
     c->tracing = tracing0;
     c->book = dl::SlotBook();
+    c->book.n_slots = c->n_slots;
     sync_streams(c);
     for (uint64_t off : rot_tmp) c->arena.free(off);
     c->copies.clear();
@@ -1134,6 +1143,27 @@ int32_t dl_set_run_ahead(dl_ctx* c, int32_t passes) {
     if (rc) return rc;
     if (passes < 0 || passes > dl_ctx::kMaxRunAhead) return fail(c, DL_ERR_INVALID_ARG, "run-ahead outside [0, 8]");
     c->run_ahead = passes;
+    return DL_OK;
+}
+
+int32_t dl_set_slot_count(dl_ctx* c, int32_t n_slots) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (n_slots != 1 && n_slots != 2) return fail(c, DL_ERR_INVALID_ARG, "slot count must be 1 or 2");
+    if (n_slots == c->n_slots) return DL_OK;
+    rc = sync_streams(c);
+    if (rc) return rc;
+    const int32_t before = c->n_slots;
+    c->n_slots = n_slots;
+    // re-size through the same path as a residency change (of any finalized module, keeping its residency)
+    for (size_t m = 0; m < c->mods.size(); ++m) {
+        if (!c->mods[m].finalized) continue;
+        rc = rebalance(c, int32_t(m), nullptr);
+        if (rc) c->n_slots = before;
+        return rc;
+    }
+    c->book = dl::SlotBook();
+    c->book.n_slots = c->n_slots;
     return DL_OK;
 }
 

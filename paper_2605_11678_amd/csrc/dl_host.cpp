@@ -290,7 +290,7 @@ void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32
             int32_t s = -1;
             if (st) {
                 ++si;
-                s = int32_t(book->ordinal++ % 2);
+                s = int32_t(book->ordinal++ % uint64_t(book->n_slots));
                 if (book->pass_recorded) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_PASS_DONE, -1, module, i));
                 ops->push_back(mk(QD, DL_OP_COPY, -1, s, module, i));
                 ops->push_back(mk(QD, DL_OP_RECORD, DL_EV_DMA_DONE, s, module, i));
@@ -309,7 +309,7 @@ void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32
     }
 
     auto issue_copy = [&](int32_t layer, bool gate_on_pass) -> int32_t {
-        const int32_t s = int32_t(book->ordinal++ % 2);
+        const int32_t s = int32_t(book->ordinal++ % uint64_t(book->n_slots));
         if (gate_on_pass && book->pass_recorded) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_PASS_DONE, -1, module, layer));
         // the slot may be overwritten only after the layer that last used it has executed
         if (book->compute_recorded[s]) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_COMPUTE_DONE, s, module, layer));
@@ -329,6 +329,24 @@ void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32
     }
     book->pending_module = book->pending_layer = book->pending_slot = -1;
 
+    // the copy that follows streamed layer number si: the next streamed layer, or (cross-pass prefetch) the first
+    // streamed layer of the next pass
+    auto issue_following = [&](size_t si) {
+        if (si < streamed.size()) {
+            slot_of[streamed[si]] = issue_copy(streamed[si], false);
+        } else if (wrap_prefetch) {
+            book->pending_slot = issue_copy(streamed[0], false);
+            for (size_t b = ops->size(); b-- > 0;)
+                if ((*ops)[b].op == DL_OP_COPY) { (*ops)[b].flags |= DL_OPF_NEXT_PASS; break; }
+            book->pending_module = module;
+            book->pending_layer = streamed[0];
+        }
+    };
+    // With two slots the following copy goes to the other slot, whose last user has long recorded its compute-done
+    // event: it is issued before this layer executes and overlaps it.  With one slot it overwrites THIS layer's
+    // parameters, so it is issued after this layer's compute-done record (a wait refers to the latest record issued
+    // before it) and overlaps only the resident layers that follow.
+    const bool one_slot = book->n_slots == 1;
     size_t si = 0;
     for (int32_t i = 0; i < n_layers; ++i) {
         const bool st = si < streamed.size() && streamed[si] == i;
@@ -338,20 +356,13 @@ void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32
             // a layer never executes before its parameters have arrived
             ops->push_back(mk(QC, DL_OP_WAIT, DL_EV_DMA_DONE, s, module, i));
             ++si;
-            if (si < streamed.size()) {
-                slot_of[streamed[si]] = issue_copy(streamed[si], false);   // prefetch the next streamed layer
-            } else if (wrap_prefetch) {
-                book->pending_slot = issue_copy(streamed[0], false);       // first streamed layer of the next pass
-                for (size_t b = ops->size(); b-- > 0;)
-                    if ((*ops)[b].op == DL_OP_COPY) { (*ops)[b].flags |= DL_OPF_NEXT_PASS; break; }
-                book->pending_module = module;
-                book->pending_layer = streamed[0];
-            }
+            if (!one_slot) issue_following(si);
         }
         ops->push_back(mk(QC, DL_OP_EXEC, -1, s, module, i));
         if (st) {
             ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_COMPUTE_DONE, s, module, i));
             book->compute_recorded[s] = true;
+            if (one_slot) issue_following(si);
         }
     }
     ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_PASS_DONE, -1, module, n_layers - 1));
@@ -413,9 +424,10 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
 
 int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
                     const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
-                    int32_t mode, int32_t wrap_prefetch, double overhead_ms,
+                    int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms) {
     if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
+    if (n_slots != 1 && n_slots != 2) return DL_ERR_INVALID_ARG;
     if (mode != DL_MODE_PIPELINED && mode != DL_MODE_SEQUENTIAL) return DL_ERR_INVALID_ARG;
     if (n > 0 && !pass_start[0]) return DL_ERR_INVALID_ARG;
     // Replays the very schedule a pass enqueues (build_pass) on two in-order queues.
@@ -428,6 +440,7 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
         j = j1;
     }
     dl::SlotBook book;
+    book.n_slots = n_slots;
     double t[2] = {0, 0};                       // queue clocks: [0] compute, [1] copy
     double ev_dma[2] = {0, 0}, ev_comp[2] = {0, 0}, ev_pass = 0;
     double copy_start[2] = {0, 0}, copy_dur[2] = {0, 0};

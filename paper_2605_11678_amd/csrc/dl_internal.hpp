@@ -73,7 +73,8 @@ KvLayout make_kv(const dl_module_desc& d);
 // ---- the schedule of one pass as data (Sec. IV-C(ii)) ----
 struct SlotBook {
     // persistent across passes
-    uint64_t ordinal = 0;                 // count of copies issued so far; slot = ordinal % 2
+    int32_t n_slots = 2;                  // 1 or 2 device slots
+    uint64_t ordinal = 0;                 // count of copies issued so far; slot = ordinal % n_slots
     bool dma_recorded[2] = {false, false};
     bool compute_recorded[2] = {false, false};
     bool pass_recorded = false;

@@ -35,13 +35,16 @@ def test_tiny_decoder_prefill_parity_and_bit_identity():
         got = g.forward(x, final_norm=True)
         assert rel_err(got, want) <= TOL, rel_err(got, want)
         ref_bits = g.forward_bits(x)
-        # every residency set, both modes, both prefetch settings: identical bits (Table IX)
-        for mask in itertools.product([0, 1], repeat=c.n_layers):
-            g.eng.ctx.set_residency(g.mid, [i for i in range(c.n_layers) if mask[i]])
-            for mode, wrap in ((B.DL_MODE_PIPELINED, 0), (B.DL_MODE_PIPELINED, 1), (B.DL_MODE_SEQUENTIAL, 0)):
-                g.eng.ctx.set_mode(mode, wrap)
-                for rep in range(2):
-                    assert np.array_equal(g.forward_bits(x), ref_bits), (mask, mode, wrap, rep)
+        # every residency set, both modes, both prefetch settings, two slots and one: identical bits (Table IX)
+        for n_slots in (2, 1):
+            g.eng.ctx.set_residency(g.mid, [])
+            g.eng.ctx.set_slot_count(n_slots)
+            for mask in itertools.product([0, 1], repeat=c.n_layers):
+                g.eng.ctx.set_residency(g.mid, [i for i in range(c.n_layers) if mask[i]])
+                for mode, wrap in ((B.DL_MODE_PIPELINED, 0), (B.DL_MODE_PIPELINED, 1), (B.DL_MODE_SEQUENTIAL, 0)):
+                    g.eng.ctx.set_mode(mode, wrap)
+                    for rep in range(2):
+                        assert np.array_equal(g.forward_bits(x), ref_bits), (n_slots, mask, mode, wrap, rep)
     finally:
         g.close()
 

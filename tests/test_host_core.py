@@ -181,8 +181,9 @@ def _ops_for_des(trace, dma, exe):
     return ops
 
 
+@pytest.mark.parametrize("n_slots", [2, 1])
 @pytest.mark.parametrize("wrap", [0, 1])
-def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap):
+def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap, n_slots):
     """The schedule dl_forward enqueues (recorded by a host-only context) is replayed on an independent
     two-queue simulator: a layer never executes before its copy ended, a slot is never overwritten while
     the layer that used it is still running (Sec. IV-C(ii)), and the end time equals both predictors."""
@@ -191,6 +192,7 @@ def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap):
         c = small_cfg(L)
         eng, mid = _host_engine_with_module(c)
         eng.ctx.set_mode(B.DL_MODE_PIPELINED, wrap)
+        eng.ctx.set_slot_count(n_slots)
         dma = [rnd.uniform(0.2, 4) for _ in range(L)]
         exe = [rnd.uniform(0.2, 4) for _ in range(L)]
         for mask in itertools.product([0, 1], repeat=L):
@@ -205,6 +207,7 @@ def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap):
             assert [o["layer"] for o in execs] == list(range(L)) * n_pass
             for o in execs:
                 assert (o["slot"] < 0) == (o["layer"] in resident)
+                assert o["slot"] < n_slots
             ops = _ops_for_des(trace, dma, exe)
             times = simulate(ops)
             # safety: pair every streamed exec with the last copy into its slot
@@ -222,8 +225,8 @@ def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap):
                     busy_until[s] = t1
             total = max(t1 for (q, op), (t0, t1) in zip(ops, times) if q == "compute")
             inv = [[(dma[i], exe[i], not mask[i]) for i in range(L)]] * n_pass
-            assert total == pytest.approx(P.timeline(inv, wrap_prefetch=bool(wrap))["total"], rel=1e-12)
-            assert total == pytest.approx(B.timeline(*_flatten(inv), wrap_prefetch=wrap)["total"], rel=1e-12)
+            assert total == pytest.approx(P.timeline(inv, wrap_prefetch=bool(wrap), n_slots=n_slots)["total"], rel=1e-12)
+            assert total == pytest.approx(B.timeline(*_flatten(inv), wrap_prefetch=wrap, n_slots=n_slots)["total"], rel=1e-12)
         eng.close()
 
 
@@ -287,6 +290,31 @@ def test_all_resident_releases_slots_and_bigger_module_resizes_them():
     assert packed2 > packed
     ws_kv2 = eng.ctx.arena_stats()["used"] - base - 2 * (packed2 - packed)
     assert ws_kv2 > 0            # slots grew to the largest layer over all modules (2 x M_max), plus module 2's workspace
+    eng.close()
+
+
+def test_one_slot_gives_a_layer_back_and_only_overlaps_resident_layers():
+    c = small_cfg(4)
+    eng, mid = _host_engine_with_module(c, cap=1 << 30)
+    packed, _ = eng.ctx.module_layer_bytes(mid)
+    used2 = eng.ctx.arena_stats()["used"]
+    eng.ctx.set_slot_count(1)
+    assert eng.ctx.arena_stats()["used"] == used2 - packed
+    # all streamed through one slot: copy j+1 cannot start before layer j has executed, so nothing overlaps
+    dma, exe = [3.0, 1.0, 2.0, 5.0], [0.5, 0.25, 1.5, 1.0]
+    inv = [[(dma[i], exe[i], True) for i in range(4)]]
+    assert B.timeline(*_flatten(inv), n_slots=1)["total"] == pytest.approx(sum(dma) + sum(exe))
+    assert P.timeline(inv, n_slots=1)["total"] == pytest.approx(sum(dma) + sum(exe))
+    # layers 1 and 2 resident: the copy of layer 3 overlaps their execution
+    inv = [[(dma[0], exe[0], True), (9.0, exe[1], False), (9.0, exe[2], False), (dma[3], exe[3], True)]]
+    want = dma[0] + exe[0] + max(dma[3], exe[1] + exe[2]) + exe[3]
+    assert B.timeline(*_flatten(inv), n_slots=1)["total"] == pytest.approx(want)
+    assert P.timeline(inv, n_slots=1)["total"] == pytest.approx(want)
+    eng.ctx.set_slot_count(2)
+    assert eng.ctx.arena_stats()["used"] == used2
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.set_slot_count(3)
+    assert e.value.code == B.DL_ERR_INVALID_ARG
     eng.close()
 
 
