@@ -121,8 +121,8 @@ def test_encoder_ragged_shapes(T):
 @pytest.mark.parametrize("dh", [64, 128])
 def test_gqa_decoder_prefill_chunks_and_decode(dh):
     c = small_gqa(dh)
-    T0, T1, steps = 200, 70, 3
-    x = CFG.make_tokens(T0 + T1 + steps, c.d_model, seed=23)
+    T0, T1, T2, steps = 200, 70, 13, 3
+    x = CFG.make_tokens(T0 + T1 + T2 + steps, c.d_model, seed=23)
     g = GpuStack(c, max_tokens=T0)
     try:
         kv = F.new_kv_cache(oracle_cfg(c))
@@ -133,8 +133,12 @@ def test_gqa_decoder_prefill_chunks_and_decode(dh):
         want1 = oracle_stack(c, g.weights, x[T0:T0 + T1], T0, kv)
         got1 = g.forward(x[T0:T0 + T1], T0)
         assert rel_err(got1, want1) <= TOL
+        # a third chunk whose first position is not a multiple of 8 (the transposed-V append falls back to 2-byte stores)
+        want2 = oracle_stack(c, g.weights, x[T0 + T1:T0 + T1 + T2], T0 + T1, kv)
+        got2 = g.forward(x[T0 + T1:T0 + T1 + T2], T0 + T1)
+        assert rel_err(got2, want2) <= TOL
         for s in range(steps):
-            p = T0 + T1 + s
+            p = T0 + T1 + T2 + s
             want = oracle_stack(c, g.weights, x[p:p + 1], p, kv)
             got = g.forward(x[p:p + 1], p)      # single-token kernels
             assert rel_err(got, want) <= TOL, (s, rel_err(got, want))
