@@ -146,6 +146,15 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
             ctx.set_slot_count(2)
             if ballast:
                 ctx.arena_free(ballast)
+    # the planner's choice per cap = the candidate (placement, slot count, prefetch setting) with the lowest PREDICTED
+    # time, taken from the one profiling run above; reported next to what that candidate measured
+    res["planner_choice"] = []
+    for cap_name in ("16e9", "12e9"):
+        cand = [r for r in res["runs"] if r["cap"] == cap_name and r["policy"].startswith("interleaved_eq8")]
+        if cand:
+            best = min(cand, key=lambda r: r["predicted_ms_per_token"])
+            res["planner_choice"].append({k: best[k] for k in ("cap", "policy", "k", "slots", "wrap_prefetch",
+                                                               "predicted_ms_per_token", "ms_per_token", "pred_err_pct")})
     return res
 
 
