@@ -161,6 +161,21 @@ def test_cross_attention_module():
         g.close()
 
 
+def test_decoder_without_cache_rotates_k_in_place():
+    """No KV cache: K is rotated inside the QKV rows and attention reads it from there (ragged T)."""
+    c = small_gqa(64)
+    c.max_seq = 0
+    T = 130
+    x = CFG.make_tokens(T, c.d_model, seed=43)
+    g = GpuStack(c, max_tokens=T)
+    try:
+        want = oracle_stack(c, g.weights, x)
+        got = g.forward(x)
+        assert rel_err(got, want) <= TOL, rel_err(got, want)
+    finally:
+        g.close()
+
+
 def test_identity_layer_is_exact():
     """A block whose output projections are zero must return its input bit for bit."""
     c = small_gqa(64)
