@@ -212,10 +212,27 @@ int32_t rebalance(dl_ctx* c, int32_t mi, const std::vector<uint8_t>* new_res) {
 // ---- one layer on the compute stream -------------------------------------------------------------
 using dlk::bf16_t;
 
+// A single-token product may take its input as "the normalisation of an fp32 row" instead of a bf16 vector.
+struct NormSrc {
+    const float* x = nullptr;
+    const bf16_t* g = nullptr;
+    const bf16_t* b = nullptr;
+    int kind = 0;
+    float eps = 0.0f;
+};
+void with_norm(dlk::GemvArgs& g, const NormSrc& n) {
+    g.norm_x = n.x;
+    g.norm_g = n.g;
+    g.norm_b = n.b;
+    g.norm_kind = n.kind;
+    g.norm_eps = n.eps;
+}
+
 void linear(hipStream_t st, int T, const bf16_t* A, int lda, const bf16_t* B, int K, int N, const bf16_t* bias,
-            int epi, void* out, int ldo, const float* resid, int ldr) {
+            int epi, void* out, int ldo, const float* resid, int ldr, const NormSrc& nsrc = NormSrc()) {
     if (T == 1) {
         dlk::GemvArgs g{A, B, K, bias, out, resid, N, K, epi};
+        with_norm(g, nsrc);
         dlk::gemv(g, st);
     } else {
         dlk::GemmArgs g{A, lda, B, K, bias, out, ldo, resid, ldr, T, N, K, epi};
@@ -260,10 +277,14 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     };
     double fl, by;
 
-    // attention sub-block
-    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
-    dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
-    kend();
+    // attention sub-block.  A single-token pass has no normalisation launches: the matrix-vector kernels of the
+    // QKV projection and of the feed-forward's first map normalise their input row themselves.
+    const bool fused_norm = T == 1;
+    if (!fused_norm) {
+        kbegin(DL_K_NORM, 0, Td * dm * 6.0);
+        dlk::norm_rows(d.norm, in, P(L.norm1_g), P(L.norm1_b), nbuf, false, T, dm, d.norm_eps, st);
+        kend();
+    }
     bf16_t* kc = nullptr;
     bf16_t* vt;
     uint64_t k_hs, v_hs;
@@ -288,7 +309,8 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     kbegin(DL_K_GEMM_QKV, fl, by);
     if (T == 1) {
         // single token: rotary embedding and the append to the K / V^T caches happen in the product's epilogue
-        dlk::GemvArgs g{nbuf, P(L.w_qkv), dm, P(L.b_qkv), qkv, nullptr, L.n_qkv, dm, dlk::EPI_QKV_POST, qp};
+        dlk::GemvArgs g{nullptr, P(L.w_qkv), dm, P(L.b_qkv), qkv, nullptr, L.n_qkv, dm, dlk::EPI_QKV_POST, qp};
+        with_norm(g, NormSrc{in, P(L.norm1_g), P(L.norm1_b), d.norm, d.norm_eps});
         dlk::gemv(g, st);
         kend();
     } else {
@@ -340,15 +362,20 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
     }
 
     // feed-forward sub-block
-    kbegin(DL_K_NORM, 0, Td * dm * 6.0);
-    dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
-    kend();
+    NormSrc n2;
+    if (fused_norm) {
+        n2 = NormSrc{out, P(L.norm2_g), P(L.norm2_b), d.norm, d.norm_eps};
+    } else {
+        kbegin(DL_K_NORM, 0, Td * dm * 6.0);
+        dlk::norm_rows(d.norm, out, P(L.norm2_g), P(L.norm2_b), nbuf, false, T, dm, d.norm_eps, st);
+        kend();
+    }
     lin_work(Td, L.n_up, dm, &fl, &by);
     kbegin(DL_K_GEMM_UP, fl, 2.0 * (Td * dm + double(L.n_up) * dm + Td * d.d_ff));
     if (d.act == DL_ACT_SWIGLU)
-        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, L.ffp, nullptr, 0);
+        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, nullptr, dlk::EPI_SWIGLU_BF16, mid, L.ffp, nullptr, 0, n2);
     else
-        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, L.ffp, nullptr, 0);
+        linear(st, T, nbuf, dm, P(L.w_up), dm, L.n_up, P(L.b_up), dlk::EPI_GELU_BF16, mid, L.ffp, nullptr, 0, n2);
     kend();
     lin_work(Td, dm, d.d_ff, &fl, &by);
     kbegin(DL_K_GEMM_DOWN, fl, by + 8.0 * Td * dm);
@@ -767,16 +794,17 @@ static int32_t head_common(dl_ctx* c, Module* M, const void* h) {
     if (!on_gpu(c)) return DL_OK;
     if (!h) return fail(c, DL_ERR_INVALID_ARG, "null hidden state");
     uint8_t* ws = c->base + M->ws_off;
-    bf16_t* nbuf = reinterpret_cast<bf16_t*>(ws + M->W.nbuf);
     float* logits = reinterpret_cast<float*>(ws + M->W.logits);
     int32_t* tok = reinterpret_cast<int32_t*>(ws + M->W.token);
     hipStream_t st = c->s_compute;
-    dlk::norm_rows(M->d.norm, static_cast<const float*>(h),
-                   reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_G]),
-                   M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr,
-                   nbuf, false, 1, M->d.d_model, M->d.norm_eps, st);
-    dlk::GemvArgs g{nbuf, reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_HEAD]), M->d.d_model, nullptr,
+    // the final normalisation happens inside the matrix-vector kernel
+    dlk::GemvArgs g{nullptr, reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_HEAD]), M->d.d_model, nullptr,
                     logits, nullptr, M->d.vocab, M->d.d_model, dlk::EPI_F32};
+    g.norm_x = static_cast<const float*>(h);
+    g.norm_g = reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_G]);
+    g.norm_b = M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr;
+    g.norm_kind = M->d.norm;
+    g.norm_eps = M->d.norm_eps;
     dlk::gemv(g, st);
     dlk::argmax_f32(logits, M->d.vocab, tok, st);
     DL_HIP(c, hipGetLastError());

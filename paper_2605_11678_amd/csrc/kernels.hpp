@@ -55,6 +55,13 @@ struct GemvArgs {
     // EPI_QKV_POST: `out` is the token's qkv row (= post.qkv, T = 1); q and k are rotated, k goes to the cache (or
     // stays in the row), v goes to the transposed cache, exactly as qkv_post would do after an EPI_BF16 product
     QkvPostArgs post;
+    // When norm_x != nullptr (epilogues QKV_POST, SWIGLU, GELU and F32 only) the input vector is not x but the
+    // normalisation of the fp32 row norm_x[K] (kind as in norm_rows), computed inside the kernel; x is ignored.
+    const float* norm_x;
+    const bf16_t* norm_g;
+    const bf16_t* norm_b;
+    int norm_kind;
+    float norm_eps;
 };
 void gemv(const GemvArgs& a, hipStream_t st);
 

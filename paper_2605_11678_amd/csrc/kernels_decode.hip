@@ -3,6 +3,7 @@
 // the row and multiplies them with the activation vector held in LDS, then the 64 partial sums are
 // folded with cross-lane shuffles.  Same epilogues as the GEMM.
 #include "kernels.hpp"
+#include "norm_device.hpp"
 
 namespace dlk {
 
@@ -47,9 +48,12 @@ __device__ __forceinline__ float wave_sum(float v) {
 // a "unit" is one output element; for SwiGLU it needs two weight rows (gate and up)
 // ROWS: rows a wavefront streams together (4: two SwiGLU units = 2 gate + 2 up rows, or four plain units; 2 for
 // matrices with so few rows that 4 would leave compute units without a workgroup)
-template <int EPI, int ROWS>
+// NORM: -1 the input vector is p.x (bf16); 0 / 1: it is RMSNorm / LayerNorm of the fp32 row p.norm_x, computed by
+// every workgroup for itself (the row and its gains sit in L2; this saves a launch per product)
+template <int EPI, int ROWS, int NORM>
 __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
     extern __shared__ __attribute__((aligned(16))) bf16_t sx[];
+    __shared__ float red[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nchunk = p.K >> 3;
 
@@ -97,10 +101,25 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemvArgs p) {
         }
     };
     u32x4 wA[ROWS][CU], wB[ROWS][CU];
-    if (piped) load_group(0, wA);
-
-    for (int c = tid; c < nchunk; c += 256)
-        reinterpret_cast<u32x4*>(sx)[c] = reinterpret_cast<const u32x4*>(p.x)[c];
+    if constexpr (NORM >= 0) {
+        // the row is requested first and the first weight group right behind it: memory returns loads in order, so
+        // the normalisation runs while the weights are still on their way
+        const float4* row = reinterpret_cast<const float4*>(p.norm_x);
+        normdev::RowPieces<NORM> rp;
+        rp.request(row, p.norm_g, p.norm_b, p.K >> 2);
+        if (piped) load_group(0, wA);
+        normdev::norm_row<NORM>(rp, row, p.norm_g, p.norm_b, p.K, p.norm_eps, red,
+                                [&](int i, float o0, float o1, float o2, float o3) {
+                                    uint2 pk;
+                                    pk.x = uint32_t(f_to_bf16(o0)) | (uint32_t(f_to_bf16(o1)) << 16);
+                                    pk.y = uint32_t(f_to_bf16(o2)) | (uint32_t(f_to_bf16(o3)) << 16);
+                                    reinterpret_cast<uint2*>(sx)[i] = pk;
+                                });
+    } else {
+        if (piped) load_group(0, wA);
+        for (int c = tid; c < nchunk; c += 256)
+            reinterpret_cast<u32x4*>(sx)[c] = reinterpret_cast<const u32x4*>(p.x)[c];
+    }
     __syncthreads();
 
     float acc[ROWS];
@@ -323,17 +342,29 @@ __global__ __launch_bounds__(512) void decode_attn_merge(DecodeAttnArgs p, float
 
 }  // namespace
 
-template <int EPI>
-void launch_gemv(const GemvArgs& a, int n_units, hipStream_t st) {
+template <int EPI, int NORM>
+void launch_gemv_n(const GemvArgs& a, int n_units, hipStream_t st) {
     const size_t lds = size_t(a.K) * 2;
     constexpr bool SW = EPI == EPI_SWIGLU_BF16 || EPI == EPI_QKV_POST;     // two rows per unit
     // 4 rows per wavefront unless that gives fewer than two workgroups per compute unit
     const int blocks4 = (n_units + (SW ? 8 : 16) - 1) / (SW ? 8 : 16);
     if (EPI == EPI_SWIGLU_BF16 || blocks4 >= 512) {
-        hipLaunchKernelGGL((gemv_kernel<EPI, 4>), dim3(blocks4), dim3(256), lds, st, a);
+        hipLaunchKernelGGL((gemv_kernel<EPI, 4, NORM>), dim3(blocks4), dim3(256), lds, st, a);
     } else {
-        hipLaunchKernelGGL((gemv_kernel<EPI, 2>), dim3((n_units + (SW ? 4 : 8) - 1) / (SW ? 4 : 8)), dim3(256), lds, st, a);
+        hipLaunchKernelGGL((gemv_kernel<EPI, 2, NORM>), dim3((n_units + (SW ? 4 : 8) - 1) / (SW ? 4 : 8)), dim3(256), lds,
+                           st, a);
     }
+}
+
+template <int EPI>
+void launch_gemv(const GemvArgs& a, int n_units, hipStream_t st) {
+    // the products that follow a normalisation: QKV, the feed-forward's first map, the output head
+    constexpr bool kAfterNorm = EPI == EPI_QKV_POST || EPI == EPI_SWIGLU_BF16 || EPI == EPI_GELU_BF16 || EPI == EPI_F32;
+    if constexpr (kAfterNorm) {
+        if (a.norm_x && a.norm_kind == 0) return launch_gemv_n<EPI, 0>(a, n_units, st);
+        if (a.norm_x) return launch_gemv_n<EPI, 1>(a, n_units, st);
+    }
+    launch_gemv_n<EPI, -1>(a, n_units, st);
 }
 
 void gemv(const GemvArgs& a, hipStream_t st) {

@@ -1,6 +1,7 @@
 // Row-wise kernels that move activations once through HBM: normalisation (wavefront reductions),
 // rotary embedding + KV scatter after the QKV projection, embedding lookup, greedy argmax.
 #include "kernels.hpp"
+#include "norm_device.hpp"
 
 namespace dlk {
 
@@ -12,22 +13,6 @@ __device__ __forceinline__ bf16_t f_to_bf16(float f) {
     return *reinterpret_cast<bf16_t*>(&b);
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-
-// sum over a 256-thread block; every thread gets the result
-__device__ __forceinline__ float block_sum_256(float v, float* red) {
-    v = wave_sum(v);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    __syncthreads();               // red may still be read from a previous call
-    if (lane == 0) red[wave] = v;
-    __syncthreads();
-    return red[0] + red[1] + red[2] + red[3];
-}
-
 // One 256-thread workgroup per row; rows are read as float4 (d % 4 == 0) and kept in registers between the
 // reduction and the scaling pass when they fit (d <= 4096), so a row is read from memory once.
 template <int KIND, bool OUT_F32>
@@ -36,58 +21,9 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
                                                    float eps) {
     __shared__ float red[4];
     const float4* row = reinterpret_cast<const float4*>(x + size_t(blockIdx.x) * d);
-    const int tid = threadIdx.x, nv = d >> 2;
-    constexpr int KEEP = 4;                       // float4 per thread held in registers
-    // the row pieces and their gains (and biases) are all requested before anything is used, with the index clamped
-    // instead of a predicate: one memory round trip for the whole workgroup's share of the row
-    float4 v[KEEP];
-    uint2 gk[KEEP], bk[KEEP];
-#pragma unroll
-    for (int j = 0; j < KEEP; ++j) {
-        const int i = tid + 256 * j, ic = i < nv ? i : 0;
-        v[j] = row[ic];
-        gk[j] = reinterpret_cast<const uint2*>(g)[ic];
-        if (KIND == 1) bk[j] = reinterpret_cast<const uint2*>(b)[ic];
-    }
-#pragma unroll
-    for (int j = 0; j < KEEP; ++j)
-        if (tid + 256 * j >= nv) v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
-    float mean = 0.0f;
-    if (KIND == 1) {
-        float s = 0.0f;
-#pragma unroll
-        for (int j = 0; j < KEEP; ++j) s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
-        for (int i = tid + 256 * KEEP; i < nv; i += 256) {
-            const float4 t = row[i];
-            s += (t.x + t.y) + (t.z + t.w);
-        }
-        mean = block_sum_256(s, red) / float(d);
-    }
-    float ss = 0.0f;
-#pragma unroll
-    for (int j = 0; j < KEEP; ++j) {
-        if (tid + 256 * j < nv) {
-            const float a0 = v[j].x - mean, a1 = v[j].y - mean, a2 = v[j].z - mean, a3 = v[j].w - mean;
-            ss += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
-        }
-    }
-    for (int i = tid + 256 * KEEP; i < nv; i += 256) {
-        const float4 t = row[i];
-        const float a0 = t.x - mean, a1 = t.y - mean, a2 = t.z - mean, a3 = t.w - mean;
-        ss += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
-    }
-    const float inv = rsqrtf(block_sum_256(ss, red) / float(d) + eps);
-    auto emit = [&](int i, const float4& t, const uint2& gg, const uint2& bb) {
-        float o0 = (t.x - mean) * inv * __uint_as_float(gg.x << 16);
-        float o1 = (t.y - mean) * inv * __uint_as_float(gg.x & 0xFFFF0000u);
-        float o2 = (t.z - mean) * inv * __uint_as_float(gg.y << 16);
-        float o3 = (t.w - mean) * inv * __uint_as_float(gg.y & 0xFFFF0000u);
-        if (KIND == 1) {
-            o0 += __uint_as_float(bb.x << 16);
-            o1 += __uint_as_float(bb.x & 0xFFFF0000u);
-            o2 += __uint_as_float(bb.y << 16);
-            o3 += __uint_as_float(bb.y & 0xFFFF0000u);
-        }
+    normdev::RowPieces<KIND> rp;
+    rp.request(row, g, b, d >> 2);
+    normdev::norm_row<KIND>(rp, row, g, b, d, eps, red, [&](int i, float o0, float o1, float o2, float o3) {
         if (OUT_F32) {
             reinterpret_cast<float4*>(static_cast<float*>(out) + size_t(blockIdx.x) * d)[i] = make_float4(o0, o1, o2, o3);
         } else {
@@ -96,15 +32,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
             pk.y = uint32_t(f_to_bf16(o2)) | (uint32_t(f_to_bf16(o3)) << 16);
             reinterpret_cast<uint2*>(static_cast<bf16_t*>(out) + size_t(blockIdx.x) * d)[i] = pk;
         }
-    };
-#pragma unroll
-    for (int j = 0; j < KEEP; ++j)
-        if (tid + 256 * j < nv) emit(tid + 256 * j, v[j], gk[j], bk[j]);
-    for (int i = tid + 256 * KEEP; i < nv; i += 256) {
-        uint2 bb = make_uint2(0u, 0u);
-        if (KIND == 1) bb = reinterpret_cast<const uint2*>(b)[i];
-        emit(i, row[i], reinterpret_cast<const uint2*>(g)[i], bb);
-    }
+    });
 }
 
 __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, uint64_t n) {
