@@ -18,6 +18,7 @@
 //    16 MFMAs; fragment reads, copies and MFMAs are interleaved through sched_group_barrier so that the
 //    vector-memory path sees an even one copy per four MFMAs, and one bare s_barrier per K step.
 //  * gemm_generic<EPI> — any shape (K % 8 == 0): 128x128 tile, 64x64 per wavefront, register-staged.
+//  * gemm_few_rows<EPI> — M <= 64: 64x32 output per workgroup, reduction split over its 8 wavefronts.
 //
 // Accumulator layout of a 32x32 tile: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.
 #include <type_traits>
@@ -156,6 +157,110 @@ __global__ __launch_bounds__(256) void gemm_generic(GemmArgs p) {
                     static_cast<float*>(p.out)[size_t(m) * p.ldo + n] = v;
                 }
             }
+    }
+}
+
+
+// ---- few rows (M <= 64): the work is tiny and the launch is bound by memory latency, so it is spread as widely as a
+// deterministic sum allows.  One 512-thread workgroup per 32 output columns; its 8 wavefronts take the 64-wide K chunks
+// round-robin and each computes the whole 64 x 32 tile over its chunks with operands loaded from global memory straight
+// into MFMA fragment layout (row addresses clamped to M - 1, never predicated), three chunks in flight per wavefront.
+// The 8 partial tiles meet in LDS and are summed in wavefront order, then every thread finishes 4 adjacent columns of
+// one row.  Needs K % 64 == 0, N % 32 == 0, 16-byte aligned rows.
+constexpr int SK_WAVES = 8, SK_DEPTH = 3;
+template <int EPI>
+__global__ __launch_bounds__(512) void gemm_few_rows(GemmArgs p) {
+    __shared__ __attribute__((aligned(16))) float part[SK_WAVES][64 * 32];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n0 = blockIdx.x * 32;
+    const int lr = lane & 31, lk = (lane >> 5) * 8;
+    const int n_chunks = p.K >> 6;
+    const int n_my = wave < n_chunks ? (n_chunks - wave + SK_WAVES - 1) / SK_WAVES : 0;
+    const bf16_t* arow[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int m = 32 * i + lr;
+        arow[i] = p.A + size_t(m < p.M ? m : p.M - 1) * p.lda + lk;
+    }
+    const bf16_t* brow = p.B + size_t(n0 + lr) * p.ldb + lk;
+
+    u32x4 fa[SK_DEPTH][2][4], fb[SK_DEPTH][4];
+    auto request = [&](int d, int idx) {
+        // chunks past the wavefront's last one repeat it (in bounds, never used)
+        const int ii = idx < n_my ? idx : (n_my > 0 ? n_my - 1 : 0);
+        const int k0 = (n_my > 0 ? wave + SK_WAVES * ii : 0) * 64;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[d][i][s] = *reinterpret_cast<const u32x4*>(arow[i] + k0 + 16 * s);
+            fb[d][s] = *reinterpret_cast<const u32x4*>(brow + k0 + 16 * s);
+        }
+    };
+    f32x16 acc[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+#pragma unroll
+    for (int d = 0; d < SK_DEPTH; ++d) request(d, d);
+    for (int base = 0; base < n_my; base += SK_DEPTH) {
+#pragma unroll
+        for (int d = 0; d < SK_DEPTH; ++d) {
+            if (base + d < n_my) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int i = 0; i < 2; ++i)
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&fa[d][i][s]),
+                                                                         *reinterpret_cast<bf16x8*>(&fb[d][s]), acc[i], 0, 0, 0);
+            }
+            request(d, base + d + SK_DEPTH);
+        }
+    }
+    // accumulator (tile i, lane, register r) -> row 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
+    const int row_in = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            part[wave][(32 * i + 8 * (r >> 2) + row_in + (r & 3)) * 32 + lr] = acc[i][r];
+    __syncthreads();
+    const int row = tid >> 3, c4 = (tid & 7) * 4;
+    float4 sum = *reinterpret_cast<const float4*>(&part[0][row * 32 + c4]);
+#pragma unroll
+    for (int w = 1; w < SK_WAVES; ++w) {
+        const float4 t = *reinterpret_cast<const float4*>(&part[w][row * 32 + c4]);
+        sum.x += t.x;
+        sum.y += t.y;
+        sum.z += t.z;
+        sum.w += t.w;
+    }
+    if (row >= p.M) return;
+    const int n = n0 + c4;
+    float v[4] = {sum.x, sum.y, sum.z, sum.w};
+    if (p.bias) {
+        const uint2 bb = *reinterpret_cast<const uint2*>(p.bias + n);
+        v[0] += __uint_as_float(bb.x << 16);
+        v[1] += __uint_as_float(bb.x & 0xFFFF0000u);
+        v[2] += __uint_as_float(bb.y << 16);
+        v[3] += __uint_as_float(bb.y & 0xFFFF0000u);
+    }
+    if (EPI == EPI_BF16 || EPI == EPI_GELU_BF16) {
+        if (EPI == EPI_GELU_BF16) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
+        }
+        uint2 pk;
+        pk.x = uint32_t(f_to_bf16(v[0])) | (uint32_t(f_to_bf16(v[1])) << 16);
+        pk.y = uint32_t(f_to_bf16(v[2])) | (uint32_t(f_to_bf16(v[3])) << 16);
+        *reinterpret_cast<uint2*>(static_cast<bf16_t*>(p.out) + size_t(row) * p.ldo + n) = pk;
+    } else {
+        float4 o = make_float4(v[0], v[1], v[2], v[3]);
+        if (EPI == EPI_RESID_F32) {
+            const float4 rs = *reinterpret_cast<const float4*>(p.resid + size_t(row) * p.ldr + n);
+            o = make_float4(rs.x + v[0], rs.y + v[1], rs.z + v[2], rs.w + v[3]);
+        }
+        *reinterpret_cast<float4*>(static_cast<float*>(p.out) + size_t(row) * p.ldo + n) = o;
     }
 }
 
@@ -626,6 +731,25 @@ void gemm(const GemmArgs& a, hipStream_t st) {
             case EPI_SWIGLU_BF16: dispatch_fast<EPI_SWIGLU_BF16>(a, st); return;
             case EPI_GELU_BF16: dispatch_fast<EPI_GELU_BF16>(a, st); return;
             default: break;
+        }
+    }
+    // few rows: latency-bound, spread over N / 32 workgroups with the reduction split over 8 wavefronts
+    const bool aligned_out = a.epi == EPI_BF16 || a.epi == EPI_GELU_BF16
+                                 ? (a.ldo % 4 == 0 && reinterpret_cast<uintptr_t>(a.out) % 8 == 0)
+                                 : (a.ldo % 4 == 0 && reinterpret_cast<uintptr_t>(a.out) % 16 == 0 &&
+                                    (a.epi != EPI_RESID_F32 ||
+                                     (a.ldr % 4 == 0 && reinterpret_cast<uintptr_t>(a.resid) % 16 == 0)));
+    const bool few_rows = a.M <= 64 && a.K >= 64 && a.K % 64 == 0 && a.N % 32 == 0 && a.lda % 8 == 0 && a.ldb % 8 == 0 &&
+                          a.epi != EPI_SWIGLU_BF16 && aligned_out &&
+                          (!a.bias || reinterpret_cast<uintptr_t>(a.bias) % 8 == 0) &&
+                          reinterpret_cast<uintptr_t>(a.A) % 16 == 0 && reinterpret_cast<uintptr_t>(a.B) % 16 == 0;
+    if (few_rows) {
+        dim3 grid(a.N / 32), block(512);
+        switch (a.epi) {
+            case EPI_BF16: hipLaunchKernelGGL(gemm_few_rows<EPI_BF16>, grid, block, 0, st, a); return;
+            case EPI_RESID_F32: hipLaunchKernelGGL(gemm_few_rows<EPI_RESID_F32>, grid, block, 0, st, a); return;
+            case EPI_GELU_BF16: hipLaunchKernelGGL(gemm_few_rows<EPI_GELU_BF16>, grid, block, 0, st, a); return;
+            default: hipLaunchKernelGGL(gemm_few_rows<EPI_F32>, grid, block, 0, st, a); return;
         }
     }
     const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
