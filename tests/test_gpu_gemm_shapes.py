@@ -1,8 +1,8 @@
 """GPU parity of the GEMM kernels over the tile shapes the dispatcher can pick, through the C-ABI's two-layer
 perceptron (dl_mlp_forward: y = GELU(x W1^T + b1) W2^T + b2, Sec. II-A stage 2).  The first product takes the
 fast MFMA path with the GELU epilogue in every tile shape (128x192, 192x192, 192x256, 256x192, 256x256, and 256x256
-with the last half round split into 128x256 halves) or the generic kernel; the second one (fp32 output) always
-takes the generic kernel.  Rows are independent, so the oracle evaluates a sample of rows that covers the first and
+with the last half round split into 128x256 halves), the generic kernel, or, with at most 64 rows and K a multiple
+of 64, the few-rows kernel; the second one (fp32 output) takes the generic or the few-rows kernel.  Rows are independent, so the oracle evaluates a sample of rows that covers the first and
 last row, tile borders and the ragged tail."""
 import numpy as np
 import pytest
@@ -18,6 +18,9 @@ TOL = 2e-2
 # (tokens, d_in, d_hidden, d_out, what the dispatcher picks for the first product)
 SHAPES = [
     (50, 200, 264, 40, "generic kernel: few rows, K not a multiple of 128"),
+    (64, 1024, 4096, 1024, "few-rows kernel: both products, every wavefront has chunks"),
+    (13, 256, 320, 96, "few-rows kernel: ragged rows, half of the wavefronts without a chunk"),
+    (33, 64, 64, 32, "few-rows kernel: a single K chunk"),
     (97, 256, 384, 64, "128x192, a single ragged row tile"),
     (300, 1152, 1152, 96, "128x192, narrow output, ragged last row tile"),
     (1000, 2304, 4096, 64, "192x192"),
