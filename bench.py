@@ -253,11 +253,35 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
                     [1, n_decode]),
           B.benefit(prof["action"]["c_dma_ms"], sizes[2] / MiB, [prof["action"]["c_exe_ms"]], [10])]
     st = ctx.arena_stats()
-    budget = st["capacity"] - st["used"] - (128 << 20)      # head-room for 256-byte rounding and first-fit holes
-    k_plan = B.plan(Ls, sizes, [list(b) for b in b3], budget)
-    # the same ranking when the budget also covers the slots and these are sized by the modules that still stream:
+    free_now = st["capacity"] - st["used"]                   # everything streamed: `used` includes 2 x the largest layer
+
+    def fits(ks):
+        try:
+            for m in range(3):
+                ctx.set_residency(mods[m], [])               # release first: the new plan may not fit next to the old one
+            for m in range(3):
+                ctx.set_residency(mods[m], B.place_interleaved(Ls[m], ks[m]))
+            return True
+        except B.DLError as e:
+            log("vla plan %s does not fit the arena: %s" % (ks, str(e)[:160]))
+            return False
+
+    # The planner's budget is what the arena really accepts: plan with little head-room for first-fit holes and
+    # keep the first plan whose residency sets the library takes (it rejects a set that does not fit as a whole).
+    def plan_that_fits(planner):
+        for headroom in (8 << 20, 32 << 20, 128 << 20, 512 << 20):
+            ks = planner(free_now - headroom)
+            if fits(ks):
+                break
+        return ks, headroom
+
+    # the ranking when the budget also covers the slots and these are sized by the modules that still stream:
     # a fully resident decoder shrinks the pair from 2 x 386 MB to the small stacks' layers
-    k_shared = B.plan_shared_slots(Ls, sizes, [list(b) for b in b3], budget + 2 * max(sizes))
+    k_shared, headroom = plan_that_fits(lambda bud: B.plan_shared_slots(Ls, sizes, [list(b) for b in b3], bud + 2 * max(sizes)))
+    budget = free_now - headroom
+    k_plan, headroom_fixed = plan_that_fits(lambda bud: B.plan(Ls, sizes, [list(b) for b in b3], bud))
+    log("vla head-room left in the arena: %d MiB (slots sized by the streaming modules), %d MiB (slots fixed)" %
+        (headroom >> 20, headroom_fixed >> 20))
     log("vla benefit (ms/MiB) first/mid/last: vit %s, decoder %s, action %s; budget %.2f GB -> k = %s (slots fixed at 2 x M_max), "
         "%s (slots sized by the streaming modules)" %
         (np.round(b3[0], 4).tolist(), np.round(b3[1], 4).tolist(), np.round(b3[2], 4).tolist(), budget / 1e9, k_plan, k_shared))
@@ -274,7 +298,7 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
         bb = b3_for(n_dec, n_eul)
         crossover.append({"n_decode": n_dec, "n_euler": n_eul, "b_mid_ms_per_MiB_vit_dec_act": [round(float(b[1]), 5) for b in bb],
                           "k_vit_dec_act": B.plan_shared_slots(Ls, sizes, [list(b) for b in bb], budget + 2 * max(sizes)),
-                          "k_with_slots_2x_largest_layer": B.plan(Ls, sizes, [list(b) for b in bb], budget)})
+                          "k_with_slots_2x_largest_layer": B.plan(Ls, sizes, [list(b) for b in bb], free_now - headroom_fixed)})
 
     # greedy head per token (resident, outside the layer passes)
     ctx.sync()
@@ -351,7 +375,7 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     res = {"workload": "configs[4]: ViT 27L T=4096 -> merger -> 8B decoder prefill 3072 + %d decode steps -> action head 8L x 10 Euler "
                        "steps on 64 tokens; cap %.3g B" % (n_decode, cap),
            "layer_bytes": sizes, "profile": prof, "benefit_ms_per_MiB": [np.round(b, 5).tolist() for b in b3],
-           "budget_gb": round(budget / 1e9, 3), "head_ms": round(head_ms, 4), "glue_ms": round(glue_ms, 4), "runs": rows,
+           "budget_gb": round(budget / 1e9, 3), "headroom_mib": headroom >> 20, "head_ms": round(head_ms, 4), "glue_ms": round(glue_ms, 4), "runs": rows,
            "benefit_vs_decode_length_and_euler_steps": crossover,
            "trajectory_finite": bool(np.all(np.isfinite(ref["trajectory"]))) if ref else None}
     eng.close()
