@@ -787,10 +787,13 @@ int32_t dl_final_norm(dl_ctx* c, int32_t module, const void* h, void* out, int32
     return DL_OK;
 }
 
-static int32_t head_common(dl_ctx* c, Module* M, const void* h) {
+// final norm + head + greedy choice; with x_next != nullptr the chosen token's embedding row is written there (and the
+// token to token_copy, if given) by the same launch that picks it
+static int32_t head_common(dl_ctx* c, Module* M, const void* h, int32_t* token_copy = nullptr, float* x_next = nullptr) {
     if (!M || !M->finalized) return fail(c, DL_ERR_BAD_STATE, "module missing or not finalized");
     if (M->d.vocab <= 0 || !M->rt_set[DL_R_HEAD] || !M->rt_set[DL_R_FINAL_NORM_G])
         return fail(c, DL_ERR_BAD_STATE, "head or final norm not set");
+    if (x_next && !M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
     if (!on_gpu(c)) return DL_OK;
     if (!h) return fail(c, DL_ERR_INVALID_ARG, "null hidden state");
     uint8_t* ws = c->base + M->ws_off;
@@ -806,7 +809,9 @@ static int32_t head_common(dl_ctx* c, Module* M, const void* h) {
     g.norm_kind = M->d.norm;
     g.norm_eps = M->d.norm_eps;
     dlk::gemv(g, st);
-    dlk::argmax_f32(logits, M->d.vocab, tok, st);
+    dlk::argmax_f32(logits, M->d.vocab, tok, token_copy,
+                    x_next ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_EMBED]) : nullptr, M->d.d_model, x_next,
+                    st);
     DL_HIP(c, hipGetLastError());
     return DL_OK;
 }
@@ -831,18 +836,9 @@ int32_t dl_greedy_step(dl_ctx* c, int32_t module, const void* h, int32_t* token_
     int32_t rc = enter(c);
     if (rc) return rc;
     Module* M = get_module(c, module);
-    rc = head_common(c, M, h);
-    if (rc) return rc;
-    if (!M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
-    if (!on_gpu(c)) return DL_OK;
-    if (!x_dev) return fail(c, DL_ERR_INVALID_ARG, "null x_dev");
-    uint8_t* ws = c->base + M->ws_off;
-    const int32_t* tok = reinterpret_cast<const int32_t*>(ws + M->W.token);
-    if (token_dev) DL_HIP(c, hipMemcpyAsync(token_dev, tok, 4, hipMemcpyDeviceToDevice, c->s_compute));
-    dlk::embed_row(reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_EMBED]), M->d.d_model, tok, 0,
-                   static_cast<float*>(x_dev), c->s_compute);
-    DL_HIP(c, hipGetLastError());
-    return DL_OK;
+    if (M && M->finalized && !M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
+    if (on_gpu(c) && !x_dev) return fail(c, DL_ERR_INVALID_ARG, "null x_dev");
+    return head_common(c, M, h, token_dev, static_cast<float*>(x_dev));
 }
 
 int32_t dl_mlp_create(dl_ctx* c, int32_t d_in, int32_t d_hidden, int32_t d_out, const void* w1, const void* b1,

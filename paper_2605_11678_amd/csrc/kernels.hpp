@@ -112,6 +112,9 @@ double mfma_rate_probe(float* out, int blocks, int iters, int pattern, hipStream
 
 // ---- head --------------------------------------------------------------------------------------------
 void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_host, float* x_out, hipStream_t st);
-void argmax_f32(const float* logits, int n, int32_t* token_dev, hipStream_t st);
+// token_dev (and token_copy, if not null) = index of the largest logit, lowest index on ties; if table != nullptr also
+// x_out[0..d) = row `token` of the bf16 table [*, d] as fp32 (the next step's input), in the same launch
+void argmax_f32(const float* logits, int n, int32_t* token_dev, int32_t* token_copy, const bf16_t* table, int d,
+                float* x_out, hipStream_t st);
 
 }  // namespace dlk

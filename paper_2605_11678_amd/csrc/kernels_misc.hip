@@ -207,30 +207,58 @@ __global__ __launch_bounds__(256) void embed_kernel(const bf16_t* __restrict__ t
         x_out[i] = bf16_to_f(table[size_t(tok) * d + i]);
 }
 
-__global__ __launch_bounds__(1024) void argmax_kernel(const float* __restrict__ v, int n, int32_t* __restrict__ out) {
-    __shared__ float sv[1024];
-    __shared__ int si[1024];
+// Greedy choice and the next input in one launch: index of the largest of v[0..n) (lowest index on ties) written to
+// out0 and, if given, out1; then, if a table is given, row `index` of the bf16 table [*, d] widened to fp32 into
+// x_out.  One 1024-thread workgroup; a thread's values are requested eight at a time with clamped indices before
+// any is compared.
+__device__ __forceinline__ void take_better(float& best, int& bi, float x, int i) {
+    if (x > best || (x == best && i < bi)) { best = x; bi = i; }
+}
+__global__ __launch_bounds__(1024) void argmax_embed_kernel(const float* __restrict__ v, int n, int32_t* __restrict__ out0,
+                                                            int32_t* __restrict__ out1, const bf16_t* __restrict__ table,
+                                                            int d, float* __restrict__ x_out) {
+    __shared__ float sv[16];
+    __shared__ int si[16];
+    __shared__ int s_tok;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float best = -INFINITY;
     int bi = 0x7FFFFFFF;
-    for (int i = threadIdx.x; i < n; i += 1024) {
-        const float x = v[i];
-        if (x > best || (x == best && i < bi)) { best = x; bi = i; }
-    }
-    sv[threadIdx.x] = best;
-    si[threadIdx.x] = bi;
-    __syncthreads();
-    for (int s = 512; s > 0; s >>= 1) {
-        if (threadIdx.x < s) {
-            const float o = sv[threadIdx.x + s];
-            const int oi = si[threadIdx.x + s];
-            if (o > sv[threadIdx.x] || (o == sv[threadIdx.x] && oi < si[threadIdx.x])) {
-                sv[threadIdx.x] = o;
-                si[threadIdx.x] = oi;
-            }
+    for (int base = 0; base < n; base += 8 * 1024) {
+        float x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = base + tid + 1024 * j;
+            x[j] = v[i < n ? i : n - 1];
         }
-        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = base + tid + 1024 * j;
+            if (i < n) take_better(best, bi, x[j], i);
+        }
     }
-    if (threadIdx.x == 0) *out = si[0] == 0x7FFFFFFF ? 0 : si[0];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ob = __shfl_xor(best, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        take_better(best, bi, ob, oi);
+    }
+    if (lane == 0) {
+        sv[wave] = best;
+        si[wave] = bi;
+    }
+    __syncthreads();
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < 16; ++w) take_better(best, bi, sv[w], si[w]);
+        const int tok = bi == 0x7FFFFFFF ? 0 : bi;
+        *out0 = tok;
+        if (out1) *out1 = tok;
+        s_tok = tok;
+    }
+    if (!table) return;
+    __syncthreads();
+    const bf16_t* row = table + size_t(s_tok) * d;
+    for (int i = tid; i < d; i += 1024) x_out[i] = bf16_to_f(row[i]);
 }
 
 }  // namespace
@@ -334,8 +362,10 @@ void embed_row(const bf16_t* table, int d, const int32_t* token_dev, int token_h
     hipLaunchKernelGGL(embed_kernel, dim3((d + 255) / 256), dim3(256), 0, st, table, d, token_dev, token_host, x_out);
 }
 
-void argmax_f32(const float* logits, int n, int32_t* token_dev, hipStream_t st) {
-    hipLaunchKernelGGL(argmax_kernel, dim3(1), dim3(1024), 0, st, logits, n, token_dev);
+void argmax_f32(const float* logits, int n, int32_t* token_dev, int32_t* token_copy, const bf16_t* table, int d,
+                float* x_out, hipStream_t st) {
+    if (n <= 0) return;
+    hipLaunchKernelGGL(argmax_embed_kernel, dim3(1), dim3(1024), 0, st, logits, n, token_dev, token_copy, table, d, x_out);
 }
 
 }  // namespace dlk
