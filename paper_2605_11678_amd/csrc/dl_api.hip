@@ -355,7 +355,8 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
                             uint64_t(dh) * M.W.vtc_ld, M.W.vtc_ld, -1, 0, dkv};
         dlk::qkv_post(cp, st);
         dlk::AttnArgs ca{qkv, dq, kvc, 2 * dkv, uint64_t(dh), vtc, M.W.vtc_ld, uint64_t(dh) * M.W.vtc_ld, attn, dq,
-                         T, n_ctx, 0, Hq, Hkv, dh, 0};
+                         T, n_ctx, 0, Hq, Hkv, dh, 0,
+                         M.W.att_part_bytes ? reinterpret_cast<float*>(ws + M.W.att_part) : nullptr, M.W.att_part_bytes};
         dlk::attention(ca, st);
         linear(st, T, attn, dq, P(L.w_oc), dq, dm, P(L.b_oc), dlk::EPI_RESID_F32, out, dm, out, dm);
         kend();

@@ -244,6 +244,13 @@ WorkspaceLayout make_workspace(const dl_module_desc& d) {
         put(&W.ctxn, 2 * C * uint64_t(d.d_ctx));
         put(&W.kvc, 2 * C * 2 * dkv);
         put(&W.vtc, 2 * dkv * uint64_t(W.vtc_ld));
+        // few queries attending to a long context: partial results of the key-range split, 16 runs x heads x
+        // queries x (padded head dim + 4) floats (the attention launcher's layout)
+        if (T <= 128) {
+            const uint64_t dhp = d.d_head <= 64 ? 64 : (d.d_head <= 96 ? 96 : 128);
+            W.att_part_bytes = 16ull * uint64_t(d.n_q_heads) * T * (dhp + 4) * 4;
+            put(&W.att_part, W.att_part_bytes);
+        }
     }
     if (d.vocab > 0) {
         put(&W.logits, 4 * uint64_t(d.vocab));

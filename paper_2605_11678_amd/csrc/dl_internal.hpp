@@ -58,7 +58,8 @@ void pack_tensor(const dl_module_desc& d, const PackLayout& L, int32_t tid, cons
 // ---- activation workspace / KV cache sizes of a module, in bytes ----
 struct WorkspaceLayout {
     uint64_t nbuf = 0, qkv = 0, attn = 0, mid = 0, vt = 0, ctxn = 0, kvc = 0, vtc = 0, logits = 0, token = 0,
-             dec_part = 0;  // offsets
+             dec_part = 0, att_part = 0;  // offsets
+    uint64_t att_part_bytes = 0;  // scratch of the split cross-attention (0: none)
     uint64_t bytes = 0;
     int32_t vt_ld = 0;      // row length (positions) of the transposed-V scratch
     int32_t vtc_ld = 0;     // same for the cross-attention V scratch

@@ -81,7 +81,13 @@ struct AttnArgs {
     const bf16_t* vt; int ldv; uint64_t v_head_stride;// kv head g, feature e, position j: vt + g*v_head_stride + e*ldv + j
     bf16_t* out; int ldo;                             // out + t*ldo + h*dh
     int T, S, q_pos0, Hq, Hkv, dh, causal;
+    // optional scratch for non-causal calls with at most 128 queries and at least 512 keys: the key range is then
+    // split over more workgroups and the pieces are merged by a second launch (fixed order).  nullptr: never split.
+    float* split_ws;
+    uint64_t split_ws_bytes;
 };
+// bytes of split_ws that let a call with T queries (T <= 128) split its key range
+uint64_t attention_split_workspace_bytes(int T, int Hq, int dh);
 void attention(const AttnArgs& a, hipStream_t st);
 
 // Single-query attention over a KV cache (decode), split over the key range: one wavefront per

@@ -33,8 +33,17 @@ namespace {
 
 constexpr int BKV = 64;
 
-template <int DHP, bool HEADS>
-__global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_log2) {
+__device__ __forceinline__ bf16_t f_to_bf16_attn(float f) {
+    __bf16 b = (__bf16)f;
+    return *reinterpret_cast<bf16_t*>(&b);
+}
+
+// SPLIT: the launch's z dimension divides the K/V tiles into runs of `tps` tiles; a workgroup handles one run and
+// writes, per query and head, its unnormalised output, reference maximum and sum to p.split_ws
+// ([run][head][query][DHP + 4] floats) for attn_merge_kernel.  Used for few queries over many keys (cross-attention
+// of a short sequence), where a launch would otherwise consist of a handful of workgroups walking the whole key range.
+template <int DHP, bool HEADS, bool SPLIT>
+__global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_log2, int tps) {
     constexpr int KLD = DHP + 8;     // sK row stride (elements)
     constexpr int VLD = BKV + 8;     // sV row stride
     constexpr int QB = HEADS ? 32 : 128;
@@ -86,7 +95,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     int kv_end = p.S;                                  // block-uniform: keys any query of the block may see
     if (p.causal) kv_end = min(p.S, p.q_pos0 + min(q0 + QB, p.T));
     const int wave_last = p.q_pos0 + min(wq0 + 31, p.T - 1);   // last query position of this wavefront
-    const int nt = (kv_end + BKV - 1) / BKV;
+    const int nt_all = (kv_end + BKV - 1) / BKV;
+    const int t_begin = SPLIT ? int(blockIdx.z) * tps : 0;
+    const int nt = SPLIT ? min(nt_all, t_begin + tps) : nt_all;      // tiles t_begin .. nt - 1
 
     // Loads are unconditional with clamped addresses (no branches, nothing waits on a load before the stash):
     //  * K rows past S repeat row S-1; those keys are masked to -inf (a tile that contains them is always masked);
@@ -121,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         }
     };
 
-    fetch(0);                                          // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
+    fetch(t_begin * BKV);                              // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
     bf16x8 qf[DHP / 16];
 #pragma unroll
     for (int kk = 0; kk < DHP / 16; ++kk) {
@@ -141,8 +152,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     }
     stash(0);
     __syncthreads();
-    for (int t = 0; t < nt; ++t) {
-        const int j0 = t * BKV, s = t & 1;
+    for (int t = t_begin; t < nt; ++t) {
+        const int j0 = t * BKV, s = (t - t_begin) & 1;
         if (t + 1 < nt) fetch(j0 + BKV);
         // a wavefront whose queries all lie before this tile has nothing to add (causal)
         const bool active = !p.causal || j0 <= wave_last;
@@ -261,6 +272,22 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (tq >= p.T) return;
+    if constexpr (SPLIT) {
+        float* prow = p.split_ws + ((size_t(blockIdx.z) * p.Hq + h) * p.T + tq) * (DHP + 4);
+#pragma unroll
+        for (int dt = 0; dt < DHP / 32; ++dt)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int e0 = 32 * dt + 8 * rg + 4 * g2;
+                *reinterpret_cast<float4*>(prow + e0) =
+                    make_float4(accO[dt][4 * rg], accO[dt][4 * rg + 1], accO[dt][4 * rg + 2], accO[dt][4 * rg + 3]);
+            }
+        if (g2 == 0) {
+            prow[DHP] = m_run * scale_log2;            // reference of this run's exponentials, base-2 units
+            prow[DHP + 1] = l_tot;
+        }
+        return;
+    }
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     bf16_t* orow = p.out + size_t(tq) * p.ldo + size_t(h) * p.dh;
 #pragma unroll
@@ -277,19 +304,56 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         }
 }
 
+// out[query, head] = sum_z w_z O_z / sum_z w_z l_z with w_z = 2^(m_z - max m), runs z taken in order
+template <int DHP>
+__global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs p, int n_runs) {
+    const int tq = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
+    const size_t run_stride = size_t(p.Hq) * p.T * (DHP + 4);
+    const float* base = p.split_ws + (size_t(h) * p.T + tq) * (DHP + 4);
+    const int ec = e < DHP ? e : DHP - 1;
+    float m = -INFINITY;
+    for (int z = 0; z < n_runs; ++z) m = fmaxf(m, base[z * run_stride + DHP]);
+    float num = 0.0f, den = 0.0f;
+    for (int z = 0; z < n_runs; ++z) {
+        const float* r = base + z * run_stride;
+        const float mz = r[DHP];
+        const float w = mz == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(mz - m);
+        num = fmaf(w, r[ec], num);
+        den = fmaf(w, r[DHP + 1], den);
+    }
+    if (e < p.dh) p.out[size_t(tq) * p.ldo + size_t(h) * p.dh + e] = f_to_bf16_attn(den > 0.0f ? num / den : 0.0f);
+}
+
 template <int DHP>
 void launch_attn(const AttnArgs& a, float scale_log2, hipStream_t st) {
     const int group = a.Hq / a.Hkv;
-    if (group % 4 == 0) {
-        dim3 grid(a.Hq / 4, (a.T + 31) / 32), block(256);
-        hipLaunchKernelGGL((attn_kernel<DHP, true>), grid, block, 0, st, a, scale_log2);
-    } else {
-        dim3 grid(a.Hq, (a.T + 127) / 128), block(256);
-        hipLaunchKernelGGL((attn_kernel<DHP, false>), grid, block, 0, st, a, scale_log2);
+    const bool heads = group % 4 == 0;
+    const dim3 grid = heads ? dim3(a.Hq / 4, (a.T + 31) / 32) : dim3(a.Hq, (a.T + 127) / 128);
+    // few queries over many keys: split the key range over the launch's z dimension
+    const int nt = (a.S + BKV - 1) / BKV;
+    if (a.split_ws && !a.causal && a.T <= 128 && nt >= 8) {
+        int n_runs = nt / 2 < 16 ? nt / 2 : 16;
+        const int tps = (nt + n_runs - 1) / n_runs;
+        n_runs = (nt + tps - 1) / tps;                       // every run has at least one tile
+        if (uint64_t(n_runs) * a.Hq * a.T * (DHP + 4) * 4 <= a.split_ws_bytes) {
+            const dim3 g3(grid.x, grid.y, n_runs);
+            if (heads) hipLaunchKernelGGL((attn_kernel<DHP, true, true>), g3, dim3(256), 0, st, a, scale_log2, tps);
+            else hipLaunchKernelGGL((attn_kernel<DHP, false, true>), g3, dim3(256), 0, st, a, scale_log2, tps);
+            hipLaunchKernelGGL(attn_merge_kernel<DHP>, dim3(a.T, a.Hq), dim3(128), 0, st, a, n_runs);
+            return;
+        }
     }
+    if (heads) hipLaunchKernelGGL((attn_kernel<DHP, true, false>), grid, dim3(256), 0, st, a, scale_log2, 0);
+    else hipLaunchKernelGGL((attn_kernel<DHP, false, false>), grid, dim3(256), 0, st, a, scale_log2, 0);
 }
 
 }  // namespace
+
+uint64_t attention_split_workspace_bytes(int T, int Hq, int dh) {
+    const int dhp = dh <= 64 ? 64 : (dh <= 96 ? 96 : 128);
+    const uint64_t t = T < 128 ? T : 128;
+    return 16ull * uint64_t(Hq) * t * uint64_t(dhp + 4) * 4;
+}
 
 void attention(const AttnArgs& a, hipStream_t st) {
     if (a.T <= 0 || a.S <= 0) return;

@@ -146,10 +146,14 @@ def test_gqa_decoder_prefill_chunks_and_decode(dh):
         g.close()
 
 
-def test_cross_attention_module():
-    c = CFG.ModuleConfig("cross_small", 2, 256, 2, 2, 128, 512, CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, d_ctx=384,
-                         seed_base=4300)
-    T, n_ctx = 64, 150
+@pytest.mark.parametrize("T,n_ctx,heads,dh", [(64, 150, 2, 128), (64, 700, 2, 128), (20, 1100, 4, 64), (128, 515, 3, 72)],
+                         ids=["short-context", "split-ragged-last-run", "split-gqa-wavefronts", "split-padded-head-dim"])
+def test_cross_attention_module(T, n_ctx, heads, dh):
+    """Cross-attention to a context.  From 512 context positions on (and at most 128 queries) the key range is split
+    over several workgroups and merged by a second launch; the cases cover a ragged last run (700 = 10 tiles + 60
+    positions), four query heads per KV head (the wavefronts of a workgroup are heads) and a padded head dimension."""
+    c = CFG.ModuleConfig("cross_small", 2, 256, heads, 1 if heads == 4 else heads, dh, 512,
+                         CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, d_ctx=384, seed_base=4300)
     x = CFG.make_tokens(T, c.d_model, seed=31)
     ctx = CFG.make_tokens(n_ctx, c.d_ctx, seed=32)
     g = GpuStack(c, max_tokens=T, max_ctx=n_ctx)
