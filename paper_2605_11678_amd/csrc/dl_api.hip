@@ -348,7 +348,9 @@ void run_layer(dl_ctx* c, Module& M, int32_t layer, const uint8_t* w, const floa
                2.0 * (2.0 * double(dq) * dm + 2.0 * double(dkv) * d.d_ctx));
         dlk::norm_rows(d.norm, out, P(L.normc_g), P(L.normc_b), nbuf, false, T, dm, d.norm_eps, st);
         linear(st, T, nbuf, dm, P(L.w_qc), dm, dq, P(L.b_qc), dlk::EPI_BF16, qkv, dq, nullptr, 0);
-        dlk::cast_f32_bf16(ctx, ctxn, uint64_t(n_ctx) * d.d_ctx, st);
+        // the context is the same for every layer of a pass: layer 0 converts it to bf16 for all of them (a pass
+        // always starts at layer 0, and nothing else writes this buffer)
+        if (layer == 0) dlk::cast_f32_bf16(ctx, ctxn, uint64_t(n_ctx) * d.d_ctx, st);
         linear(st, n_ctx, ctxn, d.d_ctx, P(L.w_kvc), d.d_ctx, 2 * dkv, P(L.b_kvc), dlk::EPI_BF16, kvc, 2 * dkv,
                nullptr, 0);
         dlk::QkvPostArgs cp{kvc, 2 * dkv, n_ctx, 0, Hq, Hkv, dh, 0.0f, nullptr, 0, vtc,

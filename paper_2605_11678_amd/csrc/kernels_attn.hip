@@ -304,22 +304,32 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         }
 }
 
-// out[query, head] = sum_z w_z O_z / sum_z w_z l_z with w_z = 2^(m_z - max m), runs z taken in order
+// out[query, head] = sum_z w_z O_z / sum_z w_z l_z with w_z = 2^(m_z - max m), runs z taken in order.  At most 16
+// runs; every run's values are requested before the first is used (index clamped to the last run, weight zero).
 template <int DHP>
 __global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs p, int n_runs) {
+    constexpr int MAXR = 16;
     const int tq = blockIdx.x, h = blockIdx.y, e = threadIdx.x;
     const size_t run_stride = size_t(p.Hq) * p.T * (DHP + 4);
     const float* base = p.split_ws + (size_t(h) * p.T + tq) * (DHP + 4);
     const int ec = e < DHP ? e : DHP - 1;
+    float mz[MAXR], lz[MAXR], oz[MAXR];
+#pragma unroll
+    for (int z = 0; z < MAXR; ++z) {
+        const float* r = base + size_t(z < n_runs ? z : n_runs - 1) * run_stride;
+        mz[z] = r[DHP];
+        lz[z] = r[DHP + 1];
+        oz[z] = r[ec];
+    }
     float m = -INFINITY;
-    for (int z = 0; z < n_runs; ++z) m = fmaxf(m, base[z * run_stride + DHP]);
+#pragma unroll
+    for (int z = 0; z < MAXR; ++z) m = fmaxf(m, mz[z]);
     float num = 0.0f, den = 0.0f;
-    for (int z = 0; z < n_runs; ++z) {
-        const float* r = base + z * run_stride;
-        const float mz = r[DHP];
-        const float w = mz == -INFINITY ? 0.0f : __builtin_amdgcn_exp2f(mz - m);
-        num = fmaf(w, r[ec], num);
-        den = fmaf(w, r[DHP + 1], den);
+#pragma unroll
+    for (int z = 0; z < MAXR; ++z) {
+        const float w = (z < n_runs && mz[z] != -INFINITY) ? __builtin_amdgcn_exp2f(mz[z] - m) : 0.0f;
+        num = fmaf(w, oz[z], num);
+        den = fmaf(w, lz[z], den);
     }
     if (e < p.dh) p.out[size_t(tq) * p.ldo + size_t(h) * p.dh + e] = f_to_bf16_attn(den > 0.0f ? num / den : 0.0f);
 }

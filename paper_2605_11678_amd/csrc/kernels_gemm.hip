@@ -163,38 +163,48 @@ __global__ __launch_bounds__(256) void gemm_generic(GemmArgs p) {
 
 // ---- few rows (M <= 64): the work is tiny and the launch is bound by memory latency, so it is spread as widely as a
 // deterministic sum allows.  One 512-thread workgroup per 32 output columns; its 8 wavefronts take the 64-wide K chunks
-// round-robin and each computes the whole 64 x 32 tile over its chunks with operands loaded from global memory straight
-// into MFMA fragment layout (row addresses clamped to M - 1, never predicated), three chunks in flight per wavefront.
+// round-robin and each computes the whole 64 x 32 tile over its chunks.  A wavefront fetches a chunk (64 + 32 rows of
+// 128 bytes) with 8 lanes per row, so a load instruction touches 8 cache lines (fragment-shaped loads touch 32 and
+// were bound by the L1's tag rate: 15 us for K = 1024), parks it in its own piece of LDS and reads MFMA fragments
+// back from there; two chunks are in flight per wavefront, row addresses are clamped to M - 1, nothing is predicated.
 // The 8 partial tiles meet in LDS and are summed in wavefront order, then every thread finishes 4 adjacent columns of
 // one row.  Needs K % 64 == 0, N % 32 == 0, 16-byte aligned rows.
-constexpr int SK_WAVES = 8, SK_DEPTH = 3;
+constexpr int SK_WAVES = 8, SK_DEPTH = 2;
+constexpr int SK_LD = 72;                            // staged row stride (elements): 144 bytes staggers the banks
+constexpr int SK_STAGE = (64 + 32) * SK_LD;          // elements per wavefront
 template <int EPI>
 __global__ __launch_bounds__(512) void gemm_few_rows(GemmArgs p) {
-    __shared__ __attribute__((aligned(16))) float part[SK_WAVES][64 * 32];
+    // the staging area of the main loop and the partial tiles of the reduction share the same memory
+    __shared__ __attribute__((aligned(16))) char smem[SK_WAVES * SK_STAGE * 2];
+    static_assert(SK_WAVES * SK_STAGE * 2 >= SK_WAVES * 64 * 32 * 4, "partial tiles must fit the staging area");
+    bf16_t* stage = reinterpret_cast<bf16_t*>(smem) + (threadIdx.x >> 6) * SK_STAGE;
+    float (*part)[64 * 32] = reinterpret_cast<float (*)[64 * 32]>(smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n0 = blockIdx.x * 32;
-    const int lr = lane & 31, lk = (lane >> 5) * 8;
+    const int lr = lane & 31, g2 = lane >> 5;
     const int n_chunks = p.K >> 6;
     const int n_my = wave < n_chunks ? (n_chunks - wave + SK_WAVES - 1) / SK_WAVES : 0;
-    const bf16_t* arow[2];
+    // fetch mapping: load j covers rows 8 j .. 8 j + 7, lane l row 8 j + l / 8, bytes 16 (l % 8) of the chunk
+    const int frow = lane >> 3, fcol = (lane & 7) * 8;
+    const bf16_t* asrc[8];
+    const bf16_t* bsrc[4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int m = 32 * i + lr;
-        arow[i] = p.A + size_t(m < p.M ? m : p.M - 1) * p.lda + lk;
+    for (int j = 0; j < 8; ++j) {
+        const int m = 8 * j + frow;
+        asrc[j] = p.A + size_t(m < p.M ? m : p.M - 1) * p.lda + fcol;
     }
-    const bf16_t* brow = p.B + size_t(n0 + lr) * p.ldb + lk;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bsrc[j] = p.B + size_t(n0 + 8 * j + frow) * p.ldb + fcol;
 
-    u32x4 fa[SK_DEPTH][2][4], fb[SK_DEPTH][4];
+    u32x4 ra[SK_DEPTH][8], rb[SK_DEPTH][4];
     auto request = [&](int d, int idx) {
         // chunks past the wavefront's last one repeat it (in bounds, never used)
         const int ii = idx < n_my ? idx : (n_my > 0 ? n_my - 1 : 0);
         const int k0 = (n_my > 0 ? wave + SK_WAVES * ii : 0) * 64;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
+        for (int j = 0; j < 8; ++j) ra[d][j] = *reinterpret_cast<const u32x4*>(asrc[j] + k0);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) fa[d][i][s] = *reinterpret_cast<const u32x4*>(arow[i] + k0 + 16 * s);
-            fb[d][s] = *reinterpret_cast<const u32x4*>(brow + k0 + 16 * s);
-        }
+        for (int j = 0; j < 4; ++j) rb[d][j] = *reinterpret_cast<const u32x4*>(bsrc[j] + k0);
     };
     f32x16 acc[2];
 #pragma unroll
@@ -207,16 +217,33 @@ __global__ __launch_bounds__(512) void gemm_few_rows(GemmArgs p) {
 #pragma unroll
         for (int d = 0; d < SK_DEPTH; ++d) {
             if (base + d < n_my) {
+                // LDS operations of one wavefront execute in order: the fragment reads of the previous chunk are
+                // done before these writes land, and the reads below see them
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
+                for (int j = 0; j < 8; ++j)
+                    *reinterpret_cast<u32x4*>(stage + (8 * j + frow) * SK_LD + fcol) = ra[d][j];
 #pragma unroll
-                    for (int i = 0; i < 2; ++i)
-                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&fa[d][i][s]),
-                                                                         *reinterpret_cast<bf16x8*>(&fb[d][s]), acc[i], 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<u32x4*>(stage + (64 + 8 * j + frow) * SK_LD + fcol) = rb[d][j];
             }
             request(d, base + d + SK_DEPTH);
+            if (base + d < n_my) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    // read with the type the chunk was written with (the same accesses, as far as the compiler's
+                    // alias rules go), reinterpret in registers
+                    u32x4 fb = *reinterpret_cast<const u32x4*>(stage + (64 + lr) * SK_LD + 16 * s + 8 * g2);
+#pragma unroll
+                    for (int i = 0; i < 2; ++i) {
+                        u32x4 fa = *reinterpret_cast<const u32x4*>(stage + (32 * i + lr) * SK_LD + 16 * s + 8 * g2);
+                        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<bf16x8*>(&fa),
+                                                                         *reinterpret_cast<bf16x8*>(&fb), acc[i], 0, 0, 0);
+                    }
+                }
+            }
         }
     }
+    __syncthreads();                                  // everybody is done with the staging area
     // accumulator (tile i, lane, register r) -> row 32 i + 8 (r / 4) + 4 (lane / 32) + r % 4, column lane % 32
     const int row_in = (lane >> 5) * 4;
 #pragma unroll
