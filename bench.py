@@ -64,12 +64,22 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
     head_ms = (time.perf_counter() - t) * 1e3 / 50
     res["head_ms"] = round(head_ms, 4)
 
-    def run(resident, steps, wrap):
-        ctx.set_residency(mid, resident)
+    def run(resident, steps, wrap, shrink=False):
         ctx.set_mode(B.DL_MODE_PIPELINED, wrap)
-        ctx.forward(mid, xp, yp, T, 0)                       # refresh the KV cache (untimed)
         h_ptr = yp + 4 * (T - 1) * d
-        ctx.greedy_step(mid, h_ptr, tp, xp + 4 * d)          # next input lives behind row 0 so that xp's prefill rows stay intact
+        if shrink:
+            # the prefill streams everything under the long workspace; the single-token passes that follow need a
+            # workspace for one token, and the difference goes to resident layers
+            ctx.set_residency(mid, [])
+            ctx.forward(mid, xp, yp, T, 0)
+            ctx.greedy_step(mid, h_ptr, tp, xp + 4 * d)
+            ctx.sync()
+            ctx.module_set_max_tokens(mid, 1)
+            ctx.set_residency(mid, resident)
+        else:
+            ctx.set_residency(mid, resident)
+            ctx.forward(mid, xp, yp, T, 0)                   # refresh the KV cache (untimed)
+            ctx.greedy_step(mid, h_ptr, tp, xp + 4 * d)      # next input lives behind row 0 so that xp's prefill rows stay intact
         ctx.forward(mid, xp + 4 * d, yp, 1, T)               # one untimed step: first-use effects stay out of the figure
         ctx.sync()
         torch.cuda.synchronize()
@@ -112,9 +122,9 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
         ballast = ctx.arena_alloc(ballast_bytes) if ballast_bytes else None
         try:
             kfit = fit_count()
-            policies = [("none", [], 2), ("interleaved_eq8", B.place_interleaved(L, kfit), 2)]
+            policies = [("none", [], 2, False), ("interleaved_eq8", B.place_interleaved(L, kfit), 2, False)]
             if 0 < kfit < L:
-                policies.append(("first_k_consecutive", list(range(kfit)), 2))
+                policies.append(("first_k_consecutive", list(range(kfit)), 2, False))
                 # a copy takes ~60 x longer than a single-token layer executes: the overlap a second slot buys is worth
                 # less than the resident layer its memory holds
                 ctx.set_residency(mid, [])
@@ -122,20 +132,35 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
                 kfit1 = fit_count()
                 ctx.set_residency(mid, [])
                 ctx.set_slot_count(2)
-                policies.append(("interleaved_eq8_one_slot", B.place_interleaved(L, kfit1), 1))
-            for name, resident, n_slots in policies:
+                policies.append(("interleaved_eq8_one_slot", B.place_interleaved(L, kfit1), 1, False))
+                # ... and with the activation workspace shrunk from the prefill's T tokens to one token
+                ctx.set_slot_count(1)
+                ctx.module_set_max_tokens(mid, 1)
+                kfit1s = fit_count()
+                ctx.set_residency(mid, [])
+                ctx.module_set_max_tokens(mid, T)
+                ctx.set_slot_count(2)
+                if kfit1s > kfit1:
+                    policies.append(("interleaved_eq8_one_slot_decode_workspace", B.place_interleaved(L, kfit1s), 1, True))
+            for name, resident, n_slots, shrink in policies:
                 streamed_n = L - len(resident)
                 steps = 64 if streamed_n * float(np.mean(c_dma)) < 40 else 6
                 ctx.set_residency(mid, [])
                 ctx.set_slot_count(n_slots)
                 for wrap in ((0, 1) if streamed_n else (0,)):
-                    ms, st = run(resident, steps, wrap)
+                    try:
+                        ms, st = run(resident, steps, wrap, shrink)
+                        arena_used = ctx.arena_stats()["used"]
+                    finally:
+                        if shrink:
+                            ctx.set_residency(mid, [])
+                            ctx.module_set_max_tokens(mid, T)
                     pred = predict(resident, steps, wrap, n_slots)
                     row = {"cap": cap_name, "policy": name, "k": len(resident), "slots": n_slots, "wrap_prefetch": wrap, "steps": steps,
                            "ms_per_token": round(ms, 3), "predicted_ms_per_token": round(pred, 3),
                            "pred_err_pct": round((pred - ms) / ms * 100, 2), "hidden_frac": round(st["hidden_frac"], 4),
                            "h2d_gbps": round(st["h2d_gbps"], 2),
-                           "arena_gb": round(ctx.arena_stats()["used"] / 1e9 - ballast_bytes / 1e9, 3)}
+                           "arena_gb": round(arena_used / 1e9 - ballast_bytes / 1e9, 3)}
                     if not streamed_n:
                         row["weight_stream_gbps"] = round(L * packed / (ms * 1e-3) / 1e9, 1)   # HBM-bound resident pass
                     res["runs"].append(row)
@@ -143,6 +168,7 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
                         (cap_name, name, len(resident), wrap, ms, pred, row["pred_err_pct"], st["hidden_frac"]))
         finally:
             ctx.set_residency(mid, [])
+            ctx.module_set_max_tokens(mid, T)
             ctx.set_slot_count(2)
             if ballast:
                 ctx.arena_free(ballast)

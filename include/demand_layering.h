@@ -149,6 +149,16 @@ int32_t dl_set_mode(dl_ctx* ctx, int32_t mode, int32_t wrap_prefetch);
  * DL_ERR_BUDGET_EXCEEDED: nothing changed. */
 int32_t dl_set_slot_count(dl_ctx* ctx, int32_t n_slots);
 
+/* Re-sizes the activation workspace of a finalized module for passes of at most max_tokens tokens (>= 1).  The
+ * workspace is sized by the longest pass (Sec. IV-D counts activations against the same memory as the parameters):
+ * after a long prefill, shrinking it to the single-token passes that follow gives that memory to resident layers
+ * (8B-class decoder, 3072 -> 1 tokens: 164 MB, which under a 12e9-byte cap is the difference between 26 and 27
+ * resident layers).  Synchronises both streams.  Keeps the KV cache, the residency set, the resident tensors and
+ * the packed weights; discards the workspace's contents (intermediate activations, the logits and token of the
+ * last greedy step).  Afterwards dl_forward / dl_profile accept n_tokens <= max_tokens.
+ * DL_ERR_BUDGET_EXCEEDED (growing): nothing changed. */
+int32_t dl_module_set_max_tokens(dl_ctx* ctx, int32_t module, int32_t max_tokens);
+
 /* How many streaming passes (passes that copy at least one layer) may be unfinished when the next one is
  * enqueued (1..8; 0 = no limit).  Default 1: each further pass of short streamed layers in flight slowed copies and
  * kernels on MI355X (+4 % with two, +25 % with four).  Passes of resident layers only are never held back. */

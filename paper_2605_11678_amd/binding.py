@@ -111,6 +111,7 @@ SIGNATURES = {
     "dl_timeline": (_i32, [_PF64, _PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
                            _i32, _f64, _PF64, _PF64, _PF64]),
     "dl_set_slot_count": (_i32, [_p, _i32]),
+    "dl_module_set_max_tokens": (_i32, [_p, _i32, _i32]),
     "dl_plan": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _PI32]),
     "dl_plan_shared_slots": (_i32, [_i32, _PI32, _PU64, _PF64, _u64, _i32, _PI32]),
 }
@@ -315,6 +316,10 @@ class Context:
     def set_slot_count(self, n_slots):
         """1 or 2 device slots for the streamed layers (re-sizes them)."""
         self._ck(lib().dl_set_slot_count(self._h, int(n_slots)))
+
+    def module_set_max_tokens(self, module, max_tokens):
+        """Re-size a module's activation workspace for passes of at most max_tokens tokens (contents discarded)."""
+        self._ck(lib().dl_module_set_max_tokens(self._h, int(module), int(max_tokens)))
 
     def probe_mfma_rate(self, pattern=1, iters=20000):
         """Register-only BF16 MFMA rate of the device in TFLOP/s (diagnostic)."""

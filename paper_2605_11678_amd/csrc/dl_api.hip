@@ -677,7 +677,7 @@ int32_t dl_module_finalize(dl_ctx* c, int32_t module) {
     if (rc) return rc;
     // workspace and KV cache first, then the slots; undo on failure
     uint64_t ws = 0, kv = 0;
-    if (!c->arena.alloc(M->W.bytes, &ws)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the activation workspace");
+    if (!c->arena.alloc_top(M->W.bytes, &ws)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the activation workspace");
     if (M->KV.bytes && !c->arena.alloc(M->KV.bytes, &kv)) {
         c->arena.free(ws);
         return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the KV cache");
@@ -1191,6 +1191,38 @@ int32_t dl_set_slot_count(dl_ctx* c, int32_t n_slots) {
     }
     c->book = dl::SlotBook();
     c->book.n_slots = c->n_slots;
+    return DL_OK;
+}
+
+int32_t dl_module_set_max_tokens(dl_ctx* c, int32_t module, int32_t max_tokens) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    Module* M = get_module(c, module);
+    if (!M || !M->finalized) return fail(c, DL_ERR_BAD_STATE, "module missing or not finalized");
+    if (max_tokens < 1) return fail(c, DL_ERR_INVALID_ARG, "max_tokens < 1");
+    if (M->d.max_seq > 0 && max_tokens > M->d.max_seq) return fail(c, DL_ERR_INVALID_ARG, "max_tokens exceeds max_seq");
+    if (max_tokens == M->d.max_tokens) return DL_OK;
+    rc = sync_streams(c);
+    if (rc) return rc;
+    dl_module_desc d2 = M->d;
+    d2.max_tokens = max_tokens;
+    const dl::WorkspaceLayout W2 = dl::make_workspace(d2);
+    // on a copy of the allocator: release the old block, place the new one, commit only if that worked
+    dl::Arena A = c->arena;
+    A.free(M->ws_off);
+    uint64_t off = 0;
+    if (!A.alloc_top(W2.bytes, &off)) {
+        char buf[160];
+        snprintf(buf, sizeof buf, "arena cannot hold a workspace for %d tokens (%llu bytes, %llu of %llu used)", max_tokens,
+                 (unsigned long long)W2.bytes, (unsigned long long)c->arena.used(), (unsigned long long)c->arena.capacity());
+        return fail(c, DL_ERR_BUDGET_EXCEEDED, buf);
+    }
+    c->arena = A;
+    M->ws_off = off;
+    M->W = W2;
+    M->d = d2;
+    // stale bytes in the transposed-V areas must be finite numbers
+    if (on_gpu(c)) DL_HIP(c, hipMemset(c->base + off, 0, W2.bytes));
     return DL_OK;
 }
 

@@ -41,6 +41,27 @@ bool Arena::alloc(uint64_t bytes, uint64_t* off_out) {
     return false;
 }
 
+bool Arena::alloc_top(uint64_t bytes, uint64_t* off_out) {
+    const uint64_t need = align_up(bytes ? bytes : 1);
+    for (size_t i = blocks_.size(); i-- > 0;) {
+        Block& b = blocks_[i];
+        if (b.used || b.size < need) continue;
+        if (b.size > need) {
+            const Block top{b.off + b.size - need, need, true};
+            b.size -= need;
+            *off_out = top.off;
+            blocks_.insert(blocks_.begin() + i + 1, top);
+        } else {
+            b.used = true;
+            *off_out = b.off;
+        }
+        used_ += need;
+        peak_ = std::max(peak_, used_);
+        return true;
+    }
+    return false;
+}
+
 bool Arena::free(uint64_t off) {
     for (size_t i = 0; i < blocks_.size(); ++i) {
         if (blocks_[i].off != off || !blocks_[i].used) continue;

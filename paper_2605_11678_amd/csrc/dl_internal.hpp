@@ -18,6 +18,10 @@ public:
     void reset(uint64_t capacity);
     // returns false if no free range of that size exists
     bool alloc(uint64_t bytes, uint64_t* off_out);
+    // same, but takes the END of the HIGHEST free range that is large enough.  For blocks that get re-sized later
+    // (activation workspaces): kept at the top, what they give back joins the free range below them instead of
+    // leaving a hole between longer-lived blocks.
+    bool alloc_top(uint64_t bytes, uint64_t* off_out);
     bool free(uint64_t off);
     uint64_t used() const { return used_; }
     uint64_t peak() const { return peak_; }

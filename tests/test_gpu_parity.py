@@ -91,6 +91,25 @@ def test_tiny_decoder_greedy_ids_identical():
             g.eng.ctx.forward(g.mid, g.xp, g.yp, 1, T + s)
             h_ptr = g.yp
         assert g.eng.download(tv).view(np.int32).tolist() == toks
+        # the workspace shrunk to single-token passes between the prefill and the decode steps: the KV cache
+        # survives, the ids are the same, and the freed bytes are there for one more resident layer
+        g.eng.ctx.set_residency(g.mid, [])
+        g.eng.upload(g.xv[:T * c.d_model], x)
+        g.eng.ctx.forward(g.mid, g.xp, g.yp, T, 0)
+        h_ptr = g.yp + 4 * (T - 1) * c.d_model
+        g.eng.ctx.sync()
+        used_long = g.eng.ctx.arena_stats()["used"]
+        g.eng.ctx.module_set_max_tokens(g.mid, 1)
+        assert g.eng.ctx.arena_stats()["used"] < used_long
+        g.eng.ctx.set_residency(g.mid, [1, 3])
+        g.eng.upload(tv, np.zeros(steps, np.float32))
+        for s in range(steps):
+            g.eng.ctx.greedy_step(g.mid, h_ptr, tp + 4 * s, g.xp)
+            g.eng.ctx.forward(g.mid, g.xp, g.yp, 1, T + s)
+            h_ptr = g.yp
+        assert g.eng.download(tv).view(np.int32).tolist() == toks
+        with pytest.raises(B.DLError):
+            g.eng.ctx.forward(g.mid, g.xp, g.yp, 2, 0)
     finally:
         g.close()
 

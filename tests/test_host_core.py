@@ -272,6 +272,50 @@ def test_budget_two_slots_plus_one_resident_layer():
     eng.close()
 
 
+def test_shrinking_the_workspace_makes_room_for_a_resident_layer():
+    """Sec. IV-D: activations and parameters share one memory.  A workspace sized for the prefill, shrunk to the
+    single-token passes that follow, frees what one more resident layer needs; growing it back is refused while
+    that layer is resident, and the refusal changes nothing."""
+    c = small_cfg(4, d_ff=1024, max_seq=640)
+    probe, mid = _host_engine_with_module(c, cap=1 << 30, max_tokens=512)
+    packed, _ = probe.ctx.module_layer_bytes(mid)
+    base_long = probe.ctx.arena_stats()["used"]     # workspace for 512 tokens + KV cache + two slots
+    probe.ctx.module_set_max_tokens(mid, 1)
+    base_short = probe.ctx.arena_stats()["used"]
+    probe.close()
+    freed = base_long - base_short
+    assert freed > packed                           # the long workspace is worth more than a layer here
+    # room for ONE resident layer next to the long workspace
+    eng, mid = _host_engine_with_module(c, cap=base_long + packed + 256, max_tokens=512)
+    eng.ctx.forward(mid, 0, 0, 512, 0)              # a long pass is accepted ...
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.set_residency(mid, [0, 2])
+    assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED
+    eng.ctx.module_set_max_tokens(mid, 1)
+    assert eng.ctx.arena_stats()["used"] == base_short
+    eng.ctx.set_residency(mid, [0, 2])              # ... and after the shrink a second layer fits
+    used2 = eng.ctx.arena_stats()["used"]
+    assert used2 == base_short + 2 * packed
+    eng.ctx.forward(mid, 0, 0, 1, 512)
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.forward(mid, 0, 0, 2, 0)            # longer passes are refused now
+    assert e.value.code == B.DL_ERR_INVALID_ARG
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.module_set_max_tokens(mid, 512)     # no room to grow back while two layers are resident
+    assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED
+    assert eng.ctx.arena_stats()["used"] == used2 and eng.ctx.get_residency(mid, 4) == [0, 2]
+    eng.ctx.forward(mid, 0, 0, 1, 513)              # still works as before the refused call
+    eng.ctx.set_residency(mid, [])                  # release first: the grown block then finds one free range
+    eng.ctx.module_set_max_tokens(mid, 512)
+    eng.ctx.set_residency(mid, [0])
+    assert eng.ctx.arena_stats()["used"] == base_long + packed
+    for bad in (0, 641):                            # below one token, beyond the KV cache
+        with pytest.raises(B.DLError) as e:
+            eng.ctx.module_set_max_tokens(mid, bad)
+        assert e.value.code == B.DL_ERR_INVALID_ARG
+    eng.close()
+
+
 def test_all_resident_releases_slots_and_bigger_module_resizes_them():
     c = small_cfg(3)
     eng, mid = _host_engine_with_module(c, cap=1 << 30)
