@@ -97,7 +97,7 @@ def test_tiny_decoder_greedy_ids_identical():
         g.eng.upload(g.xv[:T * c.d_model], x)
         g.eng.ctx.forward(g.mid, g.xp, g.yp, T, 0)
         h_ptr = g.yp + 4 * (T - 1) * c.d_model
-        g.eng.ctx.sync()
+        prefill_out = g.eng.download(g.yv[:T * c.d_model])
         used_long = g.eng.ctx.arena_stats()["used"]
         g.eng.ctx.module_set_max_tokens(g.mid, 1)
         assert g.eng.ctx.arena_stats()["used"] < used_long
@@ -110,6 +110,13 @@ def test_tiny_decoder_greedy_ids_identical():
         assert g.eng.download(tv).view(np.int32).tolist() == toks
         with pytest.raises(B.DLError):
             g.eng.ctx.forward(g.mid, g.xp, g.yp, 2, 0)
+        # grown back, the prefill runs again and reproduces its earlier output bit for bit
+        g.eng.ctx.set_residency(g.mid, [])
+        g.eng.ctx.module_set_max_tokens(g.mid, T)
+        g.eng.upload(g.xv[:T * c.d_model], x)
+        g.eng.ctx.forward(g.mid, g.xp, g.yp, T, 0)
+        again = g.eng.download(g.yv[:T * c.d_model])
+        assert np.array_equal(again.view(np.uint32), prefill_out.view(np.uint32))
     finally:
         g.close()
 
