@@ -10,7 +10,13 @@
  *   - Every call returns an int32_t: DL_OK (0) or a negative DL_ERR_* code;
  *     dl_last_error(ctx) gives a NUL-terminated message owned by the context.
  *   - A failed call leaves the context unchanged (a residency set that does
- *     not fit is rejected whole).
+ *     not fit is rejected whole).  One exception: DL_ERR_DEVICE from a call
+ *     that re-places device memory (residency, slot count, workspace size,
+ *     registration) can mean that a copy into memory the same call had taken
+ *     from a resident layer failed after the new placement was committed; the
+ *     context then refuses every further call with DL_ERR_DEVICE (dl_destroy
+ *     and dl_last_error still work).  When the new copies touch only free
+ *     memory they are made first and a failure changes nothing.
  *   - A context is used from one host thread.  No C++ type crosses the ABI.
  *   - "host" / "device" in a parameter comment says where the pointer lives.
  *   - BF16 data is passed as raw 16-bit patterns; matrices are row-major
@@ -99,10 +105,19 @@ const char* dl_last_error(const dl_ctx* ctx);
  * module is finalized.  Sec. IV-D: residency costs VRAM; here every device byte is counted. */
 int32_t dl_set_arena(dl_ctx* ctx, void* dev_base, uint64_t bytes);
 /* Sub-allocate from the arena for the caller's activations (counted against the cap).
- * DL_ERR_BUDGET_EXCEEDED if it does not fit. */
+ * DL_ERR_BUDGET_EXCEEDED if it does not fit.  Arena discipline: blocks that never move (these, KV caches, resident
+ * non-layer tensors, MLPs) are stacked at the top of the arena with the activation workspaces right below them;
+ * slots and resident layer copies fill it from the bottom and are placed again (re-copied from the pinned store)
+ * when a change does not fit between the holes.  The call synchronises both streams, because the workspaces move
+ * down (their contents are scratch within one call of the library and are not kept). */
 int32_t dl_arena_alloc(dl_ctx* ctx, uint64_t bytes, void** dev_ptr_out);
 int32_t dl_arena_free(dl_ctx* ctx, void* dev_ptr);
 int32_t dl_arena_stats(const dl_ctx* ctx, uint64_t* used, uint64_t* peak, uint64_t* capacity);
+/* *bytes = what slots and resident layer copies may use together: the arena below its top stack.  Sec. IV-D's
+ * budget, as the library accepts it: dl_set_residency / dl_set_slot_count take every choice whose resident copies plus
+ * n_slots slots of the largest layer that still streams (dl_module_layer_bytes' packed sizes) sum to at most *bytes,
+ * whatever was resident before, so a planner given this figure never proposes a set that is then refused. */
+int32_t dl_residency_budget(const dl_ctx* ctx, uint64_t* bytes);
 
 /* compute_stream / copy_stream: hipStream_t handles owned by the caller; distinct; default priority.
  * Sec. IV-C: one queue executes layers, the other prefetches parameters. */
@@ -141,8 +156,9 @@ int32_t dl_get_residency(const dl_ctx* ctx, int32_t module, int32_t* idx_out, in
  * module's pass simply re-issues its own first copy). */
 int32_t dl_set_mode(dl_ctx* ctx, int32_t mode, int32_t wrap_prefetch);
 
-/* Number of device slots the streamed layers go through: 2 (default: the Double Flat Buffer of Sec. IV-C(i), the copy
- * of the next streamed layer overlaps the execution of the current one) or 1 (the copy of the next streamed layer
+/* Number of device slots the streamed layers go through, 1 .. 4: 2 (default: the Double Flat Buffer of Sec. IV-C(i), the
+ * copy of the next streamed layer overlaps the execution of the current one), 3 or 4 (n - 1 copies run ahead of the
+ * executing layer: deeper prefetch, one more layer of memory each), or 1 (the copy of the next streamed layer
  * starts when the current one has executed and overlaps only the resident layers in between).  One slot gives a whole
  * layer of memory back: where a layer's copy takes far longer than its execution (single-token passes: ~60 x) the
  * overlap lost is worth less than one more resident layer.  Synchronises both streams and re-sizes the slots;
@@ -224,8 +240,10 @@ typedef struct {
 /* Sec. II-C / Table III: runs the module in sequential mode `iters` times at (n_tokens, pos0),
  * discards the first iteration, writes per-layer means.  Every layer is copied (into a slot)
  * and timed regardless of residency.  Then all layers are run back to back without copies (on
- * whatever parameters the slot holds: same shapes, same cost) to time them under continuous load.  out: host array [n_layers].  Restores the KV-cache
- * contents it touches only in the sense that positions pos0.. are rewritten by the next real pass. */
+ * whatever parameters the slot holds: same shapes, same cost) to time them under continuous load.  out: host array
+ * [n_layers].  A last sequential pass with every layer's own parameters leaves the KV-cache rows pos0 .. pos0+n_tokens-1
+ * as a real pass over x_dev writes them.  The call's temporaries (an activation block, weight copies for the continuous
+ * run) come out of the arena and are returned before it ends; dl_arena_stats' peak does not include them. */
 int32_t dl_profile(dl_ctx* ctx, int32_t module, int32_t n_tokens, int32_t pos0, const void* x_dev,
                    const void* ctx_dev, int32_t n_ctx, int32_t iters, dl_layer_profile* out);
 
@@ -282,7 +300,8 @@ int32_t dl_probe_mfma_rate(dl_ctx* ctx, int32_t pattern, int32_t iters, double* 
 /* The schedule one forward pass enqueues, as data (also recorded by host-only contexts). */
 enum { DL_OP_WAIT = 0, DL_OP_RECORD = 1, DL_OP_COPY = 2, DL_OP_EXEC = 3 };
 enum { DL_EV_DMA_DONE = 0, DL_EV_COMPUTE_DONE = 1, DL_EV_PASS_DONE = 2 };
-enum { DL_OPF_NEXT_PASS = 1 };   /* a copy that prefetches the first streamed layer of the NEXT pass */
+enum { DL_OPF_NEXT_PASS = 1 };   /* flags of a COPY = how many passes ahead of the current one the copied layer executes
+                                    (0: this pass; 1: prefetch for the next pass; up to 3 with four slots) */
 typedef struct {
     int32_t queue;       /* 0 = compute stream, 1 = copy stream */
     int32_t op;          /* DL_OP_* */
@@ -321,7 +340,7 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * waiting for its copy right before it (a GPU that idled runs the next kernels slower than one
  * kept busy; dl_profile measures both).  c_fence_ms (NULL = zeros): time added on the compute queue to
  * every streamed invocation for its two cross-stream hand-offs (dl_profile's c_fence_ms).
- * mode, wrap_prefetch: as dl_set_mode; n_slots: as dl_set_slot_count (1 or 2).  overhead_ms is added to every
+ * mode, wrap_prefetch: as dl_set_mode; n_slots: as dl_set_slot_count (1 .. 4).  overhead_ms is added to every
  * execution (fixed host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
  * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
 int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,

@@ -75,6 +75,7 @@ SIGNATURES = {
     "dl_arena_alloc": (_i32, [_p, _u64, C.POINTER(_p)]),
     "dl_arena_free": (_i32, [_p, _p]),
     "dl_arena_stats": (_i32, [_p, _PU64, _PU64, _PU64]),
+    "dl_residency_budget": (_i32, [_p, _PU64]),
     "dl_set_streams": (_i32, [_p, _p, _p]),
     "dl_module_create": (_i32, [_p, C.POINTER(dl_module_desc), _PI32]),
     "dl_layer_set_tensor": (_i32, [_p, _i32, _i32, _i32, _p, _u64]),
@@ -191,6 +192,11 @@ class Context:
         u, pk, cp = _u64(), _u64(), _u64()
         self._ck(lib().dl_arena_stats(self._h, C.byref(u), C.byref(pk), C.byref(cp)))
         return dict(used=u.value, peak=pk.value, capacity=cp.value)
+
+    def residency_budget(self):
+        b = _u64()
+        self._ck(lib().dl_residency_budget(self._h, C.byref(b)))
+        return b.value
 
     def set_streams(self, compute_stream, copy_stream, keep=None):
         self._ck(lib().dl_set_streams(self._h, _p(compute_stream), _p(copy_stream)))

@@ -106,14 +106,19 @@ def layer_param_count(c: ModuleConfig) -> int:
     return sum(int(np.prod(s)) for _, s, _ in layer_tensors(c))
 
 
-def make_layer_weights(c: ModuleConfig, layer: int) -> Dict[int, np.ndarray]:
+def make_layer_weights(c: ModuleConfig, layer: int, matrix_gain: float = 0.0) -> Dict[int, np.ndarray]:
     """BF16 bit patterns (uint16) per tensor id.  Matrices and biases ~ N(0, 0.02);
-    norm gains ~ 1 + N(0, 0.02) so that every block contributes at full scale."""
+    norm gains ~ 1 + N(0, 0.02) so that every block contributes at full scale.
+    matrix_gain > 0: matrices ~ N(0, matrix_gain / sqrt(in_features)) instead.  At the 8B-class shape the
+    stated 0.02 is a gain of 0.02 * sqrt(4096) = 1.28 per linear map; a small test shape (d = 144 .. 1024) with
+    std 0.02 has a gain of 0.24 .. 0.64 and its sub-blocks add almost nothing to the residual stream, so small
+    parity cases ask for the 8B shape's gain to keep every sub-block visible in the output."""
     out = {}
     for tid, shape, kind in layer_tensors(c):
         n = int(np.prod(shape))
         mean = 1.0 if kind == "gain" else 0.0
-        out[tid] = synth.normal_bf16(n, c.seed_base + layer, tid, mean, 0.02).reshape(shape)
+        std = matrix_gain / float(np.sqrt(shape[1])) if (kind == "matrix" and matrix_gain > 0) else 0.02
+        out[tid] = synth.normal_bf16(n, c.seed_base + layer, tid, mean, std).reshape(shape)
     return out
 
 
@@ -135,14 +140,28 @@ def make_head(c: ModuleConfig, seed: int = 8) -> Dict[int, np.ndarray]:
     return out
 
 
-def make_mlp(d_in: int, d_hidden: int, d_out: int, seed: int):
-    """(w1 [d_hidden, d_in], b1, w2 [d_out, d_hidden or d_in], b2) as BF16 bits ~ N(0, 0.02); w1, b1 None if d_hidden == 0."""
+def make_mlp(d_in: int, d_hidden: int, d_out: int, seed: int, matrix_gain: float = 0.0):
+    """(w1 [d_hidden, d_in], b1, w2 [d_out, d_hidden or d_in], b2) as BF16 bits ~ N(0, 0.02); w1, b1 None if d_hidden == 0.
+    matrix_gain > 0: matrices ~ N(0, matrix_gain / sqrt(in_features)), as in make_layer_weights."""
     k2 = d_hidden if d_hidden > 0 else d_in
-    w1 = synth.normal_bf16(d_hidden * d_in, seed, 0, 0.0, 0.02).reshape(d_hidden, d_in) if d_hidden > 0 else None
+    s1 = matrix_gain / float(np.sqrt(d_in)) if matrix_gain > 0 else 0.02
+    s2 = matrix_gain / float(np.sqrt(k2)) if matrix_gain > 0 else 0.02
+    w1 = synth.normal_bf16(d_hidden * d_in, seed, 0, 0.0, s1).reshape(d_hidden, d_in) if d_hidden > 0 else None
     b1 = synth.normal_bf16(d_hidden, seed, 1, 0.0, 0.02) if d_hidden > 0 else None
-    w2 = synth.normal_bf16(d_out * k2, seed, 2, 0.0, 0.02).reshape(d_out, k2)
+    w2 = synth.normal_bf16(d_out * k2, seed, 2, 0.0, s2).reshape(d_out, k2)
     b2 = synth.normal_bf16(d_out, seed, 3, 0.0, 0.02)
     return w1, b1, w2, b2
+
+
+def make_pipeline_inputs(vit: ModuleConfig, dec: ModuleConfig, act: ModuleConfig, n_patches: int, n_text: int,
+                         n_actions: int = 64, out_dim: int = 3, seeds=(11, 12, 13, 14, 15), matrix_gain: float = 0.0):
+    """Seeded non-layer inputs of the five-stage pipeline: merger MLP (vit.d -> dec.d -> dec.d), output projection
+    (act.d -> out_dim), patch tokens, text embeddings and the initial action noise, all ~ N(0, 1) / N(0, 0.02)."""
+    return dict(proj_w=make_mlp(vit.d_model, dec.d_model, dec.d_model, seeds[0], matrix_gain),
+                out_w=make_mlp(act.d_model, 0, out_dim, seeds[1], matrix_gain),
+                patches=make_tokens(n_patches, vit.d_model, seed=seeds[2]),
+                text=make_tokens(n_text, dec.d_model, seed=seeds[3]),
+                a0=make_tokens(n_actions, act.d_model, seed=seeds[4]))
 
 
 # ---- the workloads ---------------------------------------------------------

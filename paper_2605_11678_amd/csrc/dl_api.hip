@@ -56,12 +56,18 @@ struct dl_ctx {
     std::vector<Module> mods;
     std::vector<Mlp> mlps;
     uint64_t slot_bytes = 0;
-    uint64_t slot_off[2] = {0, 0};
-    int32_t n_slots = 2;          // device slots in use: 1 or 2
+    uint64_t slot_off[dl::kMaxSlots] = {0, 0, 0, 0};
+    int32_t n_slots = 2;          // device slots in use: 1 .. kMaxSlots
     int32_t slots_held = 0;       // how many of slot_off[] are allocated right now
     bool slots_alloc = false;
+    // Arena discipline.  Blocks that never move (KV caches, resident non-layer tensors, MLPs, the caller's blocks)
+    // are stacked at the TOP of the arena, the activation workspaces right below them; slots and resident layer
+    // copies fill the arena from the BOTTOM and may be moved (re-uploaded from the pinned store) whenever a change
+    // does not fit between the holes: what slots and resident layers can use is exactly what lies below the top stack.
+    std::vector<uint64_t> perms;  // offsets of the blocks that never move
+    bool poisoned = false;        // a device copy failed after the state was committed: the context is unusable
     dl::SlotBook book;
-    hipEvent_t ev_dma[2] = {nullptr, nullptr}, ev_comp[2] = {nullptr, nullptr}, ev_pass = nullptr;
+    hipEvent_t ev_dma[dl::kMaxSlots] = {}, ev_comp[dl::kMaxSlots] = {}, ev_pass = nullptr;
     bool events_made = false;
     static constexpr int kMaxRunAhead = 8;
     hipEvent_t ev_inflight[kMaxRunAhead] = {};   // end of the most recent streaming passes on the compute stream (host throttle)
@@ -72,7 +78,7 @@ struct dl_ctx {
     std::vector<dl_trace_op> trace;
     bool timing = false;
     std::vector<TimedOp> copies, execs;
-    int32_t last_copy_in_slot[2] = {-1, -1};
+    int32_t last_copy_in_slot[dl::kMaxSlots] = {-1, -1, -1, -1};
     std::vector<hipEvent_t> ev_pool;
     size_t ev_next = 0;
     uint32_t ktiming = 0;   // bit k set: launches of kernel class k are bracketed with events
@@ -98,6 +104,7 @@ bool on_gpu(const dl_ctx* c) { return c->device >= 0; }
 
 int32_t enter(dl_ctx* c) {
     if (!c) return DL_ERR_INVALID_ARG;
+    if (c->poisoned) return fail(c, DL_ERR_DEVICE, "the context is unusable: an earlier device copy failed after its state change was committed");
     if (on_gpu(c)) DL_HIP(c, hipSetDevice(c->device));
     return DL_OK;
 }
@@ -109,7 +116,7 @@ Module* get_module(dl_ctx* c, int32_t m) {
 
 int32_t make_events(dl_ctx* c) {
     if (c->events_made || !on_gpu(c)) return DL_OK;
-    for (int s = 0; s < 2; ++s) {
+    for (int s = 0; s < dl::kMaxSlots; ++s) {
         DL_HIP(c, hipEventCreateWithFlags(&c->ev_dma[s], hipEventDisableTiming));
         DL_HIP(c, hipEventCreateWithFlags(&c->ev_comp[s], hipEventDisableTiming));
     }
@@ -137,75 +144,213 @@ int32_t sync_streams(dl_ctx* c) {
     return DL_OK;
 }
 
-// Recomputes slot and resident-copy placement for a proposed residency of module `mi` on a COPY of
-// the arena; commits only if everything fits.  new_res == nullptr: keep residency (used by finalize).
-int32_t rebalance(dl_ctx* c, int32_t mi, const std::vector<uint8_t>* new_res) {
+// ---- placement of everything the library keeps in the arena ------------------------------------------
+// A proposed change: residency per module, workspace size per module, slot count, and blocks that never move to add.
+struct Proposal {
+    std::vector<std::vector<uint8_t>> resident;   // [module][layer]
+    std::vector<uint64_t> ws_bytes;               // [module]; 0: the module has no workspace (not finalized)
+    std::vector<uint8_t> counted;                 // [module]: finalized, or being finalized by this change
+    int32_t n_slots = 2;
+    std::vector<uint64_t> new_perm;               // sizes of blocks to add to the top stack, in order
+};
+
+struct Placement {
+    dl::Arena arena;
+    std::vector<std::vector<uint64_t>> res_off;
+    std::vector<uint64_t> ws_off;
+    std::vector<uint8_t> ws_moved;
+    uint64_t slot_off[dl::kMaxSlots] = {0, 0, 0, 0};
+    uint64_t slot_bytes = 0;
+    int32_t slots_held = 0;
+    std::vector<uint64_t> perm_off;
+};
+
+Proposal current_proposal(const dl_ctx* c) {
+    Proposal p;
+    p.n_slots = c->n_slots;
+    for (const Module& M : c->mods) {
+        p.resident.push_back(M.resident);
+        p.ws_bytes.push_back(M.finalized ? M.W.bytes : 0);
+        p.counted.push_back(M.finalized ? 1 : 0);
+    }
+    return p;
+}
+
+// Places the proposal on a copy of the arena.  repack == false: blocks that stay keep their place, new ones go
+// first-fit.  repack == true: every slot, resident copy and workspace is released and placed again (top stack first,
+// then slots and resident copies from the bottom, largest layers first), which leaves no hole below the top stack.
+bool place(const dl_ctx* c, const Proposal& p, bool repack, Placement* out, std::string* why) {
     dl::Arena A = c->arena;
-    Module& M = c->mods[size_t(mi)];
-    std::vector<uint8_t> res = new_res ? *new_res : M.resident;
-    std::vector<uint64_t> off = M.res_off;
-    // 1. release copies of layers that stop being resident
-    for (int32_t i = 0; i < M.d.n_layers; ++i)
-        if (M.resident[size_t(i)] && !res[size_t(i)]) A.free(off[size_t(i)]);
-    // 2. slots: two buffers of the largest layer that may be copied into one, i.e. over the modules that stream at
-    // least one layer (a fully resident module never touches a slot, so it does not size them: with the 8B decoder
-    // resident the pair shrinks from 2 x 386 MB to what the small stacks need); none while nothing streams
+    const size_t nm = c->mods.size();
+    out->res_off.assign(nm, {});
+    out->ws_off.assign(nm, 0);
+    out->ws_moved.assign(nm, 0);
+    out->perm_off.clear();
+    bool touch_ws = repack || !p.new_perm.empty();
+    for (size_t m = 0; m < nm; ++m) {
+        const Module& M = c->mods[m];
+        out->res_off[m] = M.res_off;
+        out->ws_off[m] = M.ws_off;
+        const uint64_t old_ws = M.finalized ? M.W.bytes : 0;
+        touch_ws = touch_ws || old_ws != p.ws_bytes[m];
+    }
+    // 1. release
+    for (size_t m = 0; m < nm; ++m) {
+        const Module& M = c->mods[m];
+        for (int32_t i = 0; i < M.d.n_layers; ++i)
+            if (M.resident[size_t(i)] && (repack || !p.resident[m][size_t(i)])) A.free(M.res_off[size_t(i)]);
+        if (touch_ws && M.finalized) A.free(M.ws_off);
+    }
     uint64_t need_bytes = 0;
     bool any_streamed = false;
-    for (size_t m = 0; m < c->mods.size(); ++m) {
-        const Module& X = c->mods[m];
-        if (!X.finalized && int32_t(m) != mi) continue;
-        const std::vector<uint8_t>& r = (int32_t(m) == mi) ? res : X.resident;
+    for (size_t m = 0; m < nm; ++m) {
+        if (!p.counted[m]) continue;
         bool streams = false;
-        for (uint8_t v : r) streams |= !v;
-        if (streams) need_bytes = std::max(need_bytes, X.L.bytes);
+        for (uint8_t v : p.resident[m]) streams |= !v;
+        if (streams) need_bytes = std::max(need_bytes, c->mods[m].L.bytes);
         any_streamed |= streams;
     }
-    bool slots_alloc = c->slots_alloc;
-    uint64_t slot_off[2] = {c->slot_off[0], c->slot_off[1]};
-    uint64_t slot_bytes = c->slot_bytes;
-    int32_t slots_held = c->slots_held;
-    if (slots_alloc && (!any_streamed || slot_bytes != need_bytes || slots_held != c->n_slots)) {
-        for (int32_t k = 0; k < slots_held; ++k) A.free(slot_off[k]);
-        slots_alloc = false;
-        slots_held = 0;
+    const bool keep_slots = !repack && c->slots_alloc && any_streamed && c->slot_bytes == need_bytes && c->slots_held == p.n_slots;
+    if (c->slots_alloc && !keep_slots)
+        for (int32_t k = 0; k < c->slots_held; ++k) A.free(c->slot_off[k]);
+    // 2. the top stack: blocks that never move, then the workspaces.  Each must land inside the stack (a hole left by
+    // a released block) or directly below it; anything else would strand it among the movable blocks.
+    uint64_t top = A.capacity();
+    for (uint64_t off : c->perms) top = std::min(top, off);
+    if (!touch_ws)
+        for (size_t m = 0; m < nm; ++m)
+            if (c->mods[m].finalized) top = std::min(top, c->mods[m].ws_off);
+    auto stack_block = [&](uint64_t bytes, uint64_t* off) {
+        if (!A.alloc_top(bytes, off)) return false;
+        const uint64_t sz = dl::align_up(bytes ? bytes : 1);
+        if (*off < top && *off + sz != top) return false;
+        top = std::min(top, *off);
+        return true;
+    };
+    for (uint64_t bytes : p.new_perm) {
+        uint64_t off = 0;
+        if (!stack_block(bytes, &off)) { *why = "arena cannot hold the block below its top stack"; return false; }
+        out->perm_off.push_back(off);
     }
-    if (any_streamed && !slots_alloc) {
-        for (int32_t k = 0; k < c->n_slots; ++k)
-            if (!A.alloc(need_bytes, &slot_off[k])) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the layer slots");
-        slots_alloc = true;
-        slots_held = c->n_slots;
-        slot_bytes = need_bytes;
+    if (touch_ws)
+        for (size_t m = 0; m < nm; ++m) {
+            if (!p.ws_bytes[m]) continue;
+            uint64_t off = 0;
+            if (!stack_block(p.ws_bytes[m], &off)) { *why = "arena cannot hold the activation workspace"; return false; }
+            out->ws_moved[m] = 1;
+            out->ws_off[m] = off;
+        }
+    // 3. slots, then resident copies, from the bottom
+    out->slot_bytes = any_streamed ? need_bytes : 0;
+    out->slots_held = 0;
+    if (keep_slots) {
+        for (int32_t k = 0; k < c->slots_held; ++k) out->slot_off[k] = c->slot_off[k];
+        out->slots_held = c->slots_held;
+    } else if (any_streamed) {
+        for (int32_t k = 0; k < p.n_slots; ++k)
+            if (!A.alloc(need_bytes, &out->slot_off[k])) { *why = "arena cannot hold the layer slots"; return false; }
+        out->slots_held = p.n_slots;
     }
-    // 3. copies of newly resident layers
-    std::vector<int32_t> to_upload;
-    for (int32_t i = 0; i < M.d.n_layers; ++i) {
-        if (res[size_t(i)] && !M.resident[size_t(i)]) {
-            if (!A.alloc(M.L.bytes, &off[size_t(i)])) {
-                char buf[160];
-                snprintf(buf, sizeof buf, "arena cannot hold resident layer %d (%llu bytes each, %llu of %llu used)", i,
-                         (unsigned long long)M.L.bytes, (unsigned long long)A.used(), (unsigned long long)A.capacity());
-                return fail(c, DL_ERR_BUDGET_EXCEEDED, buf);
+    std::vector<size_t> order(nm);
+    for (size_t m = 0; m < nm; ++m) order[m] = m;
+    if (repack)
+        std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b2) { return c->mods[a].L.bytes > c->mods[b2].L.bytes; });
+    for (size_t m : order) {
+        const Module& M = c->mods[m];
+        for (int32_t i = 0; i < M.d.n_layers; ++i) {
+            if (!p.resident[m][size_t(i)] || (!repack && M.resident[size_t(i)])) continue;
+            if (!A.alloc(M.L.bytes, &out->res_off[m][size_t(i)])) {
+                char buf[200];
+                snprintf(buf, sizeof buf, "arena cannot hold resident layer %d of module %d (%llu bytes each, %llu of %llu used)", i,
+                         int(m), (unsigned long long)M.L.bytes, (unsigned long long)A.used(), (unsigned long long)A.capacity());
+                *why = buf;
+                return false;
             }
-            to_upload.push_back(i);
         }
     }
-    // commit
-    c->arena = A;
-    c->slots_alloc = slots_alloc;
-    c->slot_off[0] = slot_off[0];
-    c->slot_off[1] = slot_off[1];
-    c->slot_bytes = slot_bytes;
-    c->slots_held = slots_held;
-    M.resident = res;
-    M.res_off = off;
+    out->arena = A;
+    return true;
+}
+
+// Applies a proposal: first-fit next to what is there, and if that does not fit, with everything movable placed
+// again.  Commits only if it fits (DL_ERR_BUDGET_EXCEEDED otherwise, nothing changed); new_perm_out receives the
+// offsets of the added blocks.  The streams must be idle.
+int32_t relayout(dl_ctx* c, const Proposal& p, std::vector<uint64_t>* new_perm_out = nullptr) {
+    Placement P;
+    std::string why;
+    if (!place(c, p, false, &P, &why) && !place(c, p, true, &P, &why)) return fail(c, DL_ERR_BUDGET_EXCEEDED, why);
+    // layer copies to (re)fill from the pinned store: newly resident ones and those that moved
+    struct Up { size_t m; int32_t i; uint64_t off; };
+    std::vector<Up> ups;
+    bool reuses_live_copy = false;
+    for (size_t m = 0; m < c->mods.size(); ++m) {
+        const Module& M = c->mods[m];
+        for (int32_t i = 0; i < M.d.n_layers; ++i) {
+            if (!p.resident[m][size_t(i)]) continue;
+            if (!M.resident[size_t(i)] || M.res_off[size_t(i)] != P.res_off[m][size_t(i)]) ups.push_back({m, i, P.res_off[m][size_t(i)]});
+        }
+    }
+    // does an upload land on memory that holds a resident copy in the CURRENT state (one dropped or moved by this call)?
+    for (const Up& u : ups) {
+        const uint64_t u0 = u.off, u1 = u.off + c->mods[u.m].L.bytes;
+        for (size_t m = 0; m < c->mods.size() && !reuses_live_copy; ++m) {
+            const Module& M = c->mods[m];
+            for (int32_t i = 0; i < M.d.n_layers; ++i)
+                if (M.resident[size_t(i)] && u0 < M.res_off[size_t(i)] + M.L.bytes && M.res_off[size_t(i)] < u1) { reuses_live_copy = true; break; }
+        }
+    }
+    auto upload = [&](const Up& u) -> hipError_t {
+        const Module& M = c->mods[u.m];
+        return hipMemcpy(c->base + u.off, M.store + size_t(u.i) * M.L.bytes, M.L.bytes, hipMemcpyHostToDevice);
+    };
+    // what the slots hold is gone either way (a copy issued ahead for the next pass is simply issued again)
     c->book = dl::SlotBook();
     c->book.n_slots = c->n_slots;
-    if (on_gpu(c)) {
-        for (int32_t i : to_upload)
-            DL_HIP(c, hipMemcpy(c->base + off[size_t(i)], M.store + size_t(i) * M.L.bytes, M.L.bytes,
-                                hipMemcpyHostToDevice));
+    if (on_gpu(c) && !reuses_live_copy) {
+        // the new copies only touch memory that is free or transient in the current state: fill them first, so that a
+        // failed copy leaves the context exactly as it was
+        for (const Up& u : ups) DL_HIP(c, upload(u));
     }
+    c->arena = P.arena;
+    c->n_slots = p.n_slots;
+    c->book.n_slots = p.n_slots;
+    c->slots_alloc = P.slots_held > 0;
+    c->slots_held = P.slots_held;
+    c->slot_bytes = P.slot_bytes;
+    for (int32_t k = 0; k < dl::kMaxSlots; ++k) c->slot_off[k] = P.slot_off[k];
+    for (size_t m = 0; m < c->mods.size(); ++m) {
+        c->mods[m].resident = p.resident[m];
+        c->mods[m].res_off = P.res_off[m];
+        c->mods[m].ws_off = P.ws_off[m];
+    }
+    for (uint64_t off : P.perm_off) c->perms.push_back(off);
+    if (new_perm_out) *new_perm_out = P.perm_off;
+    if (on_gpu(c)) {
+        hipError_t e = hipSuccess;
+        if (reuses_live_copy)
+            for (const Up& u : ups)
+                if (e == hipSuccess) e = upload(u);
+        // stale bytes in the transposed-V areas of a workspace must be finite numbers: a placed workspace starts as zeros
+        for (size_t m = 0; m < c->mods.size(); ++m)
+            if (P.ws_moved[m] && e == hipSuccess) e = hipMemset(c->base + P.ws_off[m], 0, p.ws_bytes[m]);
+        if (e != hipSuccess) {
+            c->poisoned = true;
+            return fail(c, DL_ERR_DEVICE, std::string("device copy failed after the new placement was committed: ") + hipGetErrorString(e));
+        }
+    }
+    return DL_OK;
+}
+
+// adds one block to the top stack (see dl_ctx::perms); synchronises, because the workspaces move
+int32_t add_permanent(dl_ctx* c, uint64_t bytes, uint64_t* off) {
+    int32_t rc = sync_streams(c);
+    if (rc) return rc;
+    Proposal p = current_proposal(c);
+    p.new_perm.push_back(bytes);
+    std::vector<uint64_t> offs;
+    rc = relayout(c, p, &offs);
+    if (rc) return rc;
+    *off = offs[0];
     return DL_OK;
 }
 
@@ -509,7 +654,7 @@ int32_t dl_destroy(dl_ctx* c) {
             (void)hipStreamSynchronize(c->s_compute);
         }
         if (c->events_made) {
-            for (int s = 0; s < 2; ++s) {
+            for (int s = 0; s < dl::kMaxSlots; ++s) {
                 (void)hipEventDestroy(c->ev_dma[s]);
                 (void)hipEventDestroy(c->ev_comp[s]);
             }
@@ -546,8 +691,9 @@ int32_t dl_arena_alloc(dl_ctx* c, uint64_t bytes, void** out) {
     if (rc) return rc;
     if (!out || bytes == 0) return fail(c, DL_ERR_INVALID_ARG, "bad arguments");
     if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
-    uint64_t off;
-    if (!c->arena.alloc(bytes, &off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the requested block");
+    uint64_t off = 0;
+    rc = add_permanent(c, bytes, &off);
+    if (rc) return rc;
     *out = c->base + off;
     return DL_OK;
 }
@@ -557,7 +703,9 @@ int32_t dl_arena_free(dl_ctx* c, void* p) {
     if (rc) return rc;
     if (!c->arena.is_set()) return fail(c, DL_ERR_BAD_STATE, "arena not set");
     const uint64_t off = uint64_t(static_cast<uint8_t*>(p) - c->base);
-    if (!c->arena.free(off)) return fail(c, DL_ERR_INVALID_ARG, "pointer is not a live arena block");
+    auto it = std::find(c->perms.begin(), c->perms.end(), off);
+    if (!p || it == c->perms.end() || !c->arena.free(off)) return fail(c, DL_ERR_INVALID_ARG, "pointer is not a live arena block of the caller");
+    c->perms.erase(it);
     return DL_OK;
 }
 
@@ -566,6 +714,16 @@ int32_t dl_arena_stats(const dl_ctx* c, uint64_t* used, uint64_t* peak, uint64_t
     if (used) *used = c->arena.used();
     if (peak) *peak = c->arena.peak();
     if (cap) *cap = c->arena.capacity();
+    return DL_OK;
+}
+
+int32_t dl_residency_budget(const dl_ctx* c, uint64_t* bytes) {
+    if (!c || !bytes) return DL_ERR_INVALID_ARG;
+    uint64_t top = c->arena.capacity();
+    for (uint64_t off : c->perms) top = std::min(top, off);
+    for (const Module& M : c->mods)
+        if (M.finalized) top = std::min(top, M.ws_off);
+    *bytes = top;
     return DL_OK;
 }
 
@@ -644,17 +802,17 @@ int32_t dl_set_resident_tensor(dl_ctx* c, int32_t module, int32_t which, const v
     else if (which == DL_R_FINAL_NORM_G) want = M->d.d_model;
     else want = M->d.norm == DL_NORM_LN ? M->d.d_model : 0;
     if (want == 0 || want != n) return fail(c, DL_ERR_INVALID_ARG, "resident tensor has the wrong size for this module");
+    rc = sync_streams(c);
+    if (rc) return rc;
     if (!M->rt_set[which]) {
-        uint64_t off;
-        if (!c->arena.alloc(2 * n, &off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the resident tensor");
+        uint64_t off = 0;
+        rc = add_permanent(c, 2 * n, &off);
+        if (rc) return rc;
+        M = get_module(c, module);
         M->rt_off[which] = off;
         M->rt_set[which] = true;
     }
-    if (on_gpu(c)) {
-        rc = sync_streams(c);
-        if (rc) return rc;
-        DL_HIP(c, hipMemcpy(c->base + M->rt_off[which], host, 2 * n, hipMemcpyHostToDevice));
-    }
+    if (on_gpu(c)) DL_HIP(c, hipMemcpy(c->base + M->rt_off[which], host, 2 * n, hipMemcpyHostToDevice));
     return DL_OK;
 }
 
@@ -675,26 +833,17 @@ int32_t dl_module_finalize(dl_ctx* c, int32_t module) {
         }
     rc = sync_streams(c);
     if (rc) return rc;
-    // workspace and KV cache first, then the slots; undo on failure
-    uint64_t ws = 0, kv = 0;
-    if (!c->arena.alloc_top(M->W.bytes, &ws)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the activation workspace");
-    if (M->KV.bytes && !c->arena.alloc(M->KV.bytes, &kv)) {
-        c->arena.free(ws);
-        return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the KV cache");
-    }
-    M->ws_off = ws;
-    M->kv_off = kv;
-    rc = rebalance(c, module, nullptr);
-    if (rc) {
-        c->arena.free(ws);
-        if (M->KV.bytes) c->arena.free(kv);
-        return rc;
-    }
-    if (on_gpu(c)) {
-        // stale bytes in the transposed-V areas must be finite numbers: zero everything once
-        DL_HIP(c, hipMemset(c->base + ws, 0, M->W.bytes));
-        if (M->KV.bytes) DL_HIP(c, hipMemset(c->base + kv, 0, M->KV.bytes));
-    }
+    // KV cache (never moves) on the top stack, the workspace below it, the slots from the bottom: all or nothing
+    Proposal p = current_proposal(c);
+    p.counted[size_t(module)] = 1;
+    p.ws_bytes[size_t(module)] = M->W.bytes;
+    if (M->KV.bytes) p.new_perm.push_back(M->KV.bytes);
+    std::vector<uint64_t> offs;
+    rc = relayout(c, p, &offs);
+    if (rc) return rc;
+    M = get_module(c, module);
+    M->kv_off = M->KV.bytes ? offs[0] : 0;
+    if (on_gpu(c) && M->KV.bytes) DL_HIP(c, hipMemset(c->base + M->kv_off, 0, M->KV.bytes));
     M->finalized = true;
     return DL_OK;
 }
@@ -721,7 +870,9 @@ int32_t dl_set_residency(dl_ctx* c, int32_t module, const int32_t* idx, int32_t 
     }
     rc = sync_streams(c);
     if (rc) return rc;
-    return rebalance(c, module, &res);
+    Proposal p = current_proposal(c);
+    p.resident[size_t(module)] = res;
+    return relayout(c, p);
 }
 
 int32_t dl_get_residency(const dl_ctx* c, int32_t module, int32_t* idx_out, int32_t* n_out) {
@@ -794,8 +945,9 @@ int32_t dl_final_norm(dl_ctx* c, int32_t module, const void* h, void* out, int32
 // token to token_copy, if given) by the same launch that picks it
 static int32_t head_common(dl_ctx* c, Module* M, const void* h, int32_t* token_copy = nullptr, float* x_next = nullptr) {
     if (!M || !M->finalized) return fail(c, DL_ERR_BAD_STATE, "module missing or not finalized");
-    if (M->d.vocab <= 0 || !M->rt_set[DL_R_HEAD] || !M->rt_set[DL_R_FINAL_NORM_G])
-        return fail(c, DL_ERR_BAD_STATE, "head or final norm not set");
+    if (M->d.vocab <= 0 || !M->rt_set[DL_R_HEAD] || !M->rt_set[DL_R_FINAL_NORM_G] ||
+        (M->d.norm == DL_NORM_LN && !M->rt_set[DL_R_FINAL_NORM_B]))
+        return fail(c, DL_ERR_BAD_STATE, "head or final norm parameters not set");
     if (x_next && !M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
     if (!on_gpu(c)) return DL_OK;
     if (!h) return fail(c, DL_ERR_INVALID_ARG, "null hidden state");
@@ -865,16 +1017,17 @@ int32_t dl_mlp_create(dl_ctx* c, int32_t d_in, int32_t d_hidden, int32_t d_out, 
     if (m.has_b2) parts.push_back({&m.b2, 2ull * d_out, b2});
     parts.push_back({&m.xin, 2ull * max_tokens * d_in, nullptr});
     if (d_hidden > 0) parts.push_back({&m.hid, 2ull * max_tokens * d_hidden, nullptr});
-    dl::Arena A = c->arena;                       // all or nothing
-    for (Part& p : parts)
-        if (!A.alloc(p.bytes, p.off)) return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the MLP");
-    c->arena = A;
-    if (on_gpu(c)) {
-        rc = sync_streams(c);
-        if (rc) return rc;
+    rc = sync_streams(c);
+    if (rc) return rc;
+    Proposal prop = current_proposal(c);          // all or nothing
+    for (Part& p : parts) prop.new_perm.push_back(p.bytes);
+    std::vector<uint64_t> offs;
+    rc = relayout(c, prop, &offs);
+    if (rc) return rc;
+    for (size_t i = 0; i < parts.size(); ++i) *parts[i].off = offs[i];
+    if (on_gpu(c))
         for (Part& p : parts)
             if (p.src) DL_HIP(c, hipMemcpy(c->base + *p.off, p.src, p.bytes, hipMemcpyHostToDevice));
-    }
     c->mlps.push_back(m);
     *mlp_out = int32_t(c->mlps.size() - 1);
     return DL_OK;
@@ -1012,7 +1165,7 @@ int32_t dl_collect_stats(dl_ctx* c, dl_run_stats* stats, dl_layer_record* recs, 
     stats->n_layer_records = int32_t(c->execs.size());
     c->copies.clear();
     c->execs.clear();
-    c->last_copy_in_slot[0] = c->last_copy_in_slot[1] = -1;
+    for (int s = 0; s < dl::kMaxSlots; ++s) c->last_copy_in_slot[s] = -1;
     if (c->krecs.empty()) c->ev_next = 0;
     return DL_OK;
 }
@@ -1035,10 +1188,13 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     rc = sync_streams(c);
     if (rc) return rc;
     if (!c->copies.empty() || !c->execs.empty()) return fail(c, DL_ERR_BAD_STATE, "collect pending statistics first");
-    void* tmp = nullptr;
-    rc = dl_arena_alloc(c, uint64_t(T) * M->d.d_model * 4, &tmp);
-    if (rc) return rc;
-    scratch = static_cast<float*>(tmp);
+    // temporaries of this call (its output row block, weight copies for the continuous run) come from the bottom of
+    // the arena and are gone when it returns; the peak they reach is not the path's
+    const uint64_t peak_before = c->arena.peak();
+    uint64_t tmp_off = 0;
+    if (!c->arena.alloc(uint64_t(T) * M->d.d_model * 4, &tmp_off))
+        return fail(c, DL_ERR_BUDGET_EXCEEDED, "arena cannot hold the profiling run's activation block");
+    scratch = reinterpret_cast<float*>(c->base + tmp_off);
     const int32_t mode0 = c->mode, wrap0 = c->wrap;
     const bool timing0 = c->timing, tracing0 = c->tracing;
     c->mode = DL_MODE_SEQUENTIAL;
@@ -1142,6 +1298,15 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
                 for (int32_t i = 0; i < Ln; ++i) hot[size_t(i)] *= double(total) / sum;
         }
     }
+    // The continuous runs executed every layer on rotated parameters and appended THOSE keys and values at pos0..:
+    // one more sequential pass with every layer's own parameters leaves the cache rows as a real pass over this
+    // input writes them.
+    if (rc == DL_OK && M->d.max_seq > 0) {
+        c->timing = false;
+        c->book = dl::SlotBook();
+        c->book.n_slots = c->n_slots;
+        rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
+    }
     c->mode = mode0;
     c->wrap = wrap0;
     c->timing = timing0;
@@ -1153,7 +1318,8 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     c->copies.clear();
     c->execs.clear();
     if (c->krecs.empty()) c->ev_next = 0;
-    dl_arena_free(c, tmp);
+    c->arena.free(tmp_off);
+    c->arena.restore_peak(peak_before);
     if (rc) return rc;
     for (int32_t i = 0; i < Ln; ++i) {
         out[i].c_dma_ms = dma[size_t(i)] / (iters - 1);
@@ -1176,22 +1342,13 @@ int32_t dl_set_run_ahead(dl_ctx* c, int32_t passes) {
 int32_t dl_set_slot_count(dl_ctx* c, int32_t n_slots) {
     int32_t rc = enter(c);
     if (rc) return rc;
-    if (n_slots != 1 && n_slots != 2) return fail(c, DL_ERR_INVALID_ARG, "slot count must be 1 or 2");
+    if (n_slots < 1 || n_slots > dl::kMaxSlots) return fail(c, DL_ERR_INVALID_ARG, "slot count must be 1 .. 4");
     if (n_slots == c->n_slots) return DL_OK;
     rc = sync_streams(c);
     if (rc) return rc;
-    const int32_t before = c->n_slots;
-    c->n_slots = n_slots;
-    // re-size through the same path as a residency change (of any finalized module, keeping its residency)
-    for (size_t m = 0; m < c->mods.size(); ++m) {
-        if (!c->mods[m].finalized) continue;
-        rc = rebalance(c, int32_t(m), nullptr);
-        if (rc) c->n_slots = before;
-        return rc;
-    }
-    c->book = dl::SlotBook();
-    c->book.n_slots = c->n_slots;
-    return DL_OK;
+    Proposal p = current_proposal(c);
+    p.n_slots = n_slots;
+    return relayout(c, p);
 }
 
 int32_t dl_module_set_max_tokens(dl_ctx* c, int32_t module, int32_t max_tokens) {
@@ -1207,22 +1364,13 @@ int32_t dl_module_set_max_tokens(dl_ctx* c, int32_t module, int32_t max_tokens) 
     dl_module_desc d2 = M->d;
     d2.max_tokens = max_tokens;
     const dl::WorkspaceLayout W2 = dl::make_workspace(d2);
-    // on a copy of the allocator: release the old block, place the new one, commit only if that worked
-    dl::Arena A = c->arena;
-    A.free(M->ws_off);
-    uint64_t off = 0;
-    if (!A.alloc_top(W2.bytes, &off)) {
-        char buf[160];
-        snprintf(buf, sizeof buf, "arena cannot hold a workspace for %d tokens (%llu bytes, %llu of %llu used)", max_tokens,
-                 (unsigned long long)W2.bytes, (unsigned long long)c->arena.used(), (unsigned long long)c->arena.capacity());
-        return fail(c, DL_ERR_BUDGET_EXCEEDED, buf);
-    }
-    c->arena = A;
-    M->ws_off = off;
+    Proposal p = current_proposal(c);
+    p.ws_bytes[size_t(module)] = W2.bytes;
+    rc = relayout(c, p);
+    if (rc) return rc;
+    M = get_module(c, module);
     M->W = W2;
     M->d = d2;
-    // stale bytes in the transposed-V areas must be finite numbers
-    if (on_gpu(c)) DL_HIP(c, hipMemset(c->base + off, 0, W2.bytes));
     return DL_OK;
 }
 

@@ -105,6 +105,9 @@ bool validate_desc(const dl_module_desc& d, std::string* why) {
     if (d.max_seq < 0 || d.max_tokens < 1) return bad("max_seq >= 0 and max_tokens >= 1 required");
     if (d.max_seq > 0 && !d.causal) return bad("a KV cache needs a causal module");
     if (d.max_seq > 0 && d.max_tokens > d.max_seq) return bad("max_tokens exceeds max_seq");
+    // the single-token attention kernel maps the query heads of one KV head onto the 32 columns of one MFMA tile
+    if (d.max_seq > 0 && d.n_q_heads / d.n_kv_heads > 32)
+        return bad("with a KV cache at most 32 query heads may share one KV head");
     if (d.vocab < 0) return bad("vocab < 0");
     if (!(d.norm_eps >= 0)) return bad("norm_eps < 0");
     return true;
@@ -309,9 +312,11 @@ void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32
         if (force_stream_all || !resident[i]) streamed.push_back(i);
     std::vector<int32_t> slot_of(n_layers, -1);
 
+    auto drop_pending = [&]() { book->n_pending = 0; book->pending_module = -1; };
+
     if (mode == DL_MODE_SEQUENTIAL) {
         // Sec. IV-B: the copy of a layer starts only when the previous layer has finished
-        book->pending_module = book->pending_layer = book->pending_slot = -1;
+        drop_pending();
         size_t si = 0;
         for (int32_t i = 0; i < n_layers; ++i) {
             const bool st = si < streamed.size() && streamed[si] == i;
@@ -336,61 +341,88 @@ void build_pass(int32_t module, int32_t n_layers, const uint8_t* resident, int32
         return;
     }
 
-    auto issue_copy = [&](int32_t layer, bool gate_on_pass) -> int32_t {
+    auto issue_copy = [&](int32_t layer, bool gate_on_pass, int32_t passes_ahead) -> int32_t {
         const int32_t s = int32_t(book->ordinal++ % uint64_t(book->n_slots));
         if (gate_on_pass && book->pass_recorded) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_PASS_DONE, -1, module, layer));
         // the slot may be overwritten only after the layer that last used it has executed
         if (book->compute_recorded[s]) ops->push_back(mk(QD, DL_OP_WAIT, DL_EV_COMPUTE_DONE, s, module, layer));
-        ops->push_back(mk(QD, DL_OP_COPY, -1, s, module, layer));
+        dl_trace_op cp = mk(QD, DL_OP_COPY, -1, s, module, layer);
+        cp.flags = passes_ahead;
+        ops->push_back(cp);
         ops->push_back(mk(QD, DL_OP_RECORD, DL_EV_DMA_DONE, s, module, layer));
         book->dma_recorded[s] = true;
         return s;
     };
 
-    if (!streamed.empty()) {
-        const int32_t first = streamed[0];
-        if (book->pending_module == module && book->pending_layer == first && book->pending_slot >= 0) {
-            slot_of[first] = book->pending_slot;          // prefetched at the end of the previous pass
+    // The streamed layers of this pass and of the passes after it form one sequence q = 0, 1, 2, ...:
+    // q < n_str is streamed layer q of this pass, q >= n_str is layer streamed[q % n_str] of pass q / n_str ahead
+    // (copied ahead only with cross-pass prefetch, and only while the next passes run the same module).
+    const size_t n_str = streamed.size();
+    size_t issued = 0;                          // copies q < issued have been issued
+    // copies issued ahead by earlier passes: consumed in order as long as they are the copies this pass needs
+    if (n_str > 0 && book->pending_module == module) {
+        bool match = true;
+        for (int32_t j = 0; j < book->n_pending; ++j) match = match && book->pending_layer[j] == streamed[size_t(j) % n_str];
+        if (match) {
+            for (int32_t j = 0; j < book->n_pending; ++j) {
+                if (size_t(j) < n_str) slot_of[streamed[size_t(j)]] = book->pending_slot[j];
+                ++issued;
+            }
+            // entries beyond this pass's own layers stay pending for the passes after it
+            const int32_t used = int32_t(std::min(n_str, size_t(book->n_pending)));
+            for (int32_t j = used; j < book->n_pending; ++j) {
+                book->pending_layer[j - used] = book->pending_layer[j];
+                book->pending_slot[j - used] = book->pending_slot[j];
+            }
+            book->n_pending -= used;
+            if (book->n_pending == 0) book->pending_module = -1;
         } else {
-            slot_of[first] = issue_copy(first, /*gate_on_pass=*/!wrap_prefetch);
+            drop_pending();
         }
+    } else {
+        drop_pending();
     }
-    book->pending_module = book->pending_layer = book->pending_slot = -1;
-
-    // the copy that follows streamed layer number si: the next streamed layer, or (cross-pass prefetch) the first
-    // streamed layer of the next pass
-    auto issue_following = [&](size_t si) {
-        if (si < streamed.size()) {
-            slot_of[streamed[si]] = issue_copy(streamed[si], false);
-        } else if (wrap_prefetch) {
-            book->pending_slot = issue_copy(streamed[0], false);
-            for (size_t b = ops->size(); b-- > 0;)
-                if ((*ops)[b].op == DL_OP_COPY) { (*ops)[b].flags |= DL_OPF_NEXT_PASS; break; }
-            book->pending_module = module;
-            book->pending_layer = streamed[0];
+    auto issue_until = [&](size_t limit) {
+        while (issued < limit) {
+            const size_t q = issued;
+            if (q < n_str) {
+                slot_of[streamed[q]] = issue_copy(streamed[q], /*gate_on_pass=*/q == 0 && !wrap_prefetch, 0);
+            } else {
+                if (!wrap_prefetch || n_str == 0 || book->n_pending >= kMaxSlots) return;
+                const int32_t layer = streamed[q % n_str];
+                const int32_t s = issue_copy(layer, false, int32_t(q / n_str));
+                book->pending_module = module;
+                book->pending_layer[book->n_pending] = layer;
+                book->pending_slot[book->n_pending] = s;
+                ++book->n_pending;
+            }
+            ++issued;
         }
     };
-    // With two slots the following copy goes to the other slot, whose last user has long recorded its compute-done
-    // event: it is issued before this layer executes and overlaps it.  With one slot it overwrites THIS layer's
-    // parameters, so it is issued after this layer's compute-done record (a wait refers to the latest record issued
-    // before it) and overlaps only the resident layers that follow.
+    // With n slots, n - 1 copies run ahead of the streamed layer that executes: the copy into a slot is issued when
+    // the layer that used the slot n streamed layers earlier has long recorded its compute-done event, so it overlaps
+    // the execution of the layers before it.  With one slot the following copy overwrites THIS layer's parameters,
+    // so it is issued after this layer's compute-done record (a wait refers to the latest record issued before it)
+    // and overlaps only the resident layers that follow.
     const bool one_slot = book->n_slots == 1;
+    const size_t ahead = one_slot ? 0 : size_t(book->n_slots - 1);
+    if (n_str > 0) issue_until(one_slot ? 1 : std::min(ahead, n_str));
     size_t si = 0;
     for (int32_t i = 0; i < n_layers; ++i) {
-        const bool st = si < streamed.size() && streamed[si] == i;
+        const bool st = si < n_str && streamed[si] == i;
         int32_t s = -1;
         if (st) {
             s = slot_of[i];
             // a layer never executes before its parameters have arrived
             ops->push_back(mk(QC, DL_OP_WAIT, DL_EV_DMA_DONE, s, module, i));
             ++si;
-            if (!one_slot) issue_following(si);
+            if (!one_slot) issue_until(si + ahead);
         }
         ops->push_back(mk(QC, DL_OP_EXEC, -1, s, module, i));
         if (st) {
             ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_COMPUTE_DONE, s, module, i));
             book->compute_recorded[s] = true;
-            if (one_slot) issue_following(si);
+            if (one_slot) issue_until(si + 1);
         }
     }
     ops->push_back(mk(QC, DL_OP_RECORD, DL_EV_PASS_DONE, -1, module, n_layers - 1));
@@ -455,7 +487,7 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
                     int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms) {
     if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
-    if (n_slots != 1 && n_slots != 2) return DL_ERR_INVALID_ARG;
+    if (n_slots < 1 || n_slots > dl::kMaxSlots) return DL_ERR_INVALID_ARG;
     if (mode != DL_MODE_PIPELINED && mode != DL_MODE_SEQUENTIAL) return DL_ERR_INVALID_ARG;
     if (n > 0 && !pass_start[0]) return DL_ERR_INVALID_ARG;
     // Replays the very schedule a pass enqueues (build_pass) on two in-order queues.
@@ -470,8 +502,8 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
     dl::SlotBook book;
     book.n_slots = n_slots;
     double t[2] = {0, 0};                       // queue clocks: [0] compute, [1] copy
-    double ev_dma[2] = {0, 0}, ev_comp[2] = {0, 0}, ev_pass = 0;
-    double copy_start[2] = {0, 0}, copy_dur[2] = {0, 0};
+    double ev_dma[dl::kMaxSlots] = {0, 0, 0, 0}, ev_comp[dl::kMaxSlots] = {0, 0, 0, 0}, ev_pass = 0;
+    double copy_start[dl::kMaxSlots] = {0, 0, 0, 0}, copy_dur[dl::kMaxSlots] = {0, 0, 0, 0};
     double exposed = 0, dma_sum = 0;
     bool idled = false;                          // the compute queue waited for the copy of the next layer
     std::vector<dl_trace_op> ops;
@@ -505,11 +537,11 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
                     break;
                 case DL_OP_COPY: {
                     int32_t jj = j;
-                    if (o.flags & DL_OPF_NEXT_PASS) {
-                        // prefetch for the next pass: takes that pass's copy time when it runs the same module
-                        if (p + 1 < passes.size() && passes[p + 1].module == P.module &&
-                            o.layer < passes[p + 1].j1 - passes[p + 1].j0)
-                            jj = passes[p + 1].j0 + o.layer;
+                    if (o.flags > 0) {
+                        // copied ahead for a later pass: takes that pass's copy time when it runs the same module
+                        const size_t pp = p + size_t(o.flags);
+                        if (pp < passes.size() && passes[pp].module == P.module && o.layer < passes[pp].j1 - passes[pp].j0)
+                            jj = passes[pp].j0 + o.layer;
                     }
                     copy_start[o.slot] = t[q];
                     copy_dur[o.slot] = c_dma_ms[jj];

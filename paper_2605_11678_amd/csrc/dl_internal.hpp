@@ -28,6 +28,8 @@ public:
     uint64_t capacity() const { return cap_; }
     bool is_set() const { return cap_ > 0; }
     uint64_t size_of(uint64_t off) const;
+    // forget a peak reached by temporaries (profiling): the peak becomes max(peak_before, current use)
+    void restore_peak(uint64_t peak_before) { peak_ = peak_before > used_ ? peak_before : used_; }
 private:
     struct Block { uint64_t off, size; bool used; };
     std::vector<Block> blocks_;
@@ -76,14 +78,18 @@ struct KvLayout {
 KvLayout make_kv(const dl_module_desc& d);
 
 // ---- the schedule of one pass as data (Sec. IV-C(ii)) ----
+constexpr int32_t kMaxSlots = 4;
 struct SlotBook {
     // persistent across passes
-    int32_t n_slots = 2;                  // 1 or 2 device slots
+    int32_t n_slots = 2;                  // device slots, 1 .. kMaxSlots
     uint64_t ordinal = 0;                 // count of copies issued so far; slot = ordinal % n_slots
-    bool dma_recorded[2] = {false, false};
-    bool compute_recorded[2] = {false, false};
+    bool dma_recorded[kMaxSlots] = {false, false, false, false};
+    bool compute_recorded[kMaxSlots] = {false, false, false, false};
     bool pass_recorded = false;
-    int32_t pending_module = -1, pending_layer = -1, pending_slot = -1;   // a prefetched, not yet consumed copy
+    // copies issued ahead for the first streamed layers of coming passes and not consumed yet, oldest first
+    int32_t n_pending = 0;
+    int32_t pending_module = -1;
+    int32_t pending_layer[kMaxSlots] = {-1, -1, -1, -1}, pending_slot[kMaxSlots] = {-1, -1, -1, -1};
 };
 // Appends the ops of one pass over a module to `ops`.  resident[i] != 0: layer i executes from its
 // resident copy.  force_stream_all: every layer is copied (profiling).  Updates `book`.

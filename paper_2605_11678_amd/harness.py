@@ -124,23 +124,23 @@ class VlaPipeline:
 
     def __init__(self, eng: Engine, vit: CFG.ModuleConfig, dec: CFG.ModuleConfig, act: CFG.ModuleConfig,
                  n_patches: int, n_text: int, n_actions: int = 64, pool: int = 4, out_dim: int = 3,
-                 seeds=(11, 12, 13, 14, 15, 16)):
+                 seeds=(11, 12, 13, 14, 15), matrix_gain: float = 0.0):
+        """matrix_gain: see configs.make_layer_weights (0 = the stated N(0, 0.02) recipe)."""
         self.eng, self.vit, self.dec, self.act = eng, vit, dec, act
         self.n_patches, self.n_text, self.n_actions, self.pool = n_patches, n_text, n_actions, pool
         self.n_vis = n_patches // pool
         self.n_prefill = self.n_vis + n_text
         ctx = eng.ctx
-        self.m_vit = eng.add_module(vit, max_tokens=n_patches)
-        self.m_dec = eng.add_module(dec, max_tokens=self.n_prefill)
-        self.m_act = eng.add_module(act, max_tokens=n_actions, max_ctx=self.n_prefill)
-        self.proj_w = CFG.make_mlp(vit.d_model, dec.d_model, dec.d_model, seeds[0])
-        self.out_w = CFG.make_mlp(act.d_model, 0, out_dim, seeds[1])
+        gen = (lambda c: (lambda l: CFG.make_layer_weights(c, l, matrix_gain)))
+        self.m_vit = eng.add_module(vit, max_tokens=n_patches, weights=gen(vit))
+        self.m_dec = eng.add_module(dec, max_tokens=self.n_prefill, weights=gen(dec))
+        self.m_act = eng.add_module(act, max_tokens=n_actions, max_ctx=self.n_prefill, weights=gen(act))
+        inp = CFG.make_pipeline_inputs(vit, dec, act, n_patches, n_text, n_actions, out_dim, seeds, matrix_gain)
+        self.proj_w, self.out_w = inp["proj_w"], inp["out_w"]
         self.mlp_proj = ctx.mlp_create(vit.d_model, dec.d_model, dec.d_model, *self.proj_w, max_tokens=n_patches)
         self.mlp_out = ctx.mlp_create(act.d_model, 0, out_dim, None, None, self.out_w[2], self.out_w[3],
                                       max_tokens=n_actions)
-        self.patches = CFG.make_tokens(n_patches, vit.d_model, seed=seeds[2])
-        self.text = CFG.make_tokens(n_text, dec.d_model, seed=seeds[3])
-        self.a0 = CFG.make_tokens(n_actions, act.d_model, seed=seeds[4])
+        self.patches, self.text, self.a0 = inp["patches"], inp["text"], inp["a0"]
         A = eng.alloc_f32
         self.p_patch, self.v_patch = A(n_patches * vit.d_model)
         self.p_vit, self.v_vit = A(n_patches * vit.d_model)

@@ -1,68 +1,123 @@
 """GPU parity at the benchmark's full shapes, in the launch configuration bench.py times.
 
-The oracle cannot run 36 layers of the 8B-class stack in seconds, so full-size checks are of two kinds:
-(a) a few layers of the real shape against the oracle (every kernel runs at its real tile counts and grid),
-(b) properties that hold at any size on the whole stack: streamed, partially resident and fully resident
-    passes agree bit for bit (Table IX), and so do repeated passes."""
+(a) one layer of the 8B-class shape against the oracle run live (every kernel at its real tile counts and grid), once
+    as stated and once with the feed-forward zeroed so that the attention kernels are judged alone;
+(b) the full-depth stacks, the 27-layer encoder at 4096 tokens and the 36-layer decoder at 3072 tokens followed by 8
+    greedy steps through the 4096 x 32768 head, against oracle values stored by tests/golden/make_full_depth.py (a
+    script that calls only the oracle: the float64 oracle needs ~10 minutes per 36-layer pass), at sampled rows (every
+    61st / 83rd and the last, all columns), the maxima the error measures divide by taken over the whole output;
+(c) properties that hold at any size: streamed, partially resident and fully resident passes agree bit for bit
+    (Table IX), and so do repeated passes."""
+import json
+import os
+
 import numpy as np
 import pytest
 
-from oracle import forward as F
 from paper_2605_11678_amd import binding as B
 from paper_2605_11678_amd import configs as CFG
-from tests.gpu_common import GpuStack, oracle_cfg, rel_err
+from tests import parity_cases as PC
+from tests.gpu_common import GpuStack
 
 pytestmark = pytest.mark.gpu
-TOL = 2e-2
+GOLD_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 
-def test_vit_shape_two_layers_vs_oracle():
-    c = CFG.vit_encoder(n_layers=2)
-    T = 4096
-    x = CFG.make_tokens(T, c.d_model, seed=7)
-    g = GpuStack(c, max_tokens=T, cap_bytes=1 << 30)
+def golden():
+    with open(os.path.join(GOLD_DIR, "full_depth_meta.json")) as f:
+        meta = json.load(f)
+    return np.load(os.path.join(GOLD_DIR, "full_depth.npz")), meta
+
+
+def check_sampled(got, arrays, meta, key, what, contrib=True):
+    """Both error measures on the stored rows; the denominators are the stored maxima over the whole oracle output."""
+    rows = arrays[key + "_rows"]
+    err = float(np.max(np.abs(got[rows].astype(np.float64) - arrays[key + "_want"])))
+    s = err / meta[key]["max_abs"]
+    c = err / meta[key]["max_abs_contrib"] if contrib else 0.0
+    print("parity %s (%d sampled rows): stated %.3e (<= %.0e)  contrib %.3e (<= %.0e)" %
+          (what, len(rows), s, PC.TOL, c, PC.TOL_CONTRIB), flush=True)
+    assert s <= PC.TOL, (what, "stated", s)
+    assert c <= PC.TOL_CONTRIB, (what, "contrib", c)
+
+
+@pytest.mark.parametrize("name", ["dec8b_L1", "dec8b_L1_attn"])
+def test_decoder_8b_shape_one_layer_vs_oracle(name):
+    """3072-token prefill, then two single-token passes over the 3072-entry cache, oracle run live."""
+    case = PC.full_cases()[name]
+    x = case.x()
+    g = GpuStack(case.cfg, max_tokens=case.max_tokens, cap_bytes=3 << 30, weights=case.weights())
+    try:
+        want = PC.oracle_passes(case)
+        bits = None
+        for (p, t), w in zip(case.passes, want):
+            got = g.forward(x[p:p + t], p)
+            PC.check(got, w, x[p:p + t], "%s pos0=%d T=%d" % (name, p, t))
+            if p == 0:
+                bits = got.view(np.uint32).copy()
+        g.eng.ctx.set_residency(g.mid, [0])
+        assert np.array_equal(g.forward_bits(x[:case.passes[0][1]]), bits)
+    finally:
+        g.close()
+
+
+def test_vit_full_depth_vs_stored_oracle():
+    """27 layers, 4096 tokens, head dimension 72: streamed, against the stored oracle output; then k = 13 (Eq. 8
+    placement) and k = 27 reproduce the bits."""
+    arrays, meta = golden()
+    case = PC.full_cases()["vit_L27"]
+    x = case.x()
+    g = GpuStack(case.cfg, max_tokens=4096, cap_bytes=2 << 30, weights=case.weights())
     try:
         got = g.forward(x)
-        want = F.stack_forward(oracle_cfg(c), g.weights, x)
-        assert rel_err(got, want) <= TOL, rel_err(got, want)
+        check_sampled(got, arrays, meta, "vit_L27", "27-layer encoder T=4096")
         ref = got.view(np.uint32)
-        for res in ([0], [1], [0, 1]):
-            g.eng.ctx.set_residency(g.mid, res)
-            assert np.array_equal(g.forward_bits(x), ref)
+        for k in (13, 27):
+            g.eng.ctx.set_residency(g.mid, B.place_interleaved(27, k))
+            assert np.array_equal(g.forward_bits(x), ref), k
     finally:
         g.close()
 
 
-def test_decoder_8b_shape_one_layer_prefill_and_decode_vs_oracle():
-    c = CFG.decoder_8b(n_layers=1, max_seq=3136, vocab=0)
-    T = 3072
-    x = CFG.make_tokens(T + 2, c.d_model, seed=7)
-    g = GpuStack(c, max_tokens=T, cap_bytes=3 << 30)
+def test_decoder_8b_full_depth_prefill_greedy_and_bit_identity_under_16e9_cap():
+    """All 36 layers, 3072 tokens, 16e9-byte arena.  The prefill output (raw and final-normed) and 8 greedy steps
+    (token ids, the 32768 logits of every step, the hidden state after every step) against the stored oracle values;
+    k = 0, 18 (Eq. 8 placement), 36, sequential mode and a repeat agree bit for bit."""
+    arrays, meta = golden()
+    case = PC.full_cases()["dec8b_L36"]
+    c = case.cfg
+    gm = meta["greedy"]
+    head = CFG.make_head(c, seed=gm["head_seed"])
+    T, L, d = 3072, c.n_layers, c.d_model
+    x = case.x()
+    g = GpuStack(c, max_tokens=T, cap_bytes=16_000_000_000, weights=case.weights(), head=head)
     try:
-        kv = F.new_kv_cache(oracle_cfg(c))
-        want = F.stack_forward(oracle_cfg(c), g.weights, x[:T], 0, kv)
-        got = g.forward(x[:T])
-        assert rel_err(got, want) <= TOL, rel_err(got, want)
-        bits = got.view(np.uint32).copy()
-        for t in (T, T + 1):                      # single-token kernels over the 3072-entry cache
-            want1 = F.stack_forward(oracle_cfg(c), g.weights, x[t:t + 1], t, kv)
-            got1 = g.forward(x[t:t + 1], t)
-            assert rel_err(got1, want1) <= TOL, (t, rel_err(got1, want1))
-        g.eng.ctx.set_residency(g.mid, [0])
-        assert np.array_equal(g.forward_bits(x[:T]), bits)
-    finally:
-        g.close()
-
-
-def test_decoder_8b_full_stack_bit_identity_under_16e9_cap():
-    """All 36 layers, 3072 tokens, 16e9-byte arena: k = 0, 18 (Eq. 8 placement), 36 and a repeat."""
-    c = CFG.decoder_8b(vocab=0)
-    T, L = 3072, c.n_layers
-    x = CFG.make_tokens(T, c.d_model, seed=7)
-    g = GpuStack(c, max_tokens=T, cap_bytes=16_000_000_000)
-    try:
-        ref = g.forward_bits(x)
-        assert np.all(np.isfinite(ref.view(np.float32)))
+        got = g.forward(x)
+        check_sampled(got, arrays, meta, "dec8b_L36", "36-layer decoder prefill T=3072")
+        ref = got.view(np.uint32).copy()
+        g.eng.ctx.final_norm(g.mid, g.yp, g.np_, T)
+        fin = g.eng.download(g.nv[:T * d]).reshape(T, d)
+        check_sampled(fin, arrays, meta, "dec8b_L36_final", "36-layer decoder, final-normed hidden states", contrib=False)
+        # greedy steps, streamed (k = 0): ids identical, logits and hidden states within tolerance
+        toks, logits, hs = arrays["greedy_tokens"], arrays["greedy_logits"], arrays["greedy_hidden"]
+        E = B_bits_to_f32(head[CFG.R_EMBED])
+        h_ptr = g.yp + 4 * (T - 1) * d
+        lg = np.empty(c.vocab, np.float32)
+        worst_logit = 0.0
+        for s in range(gm["steps"]):
+            t = g.eng.ctx.logits_argmax(g.mid, h_ptr, lg)
+            e_logit = float(np.max(np.abs(lg.astype(np.float64) - logits[s])))
+            worst_logit = max(worst_logit, e_logit)
+            assert t == int(toks[s]), (s, t, int(toks[s]))
+            g.eng.ctx.embed_token(g.mid, t, g.xp)
+            g.eng.ctx.forward(g.mid, g.xp, g.yp, 1, T + s)
+            h = g.eng.download(g.yv[:d])
+            PC.check(h[None, :], hs[s][None, :].astype(np.float64), E[t][None, :], "greedy step %d (token %d, logit err %.2e)" % (s, t, e_logit))
+            h_ptr = g.yp
+        # integer ids are compared away from near-ties: the oracle's smallest top-1 / top-2 gap dominates the logit error
+        assert min(gm["margins"]) > 10 * worst_logit, (gm["margins"], worst_logit)
+        print("logits: worst abs error %.3e, smallest oracle margin %.3f" % (worst_logit, min(gm["margins"])), flush=True)
+        # residency never changes a bit
         for k in (18, 36, 0):
             g.eng.ctx.set_residency(g.mid, B.place_interleaved(L, k))
             assert np.array_equal(g.forward_bits(x), ref), k
@@ -75,3 +130,7 @@ def test_decoder_8b_full_stack_bit_identity_under_16e9_cap():
         assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED
     finally:
         g.close()
+
+
+def B_bits_to_f32(bits):
+    return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)

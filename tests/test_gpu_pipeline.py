@@ -8,39 +8,30 @@ from oracle import pipeline as PL
 from paper_2605_11678_amd import binding as B
 from paper_2605_11678_amd import configs as CFG
 from paper_2605_11678_amd.harness import Engine, VlaPipeline
-from tests.gpu_common import rel_err
+from tests import parity_cases as PC
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2
 
 
-def small_modules():
-    vit = CFG.ModuleConfig("vit_s", 3, 144, 2, 2, 72, 536, CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, seed_base=6100)
-    dec = CFG.ModuleConfig("dec_s", 3, 512, 8, 2, 64, 1024, CFG.NORM_RMS, CFG.ACT_SWIGLU, 0, 1, 1e6, max_seq=160,
-                           seed_base=6200, vocab=512)
-    act = CFG.ModuleConfig("act_s", 2, 256, 2, 2, 128, 512, CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, d_ctx=512,
-                           seed_base=6300)
-    return vit, dec, act
-
-
 def test_vla_pipeline_small_vs_oracle_and_residency_invariance():
-    vit, dec, act = small_modules()
-    n_decode = 4
+    vit, dec, act = PC.pipe_small_modules()
+    P = PC.PIPE_SMALL
+    n_decode = P["n_decode"]
     eng = Engine(1 << 30, device=0)
     try:
-        pipe = VlaPipeline(eng, vit, dec, act, n_patches=256, n_text=40, n_actions=64)
-        head = CFG.make_head(dec)
+        pipe = VlaPipeline(eng, vit, dec, act, n_patches=P["n_patches"], n_text=P["n_text"], n_actions=P["n_actions"],
+                           matrix_gain=P["gain"])
         pipe.run(n_decode)
         got = pipe.results(n_decode)
-        want = PL.vla_pipeline(vit.as_dict(), lambda l: CFG.make_layer_weights(vit, l), pipe.proj_w,
-                               dec.as_dict(), lambda l: CFG.make_layer_weights(dec, l), head,
-                               act.as_dict(), lambda l: CFG.make_layer_weights(act, l), (pipe.out_w[2], pipe.out_w[3]),
-                               pipe.patches, pipe.text, pipe.a0, n_decode)
-        assert rel_err(got["hidden_ctx"], want["hidden_ctx"]) <= TOL
-        assert rel_err(got["actions"], want["actions"]) <= TOL, rel_err(got["actions"], want["actions"])
-        assert rel_err(got["trajectory"], want["trajectory"]) <= TOL
+        want = PC.pipeline_oracle()
+        # each measure in units of its bound (tests/test_parity_discriminates.py shows that removing any sub-block
+        # of any of the three stacks from the oracle moves one of them past 10)
+        m = PC.pipeline_measures(got, want)
+        print("pipeline measures / bound:", {k: "%.3f" % v for k, v in m.items()}, flush=True)
+        assert max(m.values()) <= 1.0, m
         # integer ids are compared away from near-ties: with the default head seed (8) the oracle's smallest
-        # top-1/top-2 logit gap over the 4 steps is 0.10, far above the bf16-level logit error
+        # top-1/top-2 logit gap over the 4 steps must be far above the bf16-level logit error
         srt = np.sort(want["logits"], axis=1)
         assert float(np.min(srt[:, -1] - srt[:, -2])) > 0.05
         assert got["tokens"] == want["tokens"], (got["tokens"], want["tokens"])

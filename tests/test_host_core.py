@@ -181,7 +181,7 @@ def _ops_for_des(trace, dma, exe):
     return ops
 
 
-@pytest.mark.parametrize("n_slots", [2, 1])
+@pytest.mark.parametrize("n_slots", [2, 1, 3, 4])
 @pytest.mark.parametrize("wrap", [0, 1])
 def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap, n_slots):
     """The schedule dl_forward enqueues (recorded by a host-only context) is replayed on an independent
@@ -212,7 +212,7 @@ def test_slot_protocol_on_recorded_schedule_all_residency_sets(wrap, n_slots):
             times = simulate(ops)
             # safety: pair every streamed exec with the last copy into its slot
             last_copy = {}
-            busy_until = {0: 0.0, 1: 0.0}
+            busy_until = {s: 0.0 for s in range(4)}
             for (q, op), (t0, t1) in zip(ops, times):
                 if op[0] == "copy":
                     s = op[2]["slot"]
@@ -356,9 +356,15 @@ def test_one_slot_gives_a_layer_back_and_only_overlaps_resident_layers():
     assert P.timeline(inv, n_slots=1)["total"] == pytest.approx(want)
     eng.ctx.set_slot_count(2)
     assert eng.ctx.arena_stats()["used"] == used2
-    with pytest.raises(B.DLError) as e:
-        eng.ctx.set_slot_count(3)
-    assert e.value.code == B.DL_ERR_INVALID_ARG
+    # three and four slots: one more layer of memory each (deeper prefetch)
+    for n in (3, 4):
+        eng.ctx.set_slot_count(n)
+        assert eng.ctx.arena_stats()["used"] == used2 + (n - 2) * packed
+    eng.ctx.set_slot_count(2)
+    for bad in (0, 5):
+        with pytest.raises(B.DLError) as e:
+            eng.ctx.set_slot_count(bad)
+        assert e.value.code == B.DL_ERR_INVALID_ARG
     eng.close()
 
 
@@ -499,3 +505,97 @@ def test_plan_follows_benefit_ranking():
     assert B.plan(n_layers, sizes, b3, 10 * sizes[1]) == [0, 10, 0]
     # after all VLM layers, the expert layers come next (0.298 > 0.031)
     assert B.plan(n_layers, sizes, b3, 36 * sizes[1] + 5 * sizes[2] + 10) == [0, 36, 5]
+
+
+def test_fits_by_bytes_means_accepted():
+    """Sec. IV-D's budget as the library takes it: whatever is resident now, a residency whose resident copies plus
+    the slots of the largest layer that still streams sum to at most dl_residency_budget is accepted (slots and
+    resident copies are placed again when first-fit leaves holes), and one that needs a byte more is refused whole."""
+    rnd = random.Random(11)
+    cfgs = [small_cfg(5), small_cfg(3, d_ff=1536), small_cfg(6, d_ff=512)]
+    probe = Engine(1 << 32, device=-1)
+    rng = np.random.default_rng(3)
+    sizes = []
+    for c in cfgs:
+        m = probe.add_module(c, 16, weights=tiny_weights(c, rng))
+        sizes.append(probe.ctx.module_layer_bytes(m)[0])
+    top_stack = (1 << 32) - probe.ctx.residency_budget()
+    probe.close()
+    Ls = [c.n_layers for c in cfgs]
+    full = sum(L * s for L, s in zip(Ls, sizes))
+    for n_slots in (2, 1, 3):
+        cap = top_stack + full * 2 // 3 + 256 * rnd.randint(0, 4000)     # room for about two thirds of all layers
+        eng = Engine(cap, device=-1)
+        rng = np.random.default_rng(3)
+        mods = [eng.add_module(c, 16, weights=tiny_weights(c, rng)) for c in cfgs]
+        eng.ctx.set_slot_count(n_slots)
+        xp = eng.ctx.arena_alloc(4096)                                    # a caller block joins the top stack
+        budget = eng.ctx.residency_budget()
+        assert budget == cap // 256 * 256 - top_stack - 4096
+        cur = [[] for _ in cfgs]
+
+        def need(res):
+            stream = [sizes[m] for m in range(3) if len(res[m]) < Ls[m]]
+            return sum(len(res[m]) * sizes[m] for m in range(3)) + (n_slots * max(stream) if stream else 0)
+        accepted = refused = 0
+        for step in range(300):
+            m = rnd.randrange(3)
+            new = sorted(rnd.sample(range(Ls[m]), rnd.randint(0, Ls[m])))
+            trial = list(cur)
+            trial[m] = new
+            if need(trial) <= budget:
+                eng.ctx.set_residency(mods[m], new)
+                cur = trial
+                accepted += 1
+            else:
+                used = eng.ctx.arena_stats()["used"]
+                with pytest.raises(B.DLError) as e:
+                    eng.ctx.set_residency(mods[m], new)
+                assert e.value.code == B.DL_ERR_BUDGET_EXCEEDED
+                assert eng.ctx.arena_stats()["used"] == used
+                refused += 1
+            assert [eng.ctx.get_residency(mods[i], Ls[i]) for i in range(3)] == cur
+            assert eng.ctx.arena_stats()["used"] == top_stack + 4096 + need(cur)
+            assert eng.ctx.residency_budget() == budget                   # nothing movable ever strands the top stack
+        assert accepted > 50 and refused > 20, (accepted, refused)
+        # the tightest fit: fill the budget to the last layer
+        for m in range(3):
+            eng.ctx.set_residency(mods[m], [])
+        k = B.plan_shared_slots(Ls, sizes, [[1.0, 1.0, 0.5]] * 3, budget, n_slots)
+        for m in range(3):
+            eng.ctx.set_residency(mods[m], B.place_interleaved(Ls[m], k[m]))
+        eng.ctx.arena_free(xp)
+        eng.close()
+
+
+def test_head_needs_the_final_norm_bias_of_a_layernorm_module():
+    """A LayerNorm module whose final-norm bias was never set must be refused by the greedy head (the kernel would
+    read it), as dl_final_norm refuses it."""
+    c = CFG.ModuleConfig("ln_head", 1, 64, 2, 2, 32, 64, CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, vocab=32)
+    eng = Engine(1 << 26, device=-1)
+    head = CFG.make_head(c)
+    del head[CFG.R_FINAL_NORM_B]
+    rng = np.random.default_rng(0)
+    mid = eng.add_module(c, 4, weights=tiny_weights(c, rng), head=head)
+    for call in (lambda: eng.ctx.logits_argmax(mid, 0), lambda: eng.ctx.greedy_step(mid, 0, 0, 0),
+                 lambda: eng.ctx.final_norm(mid, 0, 0, 1)):
+        with pytest.raises(B.DLError) as e:
+            call()
+        assert e.value.code == B.DL_ERR_BAD_STATE
+    eng.ctx.set_resident_tensor(mid, CFG.R_FINAL_NORM_B, np.zeros(64, np.uint16))
+    eng.ctx.logits_argmax(mid, 0)
+    eng.close()
+
+
+def test_kv_cache_module_limits_query_heads_per_kv_head():
+    """The single-token attention kernel puts the query heads of one KV head on the 32 columns of an MFMA tile."""
+    eng = Engine(1 << 26, device=-1)
+    wide = small_cfg(1, n_q_heads=64, n_kv_heads=1, d_head=8, d_model=64)
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.module_create(**desc_fields(wide, 8))
+    assert e.value.code == B.DL_ERR_INVALID_ARG and "32 query heads" in str(e.value)
+    wide.max_seq = 0                                   # without a cache (prefill kernels only) the shape is fine
+    eng.ctx.module_create(**desc_fields(wide, 8))
+    ok = small_cfg(1, n_q_heads=32, n_kv_heads=1, d_head=8, d_model=64)
+    eng.ctx.module_create(**desc_fields(ok, 8))
+    eng.close()
