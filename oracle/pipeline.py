@@ -15,7 +15,9 @@ per Euler step (10 steps, 64 waypoints x 3).  What the paper leaves open is fixe
   * velocity = output of the action stack; Euler: a <- a + (1/10) * velocity;
   * trajectory = a W_out^T + b_out.
 Pins (tests/test_oracle_forward.py::test_pipeline_*): hand-computed pooling / embedding values,
-Euler against the closed form for a linear velocity field, scalar re-derivation of the MLP.
+Euler against the closed form for a linear velocity field, scalar re-derivation of the MLP, and the
+composition of the five stages (which states feed what, in which order) re-derived with scalar loops on a
+hand-sized case.
 """
 import math
 

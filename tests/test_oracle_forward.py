@@ -383,3 +383,74 @@ def test_pipeline_euler_closed_form():
     for s in range(10):
         want = want + 1.1 ** (9 - s) * 0.1 * PL.time_embedding(s / 10, c["d_model"])[None, :]
     assert got == pytest.approx(want, rel=1e-12)
+
+
+def test_pipeline_wiring_against_scalar_loops():
+    """The composition of the five stages, re-derived with scalar loops from the written reading (Sec. II-A names the
+    stages; the arithmetic between them is this build's reading): encoder -> per-token 2-layer GELU MLP -> mean of
+    every `pool` consecutive tokens -> [visual tokens ; text embeddings] -> causal decoder with a KV cache ->
+    FINAL-NORMED hidden states of the prefill positions become the cross-attention context -> greedy steps from the
+    last prefill row (un-normed state into the head, which normalises itself) -> Euler loop a += v(a + e(s/n))/n with
+    the context fixed -> linear trajectory head.  Swapping two stages, pooling before the MLP, feeding un-normed
+    states to the cross-attention or the embedding instead of the hidden state to the next step all change these
+    numbers."""
+    from oracle import pipeline as PL
+    rng = np.random.default_rng(21)
+    vit = cfg_encoder(n_layers=1, d_model=4, n_q_heads=2, d_head=2, d_ff=6)
+    vit["n_kv_heads"] = 2
+    dec = cfg_decoder(n_layers=1, d_model=6, n_q_heads=2, n_kv_heads=1, d_head=2, d_ff=8, max_seq=12)
+    act = cfg_encoder(n_layers=1, d_model=4, n_q_heads=2, d_head=2, d_ff=6, d_ctx=6)
+    act["n_kv_heads"] = 2
+    Wv, Wd, Wa = rand_weights(vit, rng), rand_weights(dec, rng), rand_weights(act, rng)
+    proj = (0.5 * rng.standard_normal((6, 4)), 0.1 * rng.standard_normal(6), 0.5 * rng.standard_normal((6, 6)),
+            0.1 * rng.standard_normal(6))
+    vocab = 5
+    head = {0: rng.standard_normal((vocab, 6)), 1: rng.standard_normal((vocab, 6)), 2: 1 + 0.1 * rng.standard_normal(6)}
+    out_proj = (rng.standard_normal((3, 4)), rng.standard_normal(3))
+    patches, text, a0 = rng.standard_normal((4, 4)), rng.standard_normal((2, 6)), rng.standard_normal((3, 4))
+    n_decode, n_euler, pool = 2, 3, 2
+    got = PL.vla_pipeline(vit, lambda l: Wv, proj, dec, lambda l: Wd, head, act, lambda l: Wa, out_proj,
+                          patches, text, a0, n_decode, n_euler=n_euler, pool=pool)
+
+    gelu = lambda u: 0.5 * u * (1 + math.tanh(math.sqrt(2 / math.pi) * (u + 0.044715 * u ** 3)))
+    # stage 1: encoder
+    v, _, _ = b_layer(vit, Wv, patches.tolist())
+    # stage 2: merger = MLP per token, THEN the mean of `pool` consecutive tokens
+    p = b_linear([[gelu(u) for u in row] for row in b_linear(v, proj[0].tolist(), proj[1].tolist())],
+                 proj[2].tolist(), proj[3].tolist())
+    vis = [[sum(p[t * pool + j][i] for j in range(pool)) / pool for i in range(6)] for t in range(len(p) // pool)]
+    # stage 3: prefill over [visual ; text]
+    seq = vis + text.tolist()
+    h, k_hist, v_hist = b_layer(dec, Wd, seq)
+    g = head[2].tolist()
+    rms = lambda row: [x / math.sqrt(sum(y * y for y in row) / len(row) + dec["norm_eps"]) * g[i] for i, x in enumerate(row)]
+    hctx = [rms(row) for row in h]
+    assert got["hidden_ctx"] == pytest.approx(np.array(hctx), rel=1e-10)
+    # stage 4: greedy steps
+    toks, h_last, pos = [], h[-1], len(seq)
+    for s in range(n_decode):
+        n = rms(h_last)
+        logits = [sum(n[i] * head[1][o][i] for i in range(6)) for o in range(vocab)]
+        assert got["logits"][s] == pytest.approx(logits, rel=1e-10)
+        tok = max(range(vocab), key=lambda o: (logits[o], -o))
+        toks.append(tok)
+        y, k_hist, v_hist = b_layer(dec, Wd, [head[0][tok].tolist()], pos0=pos, k_hist=k_hist, v_hist=v_hist)
+        h_last, pos = y[0], pos + 1
+    assert got["tokens"] == toks
+    # stage 5: Euler steps of the action stack, cross-attending to the final-normed prefill states
+    a = a0.tolist()
+    half = 2
+    for s in range(n_euler):
+        t = s / n_euler
+        e = [math.sin(1000.0 * t * 10000.0 ** (-j / half)) for j in range(half)] + \
+            [math.cos(1000.0 * t * 10000.0 ** (-j / half)) for j in range(half)]
+        vel, _, _ = b_layer(act, Wa, [[a[r][i] + e[i] for i in range(4)] for r in range(3)], ctx=hctx)
+        a = [[a[r][i] + vel[r][i] / n_euler for i in range(4)] for r in range(3)]
+    assert got["actions"] == pytest.approx(np.array(a), rel=1e-9)
+    traj = [[sum(a[r][i] * out_proj[0][o][i] for i in range(4)) + out_proj[1][o] for o in range(3)] for r in range(3)]
+    assert got["trajectory"] == pytest.approx(np.array(traj), rel=1e-9)
+    # and the wiring matters on this case: un-normed states as context, or pooling before the MLP, move the result
+    wrong_ctx = PL.euler_actions(act, lambda l: Wa, a0, np.array(h), n_euler)
+    assert np.max(np.abs(wrong_ctx - got["actions"])) > 1e-3
+    wrong_merge = PL.mlp(PL.mean_pool(np.array(v), pool), *proj)
+    assert np.max(np.abs(wrong_merge - np.array(vis))) > 1e-3
