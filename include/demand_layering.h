@@ -98,6 +98,7 @@ typedef struct {
  * and for checking the slot protocol without a GPU.  *out is owned by the library. */
 int32_t dl_create(dl_ctx** out, int32_t device);
 int32_t dl_destroy(dl_ctx* ctx);
+/* ctx == NULL: the message of the last failed call that takes no context, on the calling thread. */
 const char* dl_last_error(const dl_ctx* ctx);
 
 /* The device-memory budget.  dev_base: device pointer to a block of `bytes` bytes the caller
@@ -205,6 +206,23 @@ int32_t dl_logits_argmax(dl_ctx* ctx, int32_t module, const void* h_dev, int32_t
  * token_dev: device int32[1]. */
 int32_t dl_greedy_step(dl_ctx* ctx, int32_t module, const void* h_dev, int32_t* token_dev, void* x_dev);
 int32_t dl_sync(dl_ctx* ctx);
+
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc, or callers that hold the head's tensors in device memory of their own and have no context or arena.
+ * The greedy step of dl_greedy_step on plain device pointers: logits = FinalNorm(h) * W_head^T in fp32, token = lowest
+ * index of the maximum, x_dev = E[token]; the same two kernels, enqueued on `stream` (a hipStream_t of `device`, which
+ * is made current), no host synchronisation, no context touched.  The logits of the step live in a static device
+ * array of the library (one per GPU, 131072 floats + 256 bytes, held until the process ends); the call allocates
+ * nothing, creates no event, and records nothing a graph capture could not hold.
+ * h_dev: device fp32 [d_model]; head_dev, embed_dev: device BF16 [vocab, d_model] (embed_dev and x_dev may both be
+ * NULL: token only); norm_g_dev / norm_b_dev: device BF16 [d_model] (norm_b_dev only for DL_NORM_LN);
+ * token_dev: device int32[1]; x_dev: device fp32 [d_model].  d_model % 8 == 0, <= 16384; vocab <= 131072.
+ * DL_ERR_INVALID_ARG beyond these limits or with a missing pointer, DL_ERR_DEVICE if the launch fails; the message is
+ * read with dl_last_error(NULL) on the same thread.  All calls on one GPU share that GPU's array: calls that overlap
+ * in time on one GPU (different streams, or graphs replayed concurrently) race on it. */
+int32_t dl_greedy_step_static(int32_t device, void* stream, const void* h_dev, const void* head_dev, const void* embed_dev,
+                              const void* norm_g_dev, const void* norm_b_dev, int32_t norm, float norm_eps,
+                              int32_t d_model, int32_t vocab, int32_t* token_dev, void* x_dev);
 
 /* ---- always-resident dense parts between the layer stacks (Sec. II-A patch merger, output heads; Sec. IV-D:
  *      non-layer components stay resident in every configuration) ------------------------------------------ */

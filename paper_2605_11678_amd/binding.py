@@ -76,6 +76,7 @@ SIGNATURES = {
     "dl_arena_free": (_i32, [_p, _p]),
     "dl_arena_stats": (_i32, [_p, _PU64, _PU64, _PU64]),
     "dl_residency_budget": (_i32, [_p, _PU64]),
+    "dl_greedy_step_static": (_i32, [_i32, _p, _p, _p, _p, _p, _p, _i32, C.c_float, _i32, _i32, _p, _p]),
     "dl_set_streams": (_i32, [_p, _p, _p]),
     "dl_module_create": (_i32, [_p, C.POINTER(dl_module_desc), _PI32]),
     "dl_layer_set_tensor": (_i32, [_p, _i32, _i32, _i32, _p, _u64]),
@@ -352,6 +353,16 @@ class Context:
 
 
 # ---- pure host functions (no context) ----
+def greedy_step_static(device, stream, h_ptr, head_ptr, embed_ptr, norm_g_ptr, norm_b_ptr, norm, norm_eps, d_model, vocab,
+                       token_dev_ptr, x_ptr):
+    """dl_greedy_step_static: the greedy head on plain device pointers; allocates nothing."""
+    rc = lib().dl_greedy_step_static(int(device), _p(stream), _p(h_ptr), _p(head_ptr), _p(embed_ptr), _p(norm_g_ptr),
+                                     _p(norm_b_ptr), int(norm), float(norm_eps), int(d_model), int(vocab),
+                                     _p(token_dev_ptr), _p(x_ptr))
+    if rc != DL_OK:
+        raise DLError(rc, lib().dl_last_error(None).decode())
+
+
 def place_interleaved(n_layers, k):
     out = (_i32 * max(k, 1))()
     rc = lib().dl_place_interleaved(n_layers, k, out)

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -15,7 +16,32 @@
 
 using dl::PackLayout;
 
+// Scratch of dl_greedy_step_static (the logits of one step and the chosen token): device memory that exists once per
+// GPU for the life of the process, so that the call never allocates.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address kernels are given is looked up once per device (static_scratch_ptr below).
+constexpr int32_t kStaticMaxVocab = 131072;
+constexpr size_t kStaticScratchBytes = size_t(kStaticMaxVocab) * 4 + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kStaticMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kStaticMaxDevices] = {};
+thread_local std::string g_static_err;     // message of the last failed context-free call on this thread
+
+// Device address of `scratch` on `device`, which must be the current device.  Looked up on first use per device.
+hipError_t static_scratch_ptr(int32_t device, void** out) {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_static_ptr[device] = p;
+    }
+    *out = g_static_ptr[device];
+    return hipSuccess;
+}
 
 struct Module {
     dl_module_desc d{};
@@ -639,6 +665,10 @@ int32_t dl_create(dl_ctx** out, int32_t device) {
         if (hipGetDeviceCount(&n) != hipSuccess || device >= n) return DL_ERR_DEVICE;
         if (hipSetDevice(device) != hipSuccess) return DL_ERR_DEVICE;
     }
+    if (device >= 0 && device < kStaticMaxDevices) {
+        void* p = nullptr;                        // set-up time: resolve the static scratch of this device once
+        if (static_scratch_ptr(device, &p) != hipSuccess) return DL_ERR_DEVICE;
+    }
     dl_ctx* c = new dl_ctx();
     c->device = device;
     *out = c;
@@ -672,7 +702,7 @@ int32_t dl_destroy(dl_ctx* c) {
     return DL_OK;
 }
 
-const char* dl_last_error(const dl_ctx* c) { return c ? c->err.c_str() : "null context"; }
+const char* dl_last_error(const dl_ctx* c) { return c ? c->err.c_str() : g_static_err.c_str(); }
 
 int32_t dl_set_arena(dl_ctx* c, void* dev_base, uint64_t bytes) {
     int32_t rc = enter(c);
@@ -994,6 +1024,44 @@ int32_t dl_greedy_step(dl_ctx* c, int32_t module, const void* h, int32_t* token_
     if (M && M->finalized && !M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
     if (on_gpu(c) && !x_dev) return fail(c, DL_ERR_INVALID_ARG, "null x_dev");
     return head_common(c, M, h, token_dev, static_cast<float*>(x_dev));
+}
+
+int32_t dl_greedy_step_static(int32_t device, void* stream, const void* h_dev, const void* head_dev, const void* embed_dev,
+                              const void* norm_g_dev, const void* norm_b_dev, int32_t norm, float norm_eps,
+                              int32_t d_model, int32_t vocab, int32_t* token_dev, void* x_dev) {
+    auto bad = [&](int32_t code, const std::string& msg) { g_static_err = msg; return code; };
+    if (device < 0 || device >= kStaticMaxDevices) return bad(DL_ERR_INVALID_ARG, "device ordinal outside [0, 64)");
+    if (vocab < 1 || vocab > kStaticMaxVocab) {
+        char buf[128];
+        snprintf(buf, sizeof buf, "vocab %d outside [1, %d]: the static scratch holds at most %d logits", vocab, kStaticMaxVocab, kStaticMaxVocab);
+        return bad(DL_ERR_INVALID_ARG, buf);
+    }
+    if (d_model < 8 || d_model % 8 || d_model > 16384) return bad(DL_ERR_INVALID_ARG, "d_model must be a multiple of 8 in [8, 16384]");
+    if (norm != DL_NORM_RMS && norm != DL_NORM_LN) return bad(DL_ERR_INVALID_ARG, "unknown norm");
+    if (!(norm_eps >= 0)) return bad(DL_ERR_INVALID_ARG, "norm_eps < 0");
+    if (!h_dev || !head_dev || !norm_g_dev || !token_dev || (norm == DL_NORM_LN && !norm_b_dev))
+        return bad(DL_ERR_INVALID_ARG, "null device pointer");
+    if ((x_dev == nullptr) != (embed_dev == nullptr)) return bad(DL_ERR_INVALID_ARG, "x_dev and embed_dev go together");
+    hipError_t e = hipSetDevice(device);
+    void* sp = nullptr;
+    if (e == hipSuccess) e = static_scratch_ptr(device, &sp);
+    if (e != hipSuccess) return bad(DL_ERR_DEVICE, std::string("static scratch of the device: ") + hipGetErrorString(e));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // every logit of this call is written before the argmax reads it: nothing in the scratch has to start at zero,
+    // and what a larger earlier call left beyond `vocab` is never read
+    float* logits = static_cast<float*>(sp);
+    int32_t* tok = reinterpret_cast<int32_t*>(static_cast<unsigned char*>(sp) + size_t(kStaticMaxVocab) * 4);
+    dlk::GemvArgs g{nullptr, static_cast<const bf16_t*>(head_dev), d_model, nullptr, logits, nullptr, vocab, d_model, dlk::EPI_F32};
+    g.norm_x = static_cast<const float*>(h_dev);
+    g.norm_g = static_cast<const bf16_t*>(norm_g_dev);
+    g.norm_b = norm == DL_NORM_LN ? static_cast<const bf16_t*>(norm_b_dev) : nullptr;
+    g.norm_kind = norm;
+    g.norm_eps = norm_eps;
+    dlk::gemv(g, st);
+    dlk::argmax_f32(logits, vocab, tok, token_dev, static_cast<const bf16_t*>(embed_dev), d_model, static_cast<float*>(x_dev), st);
+    e = hipGetLastError();
+    if (e != hipSuccess) return bad(DL_ERR_DEVICE, std::string("launch failed: ") + hipGetErrorString(e));
+    return DL_OK;
 }
 
 int32_t dl_mlp_create(dl_ctx* c, int32_t d_in, int32_t d_hidden, int32_t d_out, const void* w1, const void* b1,
