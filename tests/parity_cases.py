@@ -163,6 +163,11 @@ CASES = [
     Case("gqa_dh64", _gqa_small(64), GQA_PASSES, 23),
     Case("gqa_dh128", _gqa_small(128), GQA_PASSES, 23),
     Case("gqa_nocache", _gqa_small(64, max_seq=0), [(0, 130)], 43),
+    # edges: 32 query heads on ONE KV head (the most the single-token attention kernel's tile takes), head dimension 8,
+    # passes that end exactly at the cache's last position, a single context row
+    Case("gqa_group32_dh8", CFG.ModuleConfig("g32", 2, 256, 32, 1, 8, 512, CFG.NORM_RMS, CFG.ACT_SWIGLU, 0, 1, 1e4,
+                                             max_seq=72, seed_base=4400, vocab=0), [(0, 67), (67, 1), (68, 3), (71, 1)], 47),
+    Case("cross_one_context_row", _cross_small(2, 128), [(0, 5)], 31, n_ctx=1, ctx_seed=32),
     Case("cross_short", _cross_small(2, 128), [(0, 64)], 31, n_ctx=150, ctx_seed=32),
     Case("cross_split_ragged", _cross_small(2, 128), [(0, 64)], 31, n_ctx=700, ctx_seed=32),
     Case("cross_split_gqa", _cross_small(4, 64), [(0, 20)], 31, n_ctx=1100, ctx_seed=32),

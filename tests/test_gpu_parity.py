@@ -37,8 +37,8 @@ def test_tiny_decoder_prefill_parity_and_bit_identity():
         assert rel_err(got, want) <= TOL, rel_err(got, want)
         print("tiny decoder, final-normed hidden states: %.3e" % rel_err(got, want), flush=True)
         ref_bits = g.forward_bits(x)
-        # every residency set, both modes, both prefetch settings, two slots and one: identical bits (Table IX)
-        for n_slots in (2, 1):
+        # every residency set, both modes, both prefetch settings, one to four slots: identical bits (Table IX)
+        for n_slots in (2, 1, 3, 4):
             g.eng.ctx.set_residency(g.mid, [])
             g.eng.ctx.set_slot_count(n_slots)
             for mask in itertools.product([0, 1], repeat=c.n_layers):
