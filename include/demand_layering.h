@@ -242,6 +242,53 @@ int32_t dl_axpy(dl_ctx* ctx, void* y_dev, float alpha, const void* x_dev, uint64
  * e_i = sin(1000 t w_i) for i < d/2, cos(1000 t w_{i-d/2}) otherwise, w_j = 10000^(-j/(d/2)). */
 int32_t dl_add_time_embedding(dl_ctx* ctx, const void* x_dev, void* y_dev, float t_value, int32_t n_tokens, int32_t d);
 
+/* ---- the five-stage inference as one call (Sec. II-A: vision encoder, patch merger, prefill, decode, flow-matching
+ *      action generator with Euler steps) ---------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t m_vit, m_dec, m_act;   /* finalized modules: encoder; causal decoder with KV cache, head and embedding table;
+                                      action stack with d_ctx == decoder d_model */
+    int32_t mlp_proj;              /* dl_mlp_create id: merger, encoder d_model -> hidden -> decoder d_model */
+    int32_t mlp_out;               /* dl_mlp_create id: trajectory head, action d_model -> out_dim (no hidden layer) */
+    int32_t n_patches;             /* encoder tokens; n_patches % pool == 0 */
+    int32_t pool;                  /* consecutive merged tokens averaged into one visual token (stand-in for the 2x2 merge) */
+    int32_t n_text;                /* text embeddings that follow the visual tokens in the prefill */
+    int32_t n_actions;             /* action tokens (64 waypoints) */
+    int32_t n_decode;              /* greedy decode steps after the prefill (>= 0) */
+    int32_t n_euler;               /* Euler steps of the flow-matching loop (10 in the paper) */
+    int32_t out_dim;               /* columns of the trajectory (3) */
+} dl_vla_desc;
+
+/* Device buffers of one inference, fp32 unless noted, owned by the caller (arena blocks count against the cap).
+ * n_vis = n_patches / pool, n_prefill = n_vis + n_text. */
+typedef struct {
+    const void* patches;   /* in:  [n_patches, vit.d_model] */
+    void* vit_out;         /* scratch [n_patches, vit.d_model] */
+    void* proj_out;        /* scratch [n_patches, dec.d_model] */
+    void* seq;             /* in/out [n_prefill, dec.d_model]: rows n_vis.. hold the text embeddings on entry; rows < n_vis
+                              are written (the visual tokens) */
+    void* hidden;          /* out: [n_prefill, dec.d_model] decoder output of the prefill */
+    void* hidden_ctx;      /* out: [n_prefill, dec.d_model] FinalNorm(hidden): the action stack's cross-attention context */
+    void* x1;              /* scratch [dec.d_model] */
+    void* y1;              /* scratch [dec.d_model] */
+    int32_t* tokens;       /* out: device int32 [n_decode] greedy ids */
+    void* actions;         /* in/out [n_actions, act.d_model]: noise on entry, denoised action tokens on return */
+    void* act_in;          /* scratch [n_actions, act.d_model] */
+    void* velocity;        /* scratch [n_actions, act.d_model] */
+    void* trajectory;      /* out: [n_actions, out_dim] */
+} dl_vla_buffers;
+
+/* Enqueues one whole inference on the context's streams and returns (dl_sync to wait):
+ *   v = Encoder(patches);  p = Merger(v);  seq[t] = mean of p[t*pool .. t*pool+pool-1]  (t < n_vis);
+ *   hidden = Decoder(seq) at positions 0 .. n_prefill-1;  hidden_ctx = FinalNorm(hidden);
+ *   h = hidden[n_prefill-1];  for s < n_decode: tokens[s] = greedy(head(h)); h = Decoder(E[tokens[s]]) at n_prefill+s;
+ *   for s < n_euler: actions += ActionStack(actions + e(s / n_euler); context hidden_ctx) / n_euler;
+ *   trajectory = TrajectoryHead(actions).
+ * Every step is one of the calls above (dl_forward, dl_mlp_forward, dl_mean_pool, dl_final_norm, dl_greedy_step,
+ * dl_add_time_embedding, dl_axpy) issued in this order; residency, mode and slot count apply as set.  Checks shapes
+ * against the modules (DL_ERR_INVALID_ARG) before anything is enqueued. */
+int32_t dl_vla_infer(dl_ctx* ctx, const dl_vla_desc* desc, const dl_vla_buffers* buf);
+
 /* ---- measurement ------------------------------------------------------------------------ */
 
 typedef struct {

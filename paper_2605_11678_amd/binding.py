@@ -62,6 +62,18 @@ class dl_trace_op(C.Structure):
                 ("module", C.c_int32), ("layer", C.c_int32), ("flags", C.c_int32)]
 
 
+class dl_vla_desc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "m_vit", "m_dec", "m_act", "mlp_proj", "mlp_out", "n_patches", "pool", "n_text", "n_actions", "n_decode",
+        "n_euler", "out_dim")]
+
+
+class dl_vla_buffers(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in (
+        "patches", "vit_out", "proj_out", "seq", "hidden", "hidden_ctx", "x1", "y1", "tokens", "actions", "act_in",
+        "velocity", "trajectory")]
+
+
 _p = C.c_void_p
 _i32, _u64, _f64 = C.c_int32, C.c_uint64, C.c_double
 _PI32, _PU64, _PF64 = C.POINTER(C.c_int32), C.POINTER(C.c_uint64), C.POINTER(C.c_double)
@@ -92,6 +104,7 @@ SIGNATURES = {
     "dl_logits_argmax": (_i32, [_p, _i32, _p, _PI32, C.POINTER(C.c_float)]),
     "dl_greedy_step": (_i32, [_p, _i32, _p, _p, _p]),
     "dl_sync": (_i32, [_p]),
+    "dl_vla_infer": (_i32, [_p, C.POINTER(dl_vla_desc), C.POINTER(dl_vla_buffers)]),
     "dl_mlp_create": (_i32, [_p, _i32, _i32, _i32, _p, _p, _p, _p, _i32, _PI32]),
     "dl_mlp_forward": (_i32, [_p, _i32, _p, _p, _i32]),
     "dl_mean_pool": (_i32, [_p, _p, _p, _i32, _i32, _i32]),
@@ -267,6 +280,12 @@ class Context:
 
     def sync(self):
         self._ck(lib().dl_sync(self._h))
+
+    def vla_infer(self, desc: dict, buffers: dict):
+        """desc / buffers: the fields of dl_vla_desc / dl_vla_buffers by name (buffers as device addresses)."""
+        d = dl_vla_desc(**{k: int(v) for k, v in desc.items()})
+        b = dl_vla_buffers(**{k: (int(v) if v else None) for k, v in buffers.items()})
+        self._ck(lib().dl_vla_infer(self._h, C.byref(d), C.byref(b)))
 
     def mlp_create(self, d_in, d_hidden, d_out, w1, b1, w2, b2, max_tokens):
         def ptr(a):

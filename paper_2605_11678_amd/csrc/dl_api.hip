@@ -1160,6 +1160,61 @@ int32_t dl_add_time_embedding(dl_ctx* c, const void* x, void* y, float tval, int
     return DL_OK;
 }
 
+int32_t dl_vla_infer(dl_ctx* c, const dl_vla_desc* v, const dl_vla_buffers* b) {
+    int32_t rc = enter(c);
+    if (rc) return rc;
+    if (!v || !b) return fail(c, DL_ERR_INVALID_ARG, "null description or buffers");
+    Module* vit = get_module(c, v->m_vit);
+    Module* dec = get_module(c, v->m_dec);
+    Module* act = get_module(c, v->m_act);
+    if (!vit || !dec || !act || !vit->finalized || !dec->finalized || !act->finalized)
+        return fail(c, DL_ERR_BAD_STATE, "the three modules must exist and be finalized");
+    if (v->mlp_proj < 0 || size_t(v->mlp_proj) >= c->mlps.size() || v->mlp_out < 0 || size_t(v->mlp_out) >= c->mlps.size())
+        return fail(c, DL_ERR_INVALID_ARG, "no such MLP");
+    const Mlp& proj = c->mlps[size_t(v->mlp_proj)];
+    const Mlp& outp = c->mlps[size_t(v->mlp_out)];
+    if (v->pool < 1 || v->n_patches < v->pool || v->n_patches % v->pool || v->n_text < 0 || v->n_actions < 1 || v->n_decode < 0 ||
+        v->n_euler < 1 || v->out_dim < 1)
+        return fail(c, DL_ERR_INVALID_ARG, "bad token counts");
+    const int32_t n_vis = v->n_patches / v->pool, n_prefill = n_vis + v->n_text;
+    const int32_t dv = vit->d.d_model, dd = dec->d.d_model, da = act->d.d_model;
+    if (proj.d_in != dv || proj.d_out != dd || outp.d_in != da || outp.d_out != v->out_dim || outp.d_hidden != 0)
+        return fail(c, DL_ERR_INVALID_ARG, "MLP shapes do not match the modules");
+    if (act->d.d_ctx != dd) return fail(c, DL_ERR_INVALID_ARG, "the action stack's d_ctx must equal the decoder's d_model");
+    if (dec->d.max_seq < n_prefill + v->n_decode || dec->d.vocab <= 0)
+        return fail(c, DL_ERR_INVALID_ARG, "the decoder needs a head and a KV cache of n_prefill + n_decode positions");
+    if (v->n_patches > vit->d.max_tokens || v->n_patches > proj.max_tokens || n_prefill > dec->d.max_tokens ||
+        v->n_actions > act->d.max_tokens || v->n_actions > outp.max_tokens || n_prefill > act->d.max_ctx)
+        return fail(c, DL_ERR_INVALID_ARG, "token counts exceed what the modules were sized for");
+    if (on_gpu(c) && (!b->patches || !b->vit_out || !b->proj_out || !b->seq || !b->hidden || !b->hidden_ctx || !b->x1 || !b->y1 ||
+                      (v->n_decode > 0 && !b->tokens) || !b->actions || !b->act_in || !b->velocity || !b->trajectory))
+        return fail(c, DL_ERR_INVALID_ARG, "null buffer");
+#define DL_STEP(call) do { rc = (call); if (rc) return rc; } while (0)
+    // stages 1-2: encoder, merger
+    DL_STEP(dl_forward(c, v->m_vit, b->patches, b->vit_out, v->n_patches, 0, nullptr, 0));
+    DL_STEP(dl_mlp_forward(c, v->mlp_proj, b->vit_out, b->proj_out, v->n_patches));
+    DL_STEP(dl_mean_pool(c, b->proj_out, b->seq, n_vis, v->pool, dd));
+    // stage 3: prefill over [visual tokens ; text embeddings]
+    DL_STEP(dl_forward(c, v->m_dec, b->seq, b->hidden, n_prefill, 0, nullptr, 0));
+    DL_STEP(dl_final_norm(c, v->m_dec, b->hidden, b->hidden_ctx, n_prefill));
+    // stage 4: greedy decode; the un-normed state goes into the head, which normalises it itself
+    const void* h = on_gpu(c) ? static_cast<const char*>(b->hidden) + size_t(n_prefill - 1) * dd * 4 : nullptr;
+    for (int32_t s = 0; s < v->n_decode; ++s) {
+        DL_STEP(dl_greedy_step(c, v->m_dec, h, on_gpu(c) ? b->tokens + s : nullptr, b->x1));
+        DL_STEP(dl_forward(c, v->m_dec, b->x1, b->y1, 1, n_prefill + s, nullptr, 0));
+        h = b->y1;
+    }
+    // stage 5: Euler steps of the action stack against the fixed context, then the trajectory head
+    for (int32_t s = 0; s < v->n_euler; ++s) {
+        DL_STEP(dl_add_time_embedding(c, b->actions, b->act_in, float(s) / float(v->n_euler), v->n_actions, da));
+        DL_STEP(dl_forward(c, v->m_act, b->act_in, b->velocity, v->n_actions, 0, b->hidden_ctx, n_prefill));
+        DL_STEP(dl_axpy(c, b->actions, 1.0f / float(v->n_euler), b->velocity, uint64_t(v->n_actions) * da));
+    }
+    DL_STEP(dl_mlp_forward(c, v->mlp_out, b->actions, b->trajectory, v->n_actions));
+#undef DL_STEP
+    return DL_OK;
+}
+
 int32_t dl_sync(dl_ctx* c) {
     int32_t rc = enter(c);
     if (rc) return rc;

@@ -120,7 +120,7 @@ class Engine:
 class VlaPipeline:
     """The five-stage pipeline (vision encoder, merger, decoder prefill, decoder decode, action head with
     Euler steps) wired from C-ABI calls.  One context, one slot pair shared by the three layer stacks.
-    Plumbing only: every arithmetic step is a library call."""
+    Plumbing only: it registers the parts, owns the buffers and calls dl_vla_infer."""
 
     def __init__(self, eng: Engine, vit: CFG.ModuleConfig, dec: CFG.ModuleConfig, act: CFG.ModuleConfig,
                  n_patches: int, n_text: int, n_actions: int = 64, pool: int = 4, out_dim: int = 3,
@@ -169,23 +169,14 @@ class VlaPipeline:
         ctx.sync()
 
     def enqueue(self, n_decode: int, n_euler: int = 10):
-        ctx = self.eng.ctx
-        d, da = self.dec.d_model, self.act.d_model
-        ctx.forward(self.m_vit, self.p_patch, self.p_vit, self.n_patches, 0)
-        ctx.mlp_forward(self.mlp_proj, self.p_vit, self.p_proj, self.n_patches)
-        ctx.mean_pool(self.p_proj, self.p_seq, self.n_vis, self.pool, d)
-        ctx.forward(self.m_dec, self.p_seq, self.p_h, self.n_prefill, 0)
-        ctx.final_norm(self.m_dec, self.p_h, self.p_ctx, self.n_prefill)
-        h_ptr = self.p_h + 4 * (self.n_prefill - 1) * d
-        for s in range(n_decode):
-            ctx.greedy_step(self.m_dec, h_ptr, self.p_tok + 4 * (s % 64), self.p_x1)
-            ctx.forward(self.m_dec, self.p_x1, self.p_y1, 1, self.n_prefill + s)
-            h_ptr = self.p_y1
-        for s in range(n_euler):
-            ctx.add_time_embedding(self.p_a, self.p_ain, s / n_euler, self.n_actions, da)
-            ctx.forward(self.m_act, self.p_ain, self.p_vel, self.n_actions, 0, self.p_ctx, self.n_prefill)
-            ctx.axpy(self.p_a, 1.0 / n_euler, self.p_vel, self.n_actions * da)
-        ctx.mlp_forward(self.mlp_out, self.p_a, self.p_traj, self.n_actions)
+        """One whole inference as ONE library call (dl_vla_infer sequences the five stages natively)."""
+        self.eng.ctx.vla_infer(
+            dict(m_vit=self.m_vit, m_dec=self.m_dec, m_act=self.m_act, mlp_proj=self.mlp_proj, mlp_out=self.mlp_out,
+                 n_patches=self.n_patches, pool=self.pool, n_text=self.n_text, n_actions=self.n_actions,
+                 n_decode=n_decode, n_euler=n_euler, out_dim=self.out_dim),
+            dict(patches=self.p_patch, vit_out=self.p_vit, proj_out=self.p_proj, seq=self.p_seq, hidden=self.p_h,
+                 hidden_ctx=self.p_ctx, x1=self.p_x1, y1=self.p_y1, tokens=self.p_tok, actions=self.p_a,
+                 act_in=self.p_ain, velocity=self.p_vel, trajectory=self.p_traj))
 
     def enqueue_glue(self, n_euler: int = 10):
         """Only the launches of `enqueue` that belong to no layer and not to the greedy head: projector, pooling,
@@ -202,7 +193,7 @@ class VlaPipeline:
 
     def results(self, n_decode: int):
         e = self.eng
-        toks = e.download(self.v_tok[:min(n_decode, 64)]).view(np.int32).tolist() if n_decode else []
+        toks = e.download(self.v_tok[:min(n_decode, 256)]).view(np.int32).tolist() if n_decode else []
         return dict(tokens=toks,
                     hidden_ctx=e.download(self.v_ctx).reshape(self.n_prefill, self.dec.d_model),
                     actions=e.download(self.v_a).reshape(self.n_actions, self.act.d_model),

@@ -599,3 +599,36 @@ def test_kv_cache_module_limits_query_heads_per_kv_head():
     ok = small_cfg(1, n_q_heads=32, n_kv_heads=1, d_head=8, d_model=64)
     eng.ctx.module_create(**desc_fields(ok, 8))
     eng.close()
+
+
+def test_vla_infer_records_the_five_stages_and_checks_shapes():
+    """dl_vla_infer on a host-only context: the recorded schedule is one encoder pass, one prefill pass, n_decode
+    single-token passes and n_euler action passes, in that order; mismatching shapes are refused before anything is
+    enqueued."""
+    from tests import parity_cases as PC
+    vit, dec, act = PC.pipe_small_modules()
+    eng = Engine(1 << 30, device=-1)
+    rng = np.random.default_rng(4)
+    m_vit = eng.add_module(vit, 256, weights=tiny_weights(vit, rng))
+    m_dec = eng.add_module(dec, 104, weights=tiny_weights(dec, rng))
+    m_act = eng.add_module(act, 64, 104, weights=tiny_weights(act, rng))
+    z = lambda *shape: np.zeros(shape, np.uint16)
+    proj = eng.ctx.mlp_create(vit.d_model, dec.d_model, dec.d_model, z(dec.d_model, vit.d_model), z(dec.d_model),
+                              z(dec.d_model, dec.d_model), z(dec.d_model), max_tokens=256)
+    outp = eng.ctx.mlp_create(act.d_model, 0, 3, None, None, z(3, act.d_model), z(3), max_tokens=64)
+    desc = dict(m_vit=m_vit, m_dec=m_dec, m_act=m_act, mlp_proj=proj, mlp_out=outp, n_patches=256, pool=4, n_text=40,
+                n_actions=64, n_decode=3, n_euler=5, out_dim=3)
+    bufs = {k: 0 for k, _ in B.dl_vla_buffers._fields_}
+    eng.ctx.trace_read()
+    eng.ctx.vla_infer(desc, bufs)
+    execs = [(o["module"], o["layer"]) for o in eng.ctx.trace_read() if o["op"] == B.DL_OP_EXEC]
+    want = [(m_vit, l) for l in range(vit.n_layers)] + [(m_dec, l) for l in range(dec.n_layers)] * (1 + 3) + \
+           [(m_act, l) for l in range(act.n_layers)] * 5
+    assert execs == want
+    for bad in (dict(n_patches=255), dict(n_decode=100), dict(n_text=41), dict(mlp_out=proj), dict(out_dim=4),
+                dict(n_euler=0), dict(m_act=m_vit)):
+        with pytest.raises(B.DLError) as e:
+            eng.ctx.vla_infer({**desc, **bad}, bufs)
+        assert e.value.code == B.DL_ERR_INVALID_ARG, bad
+        assert eng.ctx.trace_read() == []                    # nothing was enqueued
+    eng.close()
