@@ -35,6 +35,69 @@ __global__ __launch_bounds__(256) void norm_kernel(const float* __restrict__ x, 
     });
 }
 
+// Rows of at most 2048 elements: one WAVEFRONT per row (four rows per workgroup), the row and its gains held in
+// registers, both reductions done with cross-lane shuffles only - no LDS, no workgroup barrier.  With one workgroup per
+// row a 1152-element row (the encoder's) leaves most threads one piece each and spends its time in the two barriers of
+// every reduction: 12.1 us per launch (between events) at 4096 x 1152 against 9.6 us this way.
+template <int KIND, bool OUT_F32>
+__global__ __launch_bounds__(256) void norm_wave_kernel(const float* __restrict__ x, const bf16_t* __restrict__ g,
+                                                        const bf16_t* __restrict__ b, void* __restrict__ out, int T, int d,
+                                                        float eps) {
+    constexpr int MAXV = 8;                            // float4 pieces per lane
+    const int lane = threadIdx.x & 63, r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= T) return;
+    const int nv = d >> 2;
+    const float4* row = reinterpret_cast<const float4*>(x + size_t(r) * d);
+    float4 v[MAXV];
+    uint2 gk[MAXV], bk[MAXV];
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {                   // everything requested before anything is used; index clamped
+        const int i = lane + 64 * j, ic = i < nv ? i : 0;
+        v[j] = row[ic];
+        gk[j] = reinterpret_cast<const uint2*>(g)[ic];
+        if (KIND == 1) bk[j] = reinterpret_cast<const uint2*>(b)[ic];
+    }
+    float mean = 0.0f;
+    if (KIND == 1) {
+        float s = 0.0f;
+#pragma unroll
+        for (int j = 0; j < MAXV; ++j)
+            if (lane + 64 * j < nv) s += (v[j].x + v[j].y) + (v[j].z + v[j].w);
+        mean = normdev::wave_sum(s) / float(d);
+    }
+    float ss = 0.0f;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j)
+        if (lane + 64 * j < nv) {
+            const float a0 = v[j].x - mean, a1 = v[j].y - mean, a2 = v[j].z - mean, a3 = v[j].w - mean;
+            ss += (a0 * a0 + a1 * a1) + (a2 * a2 + a3 * a3);
+        }
+    const float inv = rsqrtf(normdev::wave_sum(ss) / float(d) + eps);
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+        const int i = lane + 64 * j;
+        if (i >= nv) continue;
+        float o0 = (v[j].x - mean) * inv * __uint_as_float(gk[j].x << 16);
+        float o1 = (v[j].y - mean) * inv * __uint_as_float(gk[j].x & 0xFFFF0000u);
+        float o2 = (v[j].z - mean) * inv * __uint_as_float(gk[j].y << 16);
+        float o3 = (v[j].w - mean) * inv * __uint_as_float(gk[j].y & 0xFFFF0000u);
+        if (KIND == 1) {
+            o0 += __uint_as_float(bk[j].x << 16);
+            o1 += __uint_as_float(bk[j].x & 0xFFFF0000u);
+            o2 += __uint_as_float(bk[j].y << 16);
+            o3 += __uint_as_float(bk[j].y & 0xFFFF0000u);
+        }
+        if (OUT_F32) {
+            reinterpret_cast<float4*>(static_cast<float*>(out) + size_t(r) * d)[i] = make_float4(o0, o1, o2, o3);
+        } else {
+            uint2 pk;
+            pk.x = uint32_t(f_to_bf16(o0)) | (uint32_t(f_to_bf16(o1)) << 16);
+            pk.y = uint32_t(f_to_bf16(o2)) | (uint32_t(f_to_bf16(o3)) << 16);
+            reinterpret_cast<uint2*>(static_cast<bf16_t*>(out) + size_t(r) * d)[i] = pk;
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void cast_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, uint64_t n) {
     for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n; i += uint64_t(gridDim.x) * 256)
         out[i] = f_to_bf16(x[i]);
@@ -266,6 +329,18 @@ __global__ __launch_bounds__(1024) void argmax_embed_kernel(const float* __restr
 void norm_rows(int kind, const float* x, const bf16_t* g, const bf16_t* b, void* out, bool out_f32, int T, int d,
                float eps, hipStream_t st) {
     if (T <= 0) return;
+    if (d <= 2048 && T >= 4) {
+        // short rows, several of them: one wavefront per row
+        dim3 grid((T + 3) / 4), block(256);
+        if (kind == 0) {
+            if (out_f32) hipLaunchKernelGGL((norm_wave_kernel<0, true>), grid, block, 0, st, x, g, b, out, T, d, eps);
+            else hipLaunchKernelGGL((norm_wave_kernel<0, false>), grid, block, 0, st, x, g, b, out, T, d, eps);
+        } else {
+            if (out_f32) hipLaunchKernelGGL((norm_wave_kernel<1, true>), grid, block, 0, st, x, g, b, out, T, d, eps);
+            else hipLaunchKernelGGL((norm_wave_kernel<1, false>), grid, block, 0, st, x, g, b, out, T, d, eps);
+        }
+        return;
+    }
     dim3 grid(T), block(256);
     if (kind == 0) {
         if (out_f32) hipLaunchKernelGGL((norm_kernel<0, true>), grid, block, 0, st, x, g, b, out, d, eps);
