@@ -9,14 +9,14 @@
 //
 //  * gemm_fast<BM,BN,EPI> — the production path for K % 128 == 0.  One workgroup per CU (256 threads =
 //    4 wavefronts in a 2x2 grid, each owning a (BM/2)x(BN/2) tile, i.e. up to 4x4 MFMA tiles = 256 fp32
-//    accumulators per lane).  K step 32.  Tiles go global -> LDS directly (global_load_lds_dwordx4, no
-//    staging registers) into four LDS stages that are separate arrays, so the compiler can tell the
-//    in-flight stages from the one being read; the wait for a copy is an explicit s_waitcnt vmcnt(n) that
-//    leaves the younger copies (up to three k-tiles ahead) in flight.  LDS rows are 64 bytes, unpadded
-//    (a wavefront's copy fills 1 KB contiguously); the 16-byte chunk index is XOR-swizzled with (row/4)%4
-//    on both sides, which keeps the 64-lane b128 fragment reads conflict-free.  Per K step two phases of
-//    16 MFMAs; fragment reads, copies and MFMAs are interleaved through sched_group_barrier so that the
-//    vector-memory path sees an even one copy per four MFMAs, and one bare s_barrier per K step.
+//    accumulators per lane).  k-tile 64: a row of a tile is one 128-byte cache line.  Tiles go global -> LDS
+//    directly (global_load_lds_dwordx4, no staging registers) into two LDS stages that are separate arrays, so
+//    the compiler can tell the stage being filled from the one being read; the wait for a copy is an explicit
+//    s_waitcnt.  LDS rows are 128 bytes, unpadded (a wavefront's copy fills 1 KB = 8 rows contiguously); the
+//    16-byte chunk index is XOR-swizzled with row%8 on both sides, which keeps the b128 fragment reads
+//    conflict-free.  Per k-tile four phases of up to 16 MFMAs, each interleaved with the fragment reads of the
+//    next phase through sched_group_barrier, ONE bare s_barrier, and the copy of the k-tile after the next
+//    spread over the two phases that follow the barrier (a whole k-tile of time to land).
 //  * gemm_generic<EPI> — any shape (K % 8 == 0): 128x128 tile, 64x64 per wavefront, register-staged.
 //  * gemm_few_rows<EPI> — M <= 64: 64x32 output per workgroup, reduction split over its 8 wavefronts.
 //
@@ -484,33 +484,31 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int* 
 #define DL_WAIT_VM(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8))
 #define DL_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt(((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0x0 << 8))
 
-// scheduling request for one phase of a K step: groups of PM MFMAs followed by PD LDS reads (and one global->LDS copy
-// while copies remain) until the NR reads are out, then the remaining copies and MFMAs
-template <int PM, int PD, int NR, int NM, int NC, int G>
-struct SchedBursts {
+// scheduling request for one phase of a k-tile: NM MFMAs with the NR fragment reads spread evenly over all but the
+// last RT of them (those cover the latency of the last read) and the NC global->LDS copies spread over all of them
+template <int NM, int NR, int NC, int RT, int M>
+struct SchedEven {
     static __device__ __forceinline__ void run() {
-        constexpr int d = (G + 1) * PD <= NR ? PD : (NR - G * PD > 0 ? NR - G * PD : 0);
-        if constexpr (d > 0) {
-            __builtin_amdgcn_sched_group_barrier(0x008, PM, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, d, 0);
-            if constexpr (G < NC) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            SchedBursts<PM, PD, NR, NM, NC, G + 1>::run();
-        } else {
-            if constexpr (NC > G) __builtin_amdgcn_sched_group_barrier(0x020, NC - G, 0);
-            if constexpr (NM > G * PM) __builtin_amdgcn_sched_group_barrier(0x008, NM - G * PM, 0);
+        if constexpr (M < NM) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            constexpr int span = NM - RT;
+            constexpr int r = M < span ? ((M + 1) * NR / span - M * NR / span) : 0;
+            if constexpr (r > 0) __builtin_amdgcn_sched_group_barrier(0x100, r, 0);
+            constexpr int c = (M + 1) * NC / NM - M * NC / NM;
+            if constexpr (c > 0) __builtin_amdgcn_sched_group_barrier(0x020, c, 0);
+            SchedEven<NM, NR, NC, RT, M + 1>::run();
         }
     }
 };
 
-// One output tile with its top-left corner at (m0, n0).  S0..S3 are the four LDS stages; they must be four distinct
-// __shared__ arrays of at least (BM + BN) * 32 elements each.
+// One output tile with its top-left corner at (m0, n0).  S0 and S1 are the two LDS stages; they must be two distinct
+// __shared__ arrays of at least (BM + BN) * 64 elements each.
 template <int BM, int BN, int EPI>
-__device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf16_t* S0, bf16_t* S1, bf16_t* S2, bf16_t* S3) {
-    constexpr int BK = 32;
+__device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf16_t* S0, bf16_t* S1) {
+    constexpr int BK = 64;
     constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;
-    constexpr int JA = BM / 64, JB = BN / 64;            // 1 KB copy blocks (16 rows x 64 B) per wavefront and k-tile
-    constexpr int NL = JA + JB;
-    static_assert(3 * NL < 64, "outstanding copies must fit the vmcnt field");
+    constexpr int JA = BM / 32, JB = BN / 32;            // 1 KB copy blocks (8 rows x 128 B) per wavefront and k-tile
+    constexpr int RT = TM * TN / 4;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
 
@@ -522,28 +520,28 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-    // copy sources: block b = wave + 4*j of a tile holds rows 16b..16b+15; lane L lands at row 16b + L/4,
-    // physical chunk L%4, and therefore fetches logical chunk (L%4) ^ swizzle(row).  Rows past the
-    // matrix edge are clamped: they produce values that the epilogue never stores.
+    // copy sources: block b = wave + 4*j of a tile holds rows 8b..8b+7, 128 bytes (one cache line, 64 k) each;
+    // lane L lands at row 8b + L/8, physical 16-byte chunk L%8, and therefore fetches logical chunk
+    // (L%8) ^ (row%8).  Rows past the matrix edge are clamped: they produce values that the epilogue never stores.
     uint32_t offA[JA], offB[JB];
 #pragma unroll
     for (int j = 0; j < JA; ++j) {
-        const int row = 16 * (wave + 4 * j) + (lane >> 2), lc = (lane & 3) ^ ((row >> 2) & 3);
+        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ (row & 7);
         offA[j] = uint32_t((size_t(min(m0 + row, p.M - 1)) * p.lda + lc * 8) * 2);
     }
 #pragma unroll
     for (int j = 0; j < JB; ++j) {
-        const int row = 16 * (wave + 4 * j) + (lane >> 2), lc = (lane & 3) ^ ((row >> 2) & 3);
+        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ (row & 7);
         offB[j] = uint32_t((size_t(min(n0 + row, p.N - 1)) * p.ldb + lc * 8) * 2);
     }
     const char* gA = reinterpret_cast<const char*>(p.A);
     const char* gB = reinterpret_cast<const char*>(p.B);
     // fragment read offsets (elements) inside a stage, one per 16-wide k step
     const int lr = lane & 31, g2 = lane >> 5;
-    int rdA[2], rdB[2];
+    int rdA[4], rdB[4];
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
-        const int pc = (2 * kk + g2) ^ ((lr >> 2) & 3);
+    for (int kk = 0; kk < 4; ++kk) {
+        const int pc = (2 * kk + g2) ^ (lr & 7);
         rdA[kk] = ((BM / 2) * wm + lr) * BK + pc * 8;
         rdB[kk] = BM * BK + ((BN / 2) * wn + lr) * BK + pc * 8;
     }
@@ -570,88 +568,74 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
             for (int j = 0; j < TN; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     };
-    // ask the scheduler for: 2 MFMA, 1 LDS read, and for the first ncopy groups 1 global->LDS copy.  The 4x4-tile
-    // wavefront (16 MFMAs, 8 fragment reads per phase) does better with its reads in two bursts of four after six
-    // MFMAs each, which leaves the last four MFMAs of a phase to cover the latency of the last read (+4 % on the
-    // gate/up shape; the 3x4 and 3x3 wavefront tiles showed no difference between the patterns tried).
     auto interleave = [&](auto ncopy_c) {
-        constexpr int ncopy = decltype(ncopy_c)::value;
-        if constexpr (TM * TN == 16) {
-            SchedBursts<6, 4, TM + TN, TM * TN, ncopy, 0>::run();
-        } else {
-#pragma unroll
-            for (int g = 0; g < TM * TN / 2; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (g < ncopy) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-        }
+        SchedEven<TM * TN, TM + TN, decltype(ncopy_c)::value, RT, 0>::run();
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    const int nk = p.K / BK;                             // host guarantees K % 128 == 0: nk is a multiple of 4
+    const int nk = p.K / BK;                             // host guarantees K % 128 == 0: nk is even and >= 2
     copyA(S0, 0); copyB(S0, 0);
-    copyA(S1, 1); copyB(S1, 1);
-    copyA(S2, 2); copyB(S2, 2);
-    DL_WAIT_VM(2 * NL);                                  // k-tile 0 has landed (this wavefront's share)
+    copyA(S1, 1);
+    DL_WAIT_VM(JA);                                      // k-tile 0 has landed (this wavefront's share)
     __builtin_amdgcn_s_barrier();
     ldfrag(a0, b0, S0, 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    // One k-tile = two phases of TM*TN MFMAs.  In steady state (AHEAD == 3) the copy of k-tile kt+3 goes into
-    // the stage that k-tile kt-1 was read from, its A half spread over the first phase, its B half over the
-    // second, so that the vector-memory path sees one copy per four MFMAs throughout.  The barrier between the
-    // phases is preceded by a wait for this wavefront's share of k-tile kt+1 and for all of its own LDS reads;
-    // past it (a) k-tile kt+1 has landed for everyone and (b) nobody reads stage kt any more after the reads
-    // already returned, so the copy issued in the next k-tile may overwrite it.
-    auto ktile = [&](const bf16_t* cur, const bf16_t* nxt, bf16_t* fill, int kt, auto ahead_c) {
-        constexpr int AHEAD = decltype(ahead_c)::value;  // 3: steady state; 2, 1, 0: tail, nothing left to copy
+    // One k-tile = four phases of TM*TN MFMAs (16-wide k steps), each overlapped with the fragment reads of the next
+    // phase.  Before the last phase the wavefront waits for its own copies of k-tile kt+1 and for all of its LDS reads
+    // and meets the others at the one barrier of the k-tile; past it (a) k-tile kt+1 has landed for everyone and
+    // (b) nobody reads stage kt any more, so the copy of k-tile kt+2 into that stage starts right there: its A half
+    // is spread over the last phase, its B half over the first phase of the next k-tile, which gives every copy
+    // almost a whole k-tile (64 MFMAs per wavefront) to land.
+    auto ktile = [&](bf16_t* cur, bf16_t* oth, int kt, auto last_c) {
+        constexpr int LAST = decltype(last_c)::value;    // 0: steady state, 1: second to last k-tile, 2: last k-tile
         ldfrag(a1, b1, cur, 1);
-        if (AHEAD == 3) copyA(fill, kt + 3);
+        if (LAST != 2) copyB(oth, kt + 1);               // second half of the copy begun in the previous k-tile
         mma(a0, b0);
-        interleave(std::integral_constant<int, (AHEAD == 3 ? JA : 0)>{});
-        if (AHEAD >= 1) {
-            // k-tile kt+1 must have landed; younger copies may stay in flight: A and B of kt+2, A of kt+3
-            if (AHEAD == 3) DL_WAIT_VM_LGKM0(JA + NL);
-            else if (AHEAD == 2) DL_WAIT_VM_LGKM0(NL);
-            else DL_WAIT_VM_LGKM0(0);
+        interleave(std::integral_constant<int, (LAST != 2 ? JB : 0)>{});
+        ldfrag(a0, b0, cur, 2);
+        mma(a1, b1);
+        interleave(std::integral_constant<int, 0>{});
+        ldfrag(a1, b1, cur, 3);
+        mma(a0, b0);
+        interleave(std::integral_constant<int, 0>{});
+        if (LAST != 2) {
+            DL_WAIT_VM_LGKM0(0);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            ldfrag(a0, b0, nxt, 0);
+            ldfrag(a0, b0, oth, 0);
+            if (LAST == 0) copyA(cur, kt + 2);
+            mma(a1, b1);
+            interleave(std::integral_constant<int, (LAST == 0 ? JA : 0)>{});
+        } else {
+            mma(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (AHEAD == 3) copyB(fill, kt + 3);
-        mma(a1, b1);
-        interleave(std::integral_constant<int, (AHEAD == 3 ? JB : 0)>{});
     };
     int kt = 0;
-    for (; kt + 4 < nk; kt += 4) {
-        ktile(S0, S1, S3, kt, std::integral_constant<int, 3>{});
-        ktile(S1, S2, S0, kt + 1, std::integral_constant<int, 3>{});
-        ktile(S2, S3, S1, kt + 2, std::integral_constant<int, 3>{});
-        ktile(S3, S0, S2, kt + 3, std::integral_constant<int, 3>{});
+    for (; kt + 2 < nk; kt += 2) {
+        ktile(S0, S1, kt, std::integral_constant<int, 0>{});
+        ktile(S1, S0, kt + 1, std::integral_constant<int, 0>{});
     }
-    ktile(S0, S1, S3, kt, std::integral_constant<int, 3>{});
-    ktile(S1, S2, S0, kt + 1, std::integral_constant<int, 2>{});
-    ktile(S2, S3, S1, kt + 2, std::integral_constant<int, 1>{});
-    ktile(S3, S0, S2, kt + 3, std::integral_constant<int, 0>{});
+    ktile(S0, S1, kt, std::integral_constant<int, 1>{});
+    ktile(S1, S0, kt + 1, std::integral_constant<int, 2>{});
 
     // wavefront tile wholly inside the matrix (SwiGLU: inside the packed gate/up columns): unpredicated epilogue
     const int mw = m0 + (BM / 2) * wm, nw = n0 + (BN / 2) * wn;
-    constexpr bool kFull = true;
-    if (kFull && mw + BM / 2 <= p.M && nw + BN / 2 <= p.N) store_tiles_full<EPI, TM, TN>(p, acc, mw, nw, lane);
+    if (mw + BM / 2 <= p.M && nw + BN / 2 <= p.N) store_tiles_full<EPI, TM, TN>(p, acc, mw, nw, lane);
     else store_tiles<EPI, TM, TN>(p, acc, mw, nw, lane);
 }
 
+// 128-row tiles leave room for two workgroups per compute unit (at most 80 KB of LDS and 128 accumulators each): one's
+// prologue and epilogue hide under the other's main loop.
 template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
-    __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * 32];
-    __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * 32];
-    __shared__ __attribute__((aligned(1024))) bf16_t S2[(BM + BN) * 32];
-    __shared__ __attribute__((aligned(1024))) bf16_t S3[(BM + BN) * 32];
+__global__ __launch_bounds__(256, (BM == 128 && BN <= 192) ? 2 : 1) void gemm_fast(GemmArgs p) {
+    __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * 64];
+    __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * 64];
     const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
     int tm, tn;
     if (!tile_of(blockIdx.x, tiles_m, tiles_n, &tm, &tn)) return;
-    fast_tile<BM, BN, EPI>(p, tm * BM, tn * BN, S0, S1, S2, S3);
+    fast_tile<BM, BN, EPI>(p, tm * BM, tn * BN, S0, S1);
 }
 
 // 256x256 tiles whose count is r full rounds of 256 workgroups plus a remainder of at most half a round: the last
@@ -660,20 +644,18 @@ __global__ __launch_bounds__(256) void gemm_fast(GemmArgs p) {
 // Block b < n_big computes whole tile b (in the XCD-aware order), block n_big + 2 j + h half h of tile n_big + j.
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_fast_split_tail(GemmArgs p, int n_big) {
-    __shared__ __attribute__((aligned(1024))) bf16_t S0[512 * 32];
-    __shared__ __attribute__((aligned(1024))) bf16_t S1[512 * 32];
-    __shared__ __attribute__((aligned(1024))) bf16_t S2[512 * 32];
-    __shared__ __attribute__((aligned(1024))) bf16_t S3[512 * 32];
+    __shared__ __attribute__((aligned(1024))) bf16_t S0[512 * 64];
+    __shared__ __attribute__((aligned(1024))) bf16_t S1[512 * 64];
     const int tiles_m = (p.M + 255) / 256, tiles_n = (p.N + 255) / 256;
     const int b = blockIdx.x;
     const int v = b < n_big ? b : n_big + ((b - n_big) >> 1);
     int tm, tn;
     if (!tile_of(v, tiles_m, tiles_n, &tm, &tn)) return;
     if (b < n_big) {
-        fast_tile<256, 256, EPI>(p, tm * 256, tn * 256, S0, S1, S2, S3);
+        fast_tile<256, 256, EPI>(p, tm * 256, tn * 256, S0, S1);
     } else {
         const int m0 = tm * 256 + 128 * ((b - n_big) & 1);
-        if (m0 < p.M) fast_tile<128, 256, EPI>(p, m0, tn * 256, S0, S1, S2, S3);
+        if (m0 < p.M) fast_tile<128, 256, EPI>(p, m0, tn * 256, S0, S1);
     }
 }
 
@@ -693,24 +675,25 @@ void launch_fast(const GemmArgs& a, hipStream_t st) {
     hipLaunchKernelGGL((gemm_fast<BM, BN, EPI>), dim3(grid), dim3(256), 0, st, a);
 }
 
-// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192, 4 = 128x192.  Cost of a shape =
-// rounds of workgroup slots x tile area / relative efficiency, the efficiencies fitted to measured launch times.
-// Shapes 0-3 hold one workgroup per compute unit (256 slots).  128x192 needs 80 KB of LDS, so two workgroups share a
-// compute unit (512 slots at half speed each, but one's prologue and epilogue hide under the other's main loop); it is
-// considered only for short reductions or narrow outputs (the encoder's K = 1152 and N = 1152 GEMMs), where the
-// large tiles leave compute units idle or spend their time outside the main loop.
+// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192, 4 = 128x192, 5 = 128x128.  Cost of
+// a shape = rounds of workgroup slots x tile area / relative efficiency, the efficiencies fitted to measured launch
+// times.  Shapes 0-3 hold one workgroup per compute unit (256 slots).  128x192 and 128x128 need at most 80 KB of LDS,
+// so two workgroups share a compute unit (512 slots at half speed each, but one's prologue and epilogue hide under the
+// other's main loop); they are considered only for short reductions or narrow outputs (the encoder's K = 1152 and
+// N = 1152 GEMMs), where the large tiles leave compute units idle or spend their time outside the main loop.
 int pick_tile(int M, int N, int K, bool need_even_cols) {
-    const int bm[5] = {256, 192, 256, 192, 128}, bn[5] = {256, 256, 192, 192, 192};
-    const double eff[5] = {1.0, 0.93, 0.93, 0.86, 1.34};
-    const int n_cand = (!need_even_cols && (K <= 2048 || N <= 1536)) ? 5 : 4;
+    const int bm[6] = {256, 192, 256, 192, 128, 128}, bn[6] = {256, 256, 192, 192, 192, 128};
+    const double eff[6] = {1.0, 0.93, 0.93, 0.90, 1.34, 1.0};
+    const bool small_ok = K <= 2048 || N <= 1536;
     int best = 0;
     double best_cost = 1e300;
-    for (int c = 0; c < n_cand; ++c) {
-        if (need_even_cols && bn[c] != 256) continue;
+    for (int c = 0; c < 6; ++c) {
+        if (need_even_cols && bn[c] % 128 != 0) continue;   // gate/up pairs need an even number of 32-wide column tiles
+        if (c >= 4 && !small_ok) continue;
         const long tiles = long((M + bm[c] - 1) / bm[c]) * ((N + bn[c] - 1) / bn[c]);
-        const long slots = c == 4 ? 512 : 256;
+        const long slots = c >= 4 ? 512 : 256;
         const double rounds = tiles >= 3 * slots ? double(tiles) / double(slots) : double((tiles + slots - 1) / slots);
-        const double cost = rounds * (c == 4 ? 2.0 : 1.0) * bm[c] * bn[c] / eff[c];
+        const double cost = rounds * (c >= 4 ? 2.0 : 1.0) * bm[c] * bn[c] / eff[c];
         if (cost < best_cost) { best_cost = cost; best = c; }
     }
     return best;
@@ -721,11 +704,12 @@ void dispatch_fast(const GemmArgs& a, hipStream_t st) {
     const int t = pick_tile(a.M, a.N, a.K, EPI == EPI_SWIGLU_BF16);
     if (t == 0) launch_fast<256, 256, EPI>(a, st);
     else if (t == 1) launch_fast<192, 256, EPI>(a, st);
-    else if (EPI != EPI_SWIGLU_BF16) {
+    else if (t == 5) launch_fast<128, 128, EPI>(a, st);
+    else if constexpr (EPI != EPI_SWIGLU_BF16) {
         // odd numbers of 32-wide tile columns per wavefront cannot pair gate/up rows: never chosen for SwiGLU
-        if (t == 2) launch_fast<256, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
-        else if (t == 3) launch_fast<192, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
-        else launch_fast<128, (EPI == EPI_SWIGLU_BF16 ? 256 : 192), EPI>(a, st);
+        if (t == 2) launch_fast<256, 192, EPI>(a, st);
+        else if (t == 3) launch_fast<192, 192, EPI>(a, st);
+        else launch_fast<128, 192, EPI>(a, st);
     }
 }
 
