@@ -16,7 +16,11 @@
 //                  query heads of ONE KV head on the same 32 query positions, so a K/V tile is loaded once
 //                  for four heads;
 //   HEADS = false: the four wavefronts are four 32-query slices of one head (128 queries per block).
-// Head dims 64 / 72 / 128 run as DHP = 64 / 96 / 128 with zero padding (exact zeros contribute nothing).
+// The score product runs over DK = the head dimension rounded up to 16 features, the output product over DV = the head
+// dimension rounded up to 32 rows (64 / 72 / 128 run as 64x64 / 80x96 / 128x128; exact zeros contribute nothing).
+// When the output tile has a padding row (dh < DV), the last one is fed with ones instead of V^T: its accumulator is
+// then the sum of the (bf16-rounded) probabilities, i.e. the softmax denominator comes out of the matrix core and the
+// vector unit does not add the probabilities up.
 // Softmax runs on raw scores: the 1/sqrt(dh) * log2(e) scale is folded into one FMA in front of the
 // base-2 exponential, masking is skipped on tiles that cannot need it, and the reference maximum of the
 // online softmax moves lazily (only past a 2^8 margin), so the running output is rescaled about once.
@@ -40,16 +44,17 @@ __device__ __forceinline__ bf16_t f_to_bf16_attn(float f) {
 
 // SPLIT: the launch's z dimension divides the K/V tiles into runs of `tps` tiles; a workgroup handles one run and
 // writes, per query and head, its unnormalised output, reference maximum and sum to p.split_ws
-// ([run][head][query][DHP + 4] floats) for attn_merge_kernel.  Used for few queries over many keys (cross-attention
+// ([run][head][query][DV + 4] floats) for attn_merge_kernel.  Used for few queries over many keys (cross-attention
 // of a short sequence), where a launch would otherwise consist of a handful of workgroups walking the whole key range.
-template <int DHP, bool HEADS, bool SPLIT>
+template <int DK, int DV, bool HEADS, bool SPLIT, bool ONES>
 __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_log2, int tps) {
-    constexpr int KLD = DHP + 8;     // sK row stride (elements)
+    constexpr int KLD = DK + 8;      // sK row stride (elements)
     constexpr int VLD = BKV + 8;     // sV row stride
     constexpr int QB = HEADS ? 32 : 128;
-    constexpr int NKC = BKV * (DHP / 8) / 256, NVC = DHP * (BKV / 8) / 256;   // 16-byte chunks per thread
+    constexpr int KCH = BKV * (DK / 8);                                       // 16-byte chunks of a K tile
+    constexpr int NKC = (KCH + 255) / 256, NVC = DV * (BKV / 8) / 256;        // chunks per thread
     __shared__ __attribute__((aligned(16))) bf16_t sK[2][BKV * KLD];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[2][DHP * VLD];
+    __shared__ __attribute__((aligned(16))) bf16_t sV[2][DV * VLD];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, g2 = lane >> 5;
@@ -73,19 +78,19 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     // Q fragments (B operand): 8 consecutive features per lane and k-step.  All of them are requested here, with
     // clamped addresses and no predicate, and turned into fragments only after the first K/V tile has been requested
     // as well: the wavefront pays one memory round trip for Q and the first tile together, not one per fragment.
-    u32x4 qv[DHP / 16];
+    u32x4 qv[DK / 16];
     {
         const bf16_t* qrow = p.q + size_t(min(tq, p.T - 1)) * p.ldq + size_t(h) * p.dh;
 #pragma unroll
-        for (int kk = 0; kk < DHP / 16; ++kk) {
+        for (int kk = 0; kk < DK / 16; ++kk) {
             const int e = 16 * kk + 8 * g2;
             qv[kk] = *reinterpret_cast<const u32x4*>(qrow + (e < p.dh ? e : 0));
         }
     }
 
-    f32x16 accO[DHP / 32];
+    f32x16 accO[DV / 32];
 #pragma unroll
-    for (int dt = 0; dt < DHP / 32; ++dt)
+    for (int dt = 0; dt < DV / 32; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) accO[dt][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;             // running maximum (raw score units) and sum
@@ -105,12 +110,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     //  * V^T rows past dh repeat row dh-1 (they produce output features nobody stores); V^T position chunks that
     //    start past S re-read the chunk at 0, and a chunk that straddles S brings along up to 7 stale positions:
     //    their probabilities are exact zeros and the buffers hold finite numbers everywhere (zeroed when the
-    //    module is finalised, rows padded to a multiple of 64 positions).
+    //    module is finalised, rows padded to a multiple of 64 positions);
+    //  * ONES: the last V^T row of the tile (a padding row) is replaced by ones when it is stashed.
     u32x4 rk[NKC], rv[NVC];
     auto fetch = [&](int j0) {
 #pragma unroll
         for (int i = 0; i < NKC; ++i) {
-            const int c = tid + 256 * i, row = c / (DHP / 8), kc = (c % (DHP / 8)) * 8;
+            const int c = min(tid + 256 * i, KCH - 1), row = c / (DK / 8), kc = (c % (DK / 8)) * 8;
             rk[i] = *reinterpret_cast<const u32x4*>(kbase + size_t(min(j0 + row, p.S - 1)) * p.ldk + (kc < p.dh ? kc : 0));
         }
 #pragma unroll
@@ -122,20 +128,21 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     auto stash = [&](int s) {
 #pragma unroll
         for (int i = 0; i < NKC; ++i) {
-            const int c = tid + 256 * i, row = c / (DHP / 8), kc = (c % (DHP / 8)) * 8;
-            *reinterpret_cast<u32x4*>(&sK[s][row * KLD + kc]) = rk[i];
+            const int c = tid + 256 * i, row = c / (DK / 8), kc = (c % (DK / 8)) * 8;
+            if (KCH % 256 == 0 || c < KCH) *reinterpret_cast<u32x4*>(&sK[s][row * KLD + kc]) = rk[i];
         }
 #pragma unroll
         for (int i = 0; i < NVC; ++i) {
             const int c = tid + 256 * i, e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
-            *reinterpret_cast<u32x4*>(&sV[s][e * VLD + jc]) = rv[i];
+            const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};        // bf16 1.0 pairs
+            *reinterpret_cast<u32x4*>(&sV[s][e * VLD + jc]) = (ONES && e == DV - 1) ? ones : rv[i];
         }
     };
 
     fetch(t_begin * BKV);                              // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
-    bf16x8 qf[DHP / 16];
+    bf16x8 qf[DK / 16];
 #pragma unroll
-    for (int kk = 0; kk < DHP / 16; ++kk) {
+    for (int kk = 0; kk < DK / 16; ++kk) {
         const int e = 16 * kk + 8 * g2;
         const u32x4 z = {0u, 0u, 0u, 0u};
         u32x4 v = (tq < p.T && e < p.dh) ? qv[kk] : z;      // queries past T and padding features are zero
@@ -160,12 +167,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         if (active) {
             // S^T tile: 64 keys x 32 queries.  LDS fragments are requested AHEAD MFMAs early so that an MFMA does
             // not wait for the read issued right in front of it.
-            constexpr int NS = 2 * (DHP / 16), AHEAD = 3;
+            constexpr int NS = 2 * (DK / 16), AHEAD = 3;
             f32x16 accS[2];
             {
                 bf16x8 fr[NS];
                 auto kfrag = [&](int n) {
-                    const int i = n / (DHP / 16), kk = n % (DHP / 16);
+                    const int i = n / (DK / 16), kk = n % (DK / 16);
                     return *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + krow) * KLD + 16 * kk + 8 * g2]);
                 };
 #pragma unroll
@@ -177,7 +184,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
 #pragma unroll
                 for (int n = 0; n < NS; ++n) {
                     if (n + AHEAD < NS) fr[n + AHEAD] = kfrag(n + AHEAD);
-                    const int i = n / (DHP / 16), kk = n % (DHP / 16);
+                    const int i = n / (DK / 16), kk = n % (DK / 16);
                     accS[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[n], qf[kk], accS[i], 0, 0, 0);
                 }
                 // keep that order: AHEAD reads, then one read per MFMA
@@ -222,7 +229,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2) : 1.0f;
                 l_run *= alpha;
 #pragma unroll
-                for (int dt = 0; dt < DHP / 32; ++dt)
+                for (int dt = 0; dt < DV / 32; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) accO[dt][r] *= alpha;
                 m_run = move ? mx : m_run;
@@ -237,13 +244,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const float pv = __builtin_amdgcn_exp2f(fmaf(accS[i][8 * t2 + j], scale_log2, -ms));
-                        psum += pv;
+                        if (!ONES) psum += pv;
                         pf[i][t2][j] = (__bf16)pv;
                     }
             l_run += psum;
             // O^T += V^T * P^T
             {
-                constexpr int NP = (DHP / 32) * 4;
+                constexpr int NP = (DV / 32) * 4;
                 bf16x8 fr[NP];
                 auto vfrag = [&](int n) {
                     const int dt = n / 4, i = (n / 2) % 2, t2 = n % 2;
@@ -270,12 +277,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         __syncthreads();
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    // ONES: output row DV - 1 (tile DV/32 - 1, register 15 of the lanes 32..63) holds the sum of the probabilities
+    const float l_tot = ONES ? __shfl(accO[DV / 32 - 1][15], 32 + lq, 64) : l_run + __shfl_xor(l_run, 32, 64);
     if (tq >= p.T) return;
     if constexpr (SPLIT) {
-        float* prow = p.split_ws + ((size_t(blockIdx.z) * p.Hq + h) * p.T + tq) * (DHP + 4);
+        float* prow = p.split_ws + ((size_t(blockIdx.z) * p.Hq + h) * p.T + tq) * (DV + 4);
 #pragma unroll
-        for (int dt = 0; dt < DHP / 32; ++dt)
+        for (int dt = 0; dt < DV / 32; ++dt)
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int e0 = 32 * dt + 8 * rg + 4 * g2;
@@ -283,15 +291,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                     make_float4(accO[dt][4 * rg], accO[dt][4 * rg + 1], accO[dt][4 * rg + 2], accO[dt][4 * rg + 3]);
             }
         if (g2 == 0) {
-            prow[DHP] = m_run * scale_log2;            // reference of this run's exponentials, base-2 units
-            prow[DHP + 1] = l_tot;
+            prow[DV] = m_run * scale_log2;             // reference of this run's exponentials, base-2 units
+            prow[DV + 1] = l_tot;
         }
         return;
     }
     const float inv = l_tot > 0.0f ? 1.0f / l_tot : 0.0f;
     bf16_t* orow = p.out + size_t(tq) * p.ldo + size_t(h) * p.dh;
 #pragma unroll
-    for (int dt = 0; dt < DHP / 32; ++dt)
+    for (int dt = 0; dt < DV / 32; ++dt)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
             const int e0 = 32 * dt + 8 * rg + 4 * g2;
@@ -334,7 +342,7 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(AttnArgs p, int n_runs)
     if (e < p.dh) p.out[size_t(tq) * p.ldo + size_t(h) * p.dh + e] = f_to_bf16_attn(den > 0.0f ? num / den : 0.0f);
 }
 
-template <int DHP>
+template <int DK, int DV, bool ONES>
 void launch_attn(const AttnArgs& a, float scale_log2, hipStream_t st) {
     const int group = a.Hq / a.Hkv;
     const bool heads = group % 4 == 0;
@@ -345,16 +353,16 @@ void launch_attn(const AttnArgs& a, float scale_log2, hipStream_t st) {
         int n_runs = nt / 2 < 16 ? nt / 2 : 16;
         const int tps = (nt + n_runs - 1) / n_runs;
         n_runs = (nt + tps - 1) / tps;                       // every run has at least one tile
-        if (uint64_t(n_runs) * a.Hq * a.T * (DHP + 4) * 4 <= a.split_ws_bytes) {
+        if (uint64_t(n_runs) * a.Hq * a.T * (DV + 4) * 4 <= a.split_ws_bytes) {
             const dim3 g3(grid.x, grid.y, n_runs);
-            if (heads) hipLaunchKernelGGL((attn_kernel<DHP, true, true>), g3, dim3(256), 0, st, a, scale_log2, tps);
-            else hipLaunchKernelGGL((attn_kernel<DHP, false, true>), g3, dim3(256), 0, st, a, scale_log2, tps);
-            hipLaunchKernelGGL(attn_merge_kernel<DHP>, dim3(a.T, a.Hq), dim3(128), 0, st, a, n_runs);
+            if (heads) hipLaunchKernelGGL((attn_kernel<DK, DV, true, true, ONES>), g3, dim3(256), 0, st, a, scale_log2, tps);
+            else hipLaunchKernelGGL((attn_kernel<DK, DV, false, true, ONES>), g3, dim3(256), 0, st, a, scale_log2, tps);
+            hipLaunchKernelGGL(attn_merge_kernel<DV>, dim3(a.T, a.Hq), dim3(128), 0, st, a, n_runs);
             return;
         }
     }
-    if (heads) hipLaunchKernelGGL((attn_kernel<DHP, true, false>), grid, dim3(256), 0, st, a, scale_log2, 0);
-    else hipLaunchKernelGGL((attn_kernel<DHP, false, false>), grid, dim3(256), 0, st, a, scale_log2, 0);
+    if (heads) hipLaunchKernelGGL((attn_kernel<DK, DV, true, false, ONES>), grid, dim3(256), 0, st, a, scale_log2, 0);
+    else hipLaunchKernelGGL((attn_kernel<DK, DV, false, false, ONES>), grid, dim3(256), 0, st, a, scale_log2, 0);
 }
 
 }  // namespace
@@ -368,9 +376,14 @@ uint64_t attention_split_workspace_bytes(int T, int Hq, int dh) {
 void attention(const AttnArgs& a, hipStream_t st) {
     if (a.T <= 0 || a.S <= 0) return;
     const float scale_log2 = 1.4426950408889634f / sqrtf(float(a.dh));
-    if (a.dh <= 64) launch_attn<64>(a, scale_log2, st);
-    else if (a.dh <= 96) launch_attn<96>(a, scale_log2, st);
-    else launch_attn<128>(a, scale_log2, st);
+    // a padding row in the output tile (dh below its multiple of 32) carries the softmax denominator
+    if (a.dh < 64) launch_attn<64, 64, true>(a, scale_log2, st);
+    else if (a.dh == 64) launch_attn<64, 64, false>(a, scale_log2, st);
+    else if (a.dh <= 80) launch_attn<80, 96, true>(a, scale_log2, st);
+    else if (a.dh < 96) launch_attn<96, 96, true>(a, scale_log2, st);
+    else if (a.dh == 96) launch_attn<96, 96, false>(a, scale_log2, st);
+    else if (a.dh < 128) launch_attn<128, 128, true>(a, scale_log2, st);
+    else launch_attn<128, 128, false>(a, scale_log2, st);
 }
 
 }  // namespace dlk
