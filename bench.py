@@ -34,14 +34,31 @@ def log(*a):
 
 
 class ClockSampler:
-    """Samples the shader clock the driver reports (the starred level of pp_dpm_sclk) on a host thread while a region
-    runs; the paper locks clocks (Sec. V-A), an ordinary user on this machine cannot, so the observed clock is recorded
-    next to the result instead."""
+    """Samples the shader clock the driver reports (the starred level of pp_dpm_sclk) and the board power (hwmon
+    power1_input, with its cap) on a host thread while a region runs; the paper locks clocks (Sec. V-A), an ordinary
+    user on this machine cannot, so the observed clock and power are recorded next to the result instead."""
 
     def __init__(self, period_s=0.02):
         import glob
         self.paths = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
-        self.period, self.samples, self._stop, self._th = period_s, [], False, None
+        self.power_paths = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input"))
+        self.period, self.samples, self.power, self._stop, self._th = period_s, [], [], False, None
+
+    def _read_power(self):
+        for p in self.power_paths:
+            try:
+                return float(open(p).read()) * 1e-6          # microwatts
+            except Exception:
+                pass
+        return None
+
+    def power_cap_w(self):
+        for p in self.power_paths:
+            try:
+                return float(open(p.replace("power1_input", "power1_cap")).read()) * 1e-6
+            except Exception:
+                pass
+        return None
 
     def _read(self):
         for p in self.paths:
@@ -62,6 +79,9 @@ class ClockSampler:
                 v = self._read()
                 if v is not None:
                     self.samples.append(v)
+                w = self._read_power()
+                if w is not None:
+                    self.power.append(w)
                 time.sleep(self.period)
         self._th = threading.Thread(target=loop, daemon=True)
         self._th.start()
@@ -75,8 +95,13 @@ class ClockSampler:
         if not self.samples:
             return None
         v = np.array(self.samples)
-        return {"sclk_mhz_median": float(np.median(v)), "sclk_mhz_min": float(v.min()), "sclk_mhz_max": float(v.max()),
-                "samples": int(v.size), "source": "pp_dpm_sclk (current level), sampled on the host during the timed region"}
+        out = {"sclk_mhz_median": float(np.median(v)), "sclk_mhz_min": float(v.min()), "sclk_mhz_max": float(v.max()),
+               "samples": int(v.size), "source": "pp_dpm_sclk (current level), sampled on the host during the timed region"}
+        if self.power:
+            w = np.array(self.power)
+            out.update({"power_w_median": float(np.median(w)), "power_w_max": float(w.max()),
+                        "power_cap_w": self.power_cap_w(), "power_source": "hwmon power1_input / power1_cap"})
+        return out
 
 
 def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):

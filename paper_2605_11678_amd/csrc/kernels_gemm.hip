@@ -13,7 +13,7 @@
 //    directly (global_load_lds_dwordx4, no staging registers) into two LDS stages that are separate arrays, so
 //    the compiler can tell the stage being filled from the one being read; the wait for a copy is an explicit
 //    s_waitcnt.  LDS rows are 128 bytes, unpadded (a wavefront's copy fills 1 KB = 8 rows contiguously); the
-//    16-byte chunk index is XOR-swizzled with row%8 on both sides, which keeps the b128 fragment reads
+//    16-byte chunk index is XOR-swizzled with (row/2)%8 on both sides, which keeps the b128 fragment reads
 //    conflict-free.  Per k-tile four phases of up to 16 MFMAs, each interleaved with the fragment reads of the
 //    next phase through sched_group_barrier, ONE bare s_barrier, and the copy of the k-tile after the next
 //    spread over the two phases that follow the barrier (a whole k-tile of time to land).
@@ -522,16 +522,18 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
 
     // copy sources: block b = wave + 4*j of a tile holds rows 8b..8b+7, 128 bytes (one cache line, 64 k) each;
     // lane L lands at row 8b + L/8, physical 16-byte chunk L%8, and therefore fetches logical chunk
-    // (L%8) ^ (row%8).  Rows past the matrix edge are clamped: they produce values that the epilogue never stores.
+    // (L%8) ^ ((row/2)%8): a b128 fragment read serves 16 lanes (16 consecutive rows, 256 bytes of banks) at a time,
+    // two rows fill the 64 banks once, so the swizzle has to differ between the 8 row PAIRS (with row%8 the counters
+    // showed every second LDS cycle of the kernel as a bank conflict).  Rows past the matrix edge are clamped: they produce values that the epilogue never stores.
     uint32_t offA[JA], offB[JB];
 #pragma unroll
     for (int j = 0; j < JA; ++j) {
-        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ (row & 7);
+        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
         offA[j] = uint32_t((size_t(min(m0 + row, p.M - 1)) * p.lda + lc * 8) * 2);
     }
 #pragma unroll
     for (int j = 0; j < JB; ++j) {
-        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ (row & 7);
+        const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
         offB[j] = uint32_t((size_t(min(n0 + row, p.N - 1)) * p.ldb + lc * 8) * 2);
     }
     const char* gA = reinterpret_cast<const char*>(p.A);
@@ -541,7 +543,7 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
     int rdA[4], rdB[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-        const int pc = (2 * kk + g2) ^ (lr & 7);
+        const int pc = (2 * kk + g2) ^ ((lr >> 1) & 7);
         rdA[kk] = ((BM / 2) * wm + lr) * BK + pc * 8;
         rdB[kk] = BM * BK + ((BN / 2) * wn + lr) * BK + pc * 8;
     }
