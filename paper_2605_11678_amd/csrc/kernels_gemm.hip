@@ -293,8 +293,10 @@ __global__ __launch_bounds__(512) void gemm_few_rows(GemmArgs p) {
 
 
 // epilogue shared by both kernels: accumulator tile (i, j) of a wavefront whose tile starts at (mw, nw)
+// n_end: first column past the tile's own columns (the matrix edge, or the start of the next tile when the tile's
+// LDS width is padded beyond its stride)
 template <int EPI, int TM, int TN>
-__device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM][TN], int mw, int nw, int lane) {
+__device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM][TN], int mw, int nw, int lane, int n_end) {
     const int col_in = lane & 31, row_in = (lane >> 5) * 4;
     if (EPI == EPI_SWIGLU_BF16) {
         // even tile columns hold gate rows, the next odd one the matching up rows (packed in groups of 32)
@@ -332,7 +334,7 @@ __device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM]
             for (int jj = 0; jj < JB; ++jj) {
                 const int j = j0 + jj;
                 if (j >= TN) continue;
-                const int nc = min(nw + 32 * j + col_in, p.N - 1);
+                const int nc = min(nw + 32 * j + col_in, n_end - 1);
                 bias[jj] = p.bias ? bf16_to_f(p.bias[nc]) : 0.0f;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -352,7 +354,7 @@ __device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM]
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int m = mw + 32 * i + 8 * (r >> 2) + row_in + (r & 3);
-                        if (m < p.M && n < p.N) out[uint32_t(m) * uint32_t(p.ldo) + uint32_t(n)] = rv[jj][i][r] + acc[i][j][r] + bias[jj];
+                        if (m < p.M && n < n_end) out[uint32_t(m) * uint32_t(p.ldo) + uint32_t(n)] = rv[jj][i][r] + acc[i][j][r] + bias[jj];
                     }
             }
         }
@@ -361,7 +363,7 @@ __device__ __forceinline__ void store_tiles(const GemmArgs& p, f32x16 (&acc)[TM]
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
         const int n = nw + 32 * j + col_in;
-        if (n >= p.N) continue;
+        if (n >= n_end) continue;
         const float bias = p.bias ? bf16_to_f(p.bias[n]) : 0.0f;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
@@ -501,16 +503,20 @@ struct SchedEven {
     }
 };
 
-// One output tile with its top-left corner at (m0, n0).  S0 and S1 are the two LDS stages; they must be two distinct
-// __shared__ arrays of at least (BM + BN) * 64 elements each.
-template <int BM, int BN, int EPI>
-__device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf16_t* S0, bf16_t* S1) {
-    constexpr int BK = 64;
-    constexpr int TM = BM / 2 / 32, TN = BN / 2 / 32;
+// One output tile with its top-left corner at (m0, n0).  S0 .. S(NS-1) are the LDS stages; they must be distinct
+// __shared__ arrays of at least (BM + BN) * 64 elements each.  The four wavefronts form a WM x (4 / WM) grid.  BNR is
+// the number of columns the tile really owns (its stride in N): with BNR < BN the last BN - BNR columns are computed
+// from the next tile's weight rows and never stored (128 x 144 of 160: 4096 x 1152 outputs are then exactly 256 tiles).
+template <int BM, int BN, int EPI, int WM = 2, int BNR = BN, int NS = 2>
+__device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf16_t* S0, bf16_t* S1, bf16_t* S2 = nullptr,
+                                          bf16_t* S3 = nullptr) {
+    constexpr int BK = 64, WN = 4 / WM;
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int JA = BM / 32, JB = BN / 32;            // 1 KB copy blocks (8 rows x 128 B) per wavefront and k-tile
     constexpr int RT = TM * TN / 4;
+    static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "whole MFMA tiles per wavefront");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -544,8 +550,8 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         const int pc = (2 * kk + g2) ^ ((lr >> 1) & 7);
-        rdA[kk] = ((BM / 2) * wm + lr) * BK + pc * 8;
-        rdB[kk] = BM * BK + ((BN / 2) * wn + lr) * BK + pc * 8;
+        rdA[kk] = ((BM / WM) * wm + lr) * BK + pc * 8;
+        rdB[kk] = BM * BK + ((BN / WN) * wn + lr) * BK + pc * 8;
     }
 
     bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
@@ -576,68 +582,114 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
     };
 
     const int nk = p.K / BK;                             // host guarantees K % 128 == 0: nk is even and >= 2
-    copyA(S0, 0); copyB(S0, 0);
-    copyA(S1, 1);
-    DL_WAIT_VM(JA);                                      // k-tile 0 has landed (this wavefront's share)
-    __builtin_amdgcn_s_barrier();
-    ldfrag(a0, b0, S0, 0);
-    __builtin_amdgcn_sched_barrier(0);
 
     // One k-tile = four phases of TM*TN MFMAs (16-wide k steps), each overlapped with the fragment reads of the next
     // phase.  Before the last phase the wavefront waits for its own copies of k-tile kt+1 and for all of its LDS reads
     // and meets the others at the one barrier of the k-tile; past it (a) k-tile kt+1 has landed for everyone and
-    // (b) nobody reads stage kt any more, so the copy of k-tile kt+2 into that stage starts right there: its A half
-    // is spread over the last phase, its B half over the first phase of the next k-tile, which gives every copy
-    // almost a whole k-tile (64 MFMAs per wavefront) to land.
-    auto ktile = [&](bf16_t* cur, bf16_t* oth, int kt, auto last_c) {
-        constexpr int LAST = decltype(last_c)::value;    // 0: steady state, 1: second to last k-tile, 2: last k-tile
+    // (b) nobody reads stage kt any more, so the copy of k-tile kt+NS into that stage starts right there: its A half
+    // is spread over the last phase, its B half over the first phase of the next k-tile.  With NS = 2 stages a copy has
+    // one k-tile of MFMAs to land (64 per wavefront for the large tiles: enough); a small tile's k-tile is 16-20 MFMAs,
+    // so it runs NS = 4 stages and its copies have three k-tiles.
+    // REM = k-tiles after this one, capped at NS (the steady state): with fewer than NS - 1 left the copy's B half has
+    // nothing to fetch, with fewer than NS its A half; the wait leaves the copies younger than k-tile kt+1 in flight.
+    auto ktile = [&](bf16_t* cur, bf16_t* nxt, bf16_t* prv, int kt, auto rem_c) {
+        constexpr int REM = decltype(rem_c)::value;
+        constexpr bool kB = REM >= NS - 1, kA = REM >= NS;
         ldfrag(a1, b1, cur, 1);
-        if (LAST != 2) copyB(oth, kt + 1);               // second half of the copy begun in the previous k-tile
+        if (kB) copyB(prv, kt + NS - 1);                 // second half of the copy begun in the previous k-tile
         mma(a0, b0);
-        interleave(std::integral_constant<int, (LAST != 2 ? JB : 0)>{});
+        interleave(std::integral_constant<int, (kB ? JB : 0)>{});
         ldfrag(a0, b0, cur, 2);
         mma(a1, b1);
         interleave(std::integral_constant<int, 0>{});
         ldfrag(a1, b1, cur, 3);
         mma(a0, b0);
         interleave(std::integral_constant<int, 0>{});
-        if (LAST != 2) {
-            DL_WAIT_VM_LGKM0(0);
+        if constexpr (REM >= 1) {
+            constexpr int younger = (REM - 1 < NS - 2 ? REM - 1 : NS - 2) * (JA + JB);
+            DL_WAIT_VM_LGKM0(younger);
             __builtin_amdgcn_s_barrier();
             __builtin_amdgcn_sched_barrier(0);
-            ldfrag(a0, b0, oth, 0);
-            if (LAST == 0) copyA(cur, kt + 2);
+            ldfrag(a0, b0, nxt, 0);
+            if (kA) copyA(cur, kt + NS);
             mma(a1, b1);
-            interleave(std::integral_constant<int, (LAST == 0 ? JA : 0)>{});
+            interleave(std::integral_constant<int, (kA ? JA : 0)>{});
         } else {
             mma(a1, b1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    int kt = 0;
-    for (; kt + 2 < nk; kt += 2) {
-        ktile(S0, S1, kt, std::integral_constant<int, 0>{});
-        ktile(S1, S0, kt + 1, std::integral_constant<int, 0>{});
+    using std::integral_constant;
+    if constexpr (NS == 2) {
+        copyA(S0, 0); copyB(S0, 0);
+        copyA(S1, 1);
+        DL_WAIT_VM(JA);                                  // k-tile 0 has landed (this wavefront's share)
+        __builtin_amdgcn_s_barrier();
+        ldfrag(a0, b0, S0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        int kt = 0;
+        for (; kt + 2 < nk; kt += 2) {
+            ktile(S0, S1, S1, kt, integral_constant<int, 2>{});
+            ktile(S1, S0, S0, kt + 1, integral_constant<int, 2>{});
+        }
+        ktile(S0, S1, S1, kt, integral_constant<int, 1>{});
+        ktile(S1, S0, S0, kt + 1, integral_constant<int, 0>{});
+    } else {
+        static_assert(NS == 4, "two or four stages");
+        // the host takes this path only for nk >= 4; nk is even, so nk % 4 is 0 or 2
+        copyA(S0, 0); copyB(S0, 0);
+        copyA(S1, 1); copyB(S1, 1);
+        copyA(S2, 2); copyB(S2, 2);
+        copyA(S3, 3);
+        DL_WAIT_VM(2 * (JA + JB) + JA);                  // k-tile 0 has landed (this wavefront's share)
+        __builtin_amdgcn_s_barrier();
+        ldfrag(a0, b0, S0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        int kt = 0;
+        for (; kt + 8 <= nk; kt += 4) {                  // whole groups of four in the steady state
+            ktile(S0, S1, S3, kt, integral_constant<int, 4>{});
+            ktile(S1, S2, S0, kt + 1, integral_constant<int, 4>{});
+            ktile(S2, S3, S1, kt + 2, integral_constant<int, 4>{});
+            ktile(S3, S0, S2, kt + 3, integral_constant<int, 4>{});
+        }
+        if (nk - kt == 4) {
+            ktile(S0, S1, S3, kt, integral_constant<int, 3>{});
+            ktile(S1, S2, S0, kt + 1, integral_constant<int, 2>{});
+            ktile(S2, S3, S1, kt + 2, integral_constant<int, 1>{});
+            ktile(S3, S0, S2, kt + 3, integral_constant<int, 0>{});
+        } else {                                         // six left: two more in the steady state, then the last four
+            ktile(S0, S1, S3, kt, integral_constant<int, 4>{});
+            ktile(S1, S2, S0, kt + 1, integral_constant<int, 4>{});
+            ktile(S2, S3, S1, kt + 2, integral_constant<int, 3>{});
+            ktile(S3, S0, S2, kt + 3, integral_constant<int, 2>{});
+            ktile(S0, S1, S3, kt + 4, integral_constant<int, 1>{});
+            ktile(S1, S2, S0, kt + 5, integral_constant<int, 0>{});
+        }
     }
-    ktile(S0, S1, kt, std::integral_constant<int, 1>{});
-    ktile(S1, S0, kt + 1, std::integral_constant<int, 2>{});
 
     // wavefront tile wholly inside the matrix (SwiGLU: inside the packed gate/up columns): unpredicated epilogue
-    const int mw = m0 + (BM / 2) * wm, nw = n0 + (BN / 2) * wn;
-    if (mw + BM / 2 <= p.M && nw + BN / 2 <= p.N) store_tiles_full<EPI, TM, TN>(p, acc, mw, nw, lane);
-    else store_tiles<EPI, TM, TN>(p, acc, mw, nw, lane);
+    const int mw = m0 + (BM / WM) * wm, nw = n0 + (BN / WN) * wn;
+    const int n_end = min(p.N, n0 + BNR);
+    if (mw + BM / WM <= p.M && nw + BN / WN <= n_end) store_tiles_full<EPI, TM, TN>(p, acc, mw, nw, lane);
+    else store_tiles<EPI, TM, TN>(p, acc, mw, nw, lane, n_end);
 }
 
 // 128-row tiles leave room for two workgroups per compute unit (at most 80 KB of LDS and 128 accumulators each): one's
 // prologue and epilogue hide under the other's main loop.
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256, (BM == 128 && BN <= 192) ? 2 : 1) void gemm_fast(GemmArgs p) {
+template <int BM, int BN, int EPI, int WM = 2, int BNR = BN, int NS = 2>
+__global__ __launch_bounds__(256, (BM == 128 && BN <= 192 && NS == 2) ? 2 : 1) void gemm_fast(GemmArgs p) {
     __shared__ __attribute__((aligned(1024))) bf16_t S0[(BM + BN) * 64];
     __shared__ __attribute__((aligned(1024))) bf16_t S1[(BM + BN) * 64];
-    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BN - 1) / BN;
+    const int tiles_m = (p.M + BM - 1) / BM, tiles_n = (p.N + BNR - 1) / BNR;
     int tm, tn;
     if (!tile_of(blockIdx.x, tiles_m, tiles_n, &tm, &tn)) return;
-    fast_tile<BM, BN, EPI>(p, tm * BM, tn * BN, S0, S1);
+    if constexpr (NS == 4) {
+        __shared__ __attribute__((aligned(1024))) bf16_t S2[(BM + BN) * 64];
+        __shared__ __attribute__((aligned(1024))) bf16_t S3[(BM + BN) * 64];
+        fast_tile<BM, BN, EPI, WM, BNR, 4>(p, tm * BM, tn * BNR, S0, S1, S2, S3);
+    } else {
+        fast_tile<BM, BN, EPI, WM, BNR, 2>(p, tm * BM, tn * BNR, S0, S1);
+    }
 }
 
 // 256x256 tiles whose count is r full rounds of 256 workgroups plus a remainder of at most half a round: the last
@@ -661,9 +713,9 @@ __global__ __launch_bounds__(256) void gemm_fast_split_tail(GemmArgs p, int n_bi
     }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int WM = 2, int BNR = BN, int NS = 2>
 void launch_fast(const GemmArgs& a, hipStream_t st) {
-    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BN - 1) / BN);
+    const int tiles = ((a.M + BM - 1) / BM) * ((a.N + BNR - 1) / BNR);
     if (BM == 256 && BN == 256) {
         // tile_of deals tiles to 8 XCDs in equal shares: the split needs every virtual index below `tiles` to be valid
         const int rem = tiles % 256;
@@ -674,10 +726,10 @@ void launch_fast(const GemmArgs& a, hipStream_t st) {
         }
     }
     const int grid = (tiles + 7) / 8 * 8;
-    hipLaunchKernelGGL((gemm_fast<BM, BN, EPI>), dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((gemm_fast<BM, BN, EPI, WM, BNR, NS>), dim3(grid), dim3(256), 0, st, a);
 }
 
-// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192, 4 = 128x192, 5 = 128x128.  Cost of
+// tile shape for the fast path: 0 = 256x256, 1 = 192x256, 2 = 256x192, 3 = 192x192, 4 = 128x192, 5 = 128x128, 6 = 128x144.  Cost of
 // a shape = rounds of workgroup slots x tile area / relative efficiency, the efficiencies fitted to measured launch
 // times.  Shapes 0-3 hold one workgroup per compute unit (256 slots).  128x192 and 128x128 need at most 80 KB of LDS,
 // so two workgroups share a compute unit (512 slots at half speed each, but one's prologue and epilogue hide under the
@@ -689,6 +741,13 @@ int pick_tile(int M, int N, int K, bool need_even_cols) {
     const bool small_ok = K <= 2048 || N <= 1536;
     int best = 0;
     double best_cost = 1e300;
+    // 6 = 128x144 (stored columns; 160 in LDS), four wavefronts stacked in M: taken when it gives every compute unit at
+    // most one tile (4096 x 1152 outputs = exactly 256 tiles), where the 128x128 tiles put two on some compute units
+    // and all of them are bound by the global -> LDS rate (a 128x128 tile moves 32 KB per 16 MFMAs of a wavefront)
+    if (!need_even_cols && small_ok) {
+        const long tiles6 = long((M + 127) / 128) * ((N + 143) / 144);
+        if (tiles6 <= 256 && K >= 2048) { best = 6; best_cost = 128.0 * 144.0 / 0.9; }
+    }
     for (int c = 0; c < 6; ++c) {
         if (need_even_cols && bn[c] % 128 != 0) continue;   // gate/up pairs need an even number of 32-wide column tiles
         if (c >= 4 && !small_ok) continue;
@@ -711,6 +770,7 @@ void dispatch_fast(const GemmArgs& a, hipStream_t st) {
         // odd numbers of 32-wide tile columns per wavefront cannot pair gate/up rows: never chosen for SwiGLU
         if (t == 2) launch_fast<256, 192, EPI>(a, st);
         else if (t == 3) launch_fast<192, 192, EPI>(a, st);
+        else if (t == 6) launch_fast<128, 160, EPI, 4, 144, 4>(a, st);
         else launch_fast<128, 192, EPI>(a, st);
     }
 }

@@ -1,6 +1,6 @@
 """GPU parity of the GEMM kernels over the tile shapes the dispatcher can pick, through the C-ABI's two-layer
 perceptron (dl_mlp_forward: y = GELU(x W1^T + b1) W2^T + b2, Sec. II-A stage 2).  The first product takes the
-fast MFMA path with the GELU epilogue in every tile shape (128x128, 128x192, 192x192, 192x256, 256x192, 256x256, and 256x256
+fast MFMA path with the GELU epilogue in every tile shape (128x128, 128x144 on four LDS stages with both loop tails, 128x192, 192x192, 192x256, 256x192, 256x256, and 256x256
 with the last half round split into 128x256 halves), the generic kernel, or, with at most 64 rows and K a multiple
 of 64, the few-rows kernel; the second one (fp32 output) takes the generic or the few-rows kernel.  Rows are independent, so the oracle evaluates a sample of rows that covers the first and
 last row, tile borders and the ragged tail."""
@@ -24,6 +24,8 @@ SHAPES = [
     (97, 256, 384, 64, "128x128, a single ragged row tile"),
     (300, 1152, 1152, 96, "128x128, narrow output, ragged last row tile"),
     (4000, 1152, 4352, 64, "128x192, short reduction, ragged last row tile"),
+    (1000, 2304, 1152, 64, "128x144 of 160, four stages, 36 k-tiles (tail of four), ragged last row tile"),
+    (300, 2176, 1096, 64, "128x144 of 160, four stages, 34 k-tiles (tail of six), last column tile cut by the matrix edge"),
     (1000, 2304, 4096, 64, "192x192"),
     (3072, 2176, 4096, 64, "192x256"),
     (4096, 2176, 3072, 64, "256x192"),
