@@ -133,6 +133,12 @@ def _enc_small():
     return CFG.ModuleConfig("enc_small", 2, 144, 2, 2, 72, 536, CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, seed_base=4100)
 
 
+def _enc_dh(dh):
+    # two heads of an odd width: the attention kernel's other score / output paddings (40 -> 64 x 64 with a denominator
+    # row, 88 -> 96 x 96 with one, 96 -> 96 x 96 without, 112 -> 128 x 128 with one)
+    return CFG.ModuleConfig("enc_dh%d" % dh, 2, 2 * dh, 2, 2, dh, 536, CFG.NORM_LN, CFG.ACT_GELU, 1, 0, 0.0, seed_base=4500 + dh)
+
+
 def _gqa_small(dh, max_seq=384):
     return CFG.ModuleConfig("gqa_small", 2, 8 * dh, 8, 2, dh, 1056, CFG.NORM_RMS, CFG.ACT_SWIGLU, 0, 1, 1e6,
                             max_seq=max_seq, seed_base=4200 + dh, vocab=0)
@@ -163,6 +169,14 @@ CASES = [
     Case("gqa_dh64", _gqa_small(64), GQA_PASSES, 23),
     Case("gqa_dh128", _gqa_small(128), GQA_PASSES, 23),
     Case("gqa_nocache", _gqa_small(64, max_seq=0), [(0, 130)], 43),
+    # head widths between the attention kernel's paddings, causal with a cache (prefill, chunk over the cache, single tokens)
+    Case("gqa_dh88", _gqa_small(88), GQA_PASSES, 23),
+    Case("gqa_dh96", _gqa_small(96), GQA_PASSES, 23),
+    Case("gqa_dh112", _gqa_small(112), GQA_PASSES, 23),
+    # and bidirectional, four 32-query slices of one head per workgroup, ragged token counts
+    Case("enc_dh40_T150", _enc_dh(40), [(0, 150)], 19),
+    Case("enc_dh96_T200", _enc_dh(96), [(0, 200)], 19),
+    Case("enc_dh112_T131", _enc_dh(112), [(0, 131)], 19),
     # edges: 32 query heads on ONE KV head (the most the single-token attention kernel's tile takes), head dimension 8,
     # passes that end exactly at the cache's last position, a single context row
     Case("gqa_group32_dh8", CFG.ModuleConfig("g32", 2, 256, 32, 1, 8, 512, CFG.NORM_RMS, CFG.ACT_SWIGLU, 0, 1, 1e4,
