@@ -569,12 +569,15 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
 #pragma unroll
         for (int j = 0; j < TN; ++j) b[j] = *reinterpret_cast<const bf16x8*>(S + rdB[kk] + 32 * j * BK);
     };
+    // serpentine order over the accumulator tiles: from one MFMA to the next exactly one operand changes
     auto mma = [&](const bf16x8* a, const bf16x8* b) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+            for (int jj = 0; jj < TN; ++jj) {
+                const int j = (i & 1) ? TN - 1 - jj : jj;
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+            }
     };
     auto interleave = [&](auto ncopy_c) {
         SchedEven<TM * TN, TM + TN, decltype(ncopy_c)::value, RT, 0>::run();
