@@ -42,19 +42,35 @@ __device__ __forceinline__ bf16_t f_to_bf16_attn(float f) {
     return *reinterpret_cast<bf16_t*>(&b);
 }
 
+#define DL_ATT_GLL16(g, l)                                                                               \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
+                                     (__attribute__((address_space(3))) void*)(l), 16, 0, 0)
+
+// K / V^T tiles sit in LDS without padding, filled by global -> LDS copies (a wavefront instruction lands 64 chunks of
+// 16 bytes contiguously).  A b128 fragment read serves 16 lanes = 16 rows of one logical chunk per cycle across 64
+// banks (256 bytes), so the physical chunk is the logical one XORed with a function of the row that makes those 16
+// slots distinct: rows of 128 bytes (8 chunks): (row / 2) % 8; 160 bytes (10): (row / 8) % 2; 192 bytes (12):
+// (row / 4) % 4; 256 bytes (16): row % 16.
+template <int CPR>
+__device__ __forceinline__ int chunk_swizzle(int row) {
+    return CPR == 8 ? (row >> 1) & 7 : (CPR == 10 ? (row >> 3) & 1 : (CPR == 12 ? (row >> 2) & 3 : row & 15));
+}
+
 // SPLIT: the launch's z dimension divides the K/V tiles into runs of `tps` tiles; a workgroup handles one run and
 // writes, per query and head, its unnormalised output, reference maximum and sum to p.split_ws
 // ([run][head][query][DV + 4] floats) for attn_merge_kernel.  Used for few queries over many keys (cross-attention
 // of a short sequence), where a launch would otherwise consist of a handful of workgroups walking the whole key range.
 template <int DK, int DV, bool HEADS, bool SPLIT, bool ONES>
 __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_log2, int tps) {
-    constexpr int KLD = DK + 8;      // sK row stride (elements)
-    constexpr int VLD = BKV + 8;     // sV row stride
     constexpr int QB = HEADS ? 32 : 128;
-    constexpr int KCH = BKV * (DK / 8);                                       // 16-byte chunks of a K tile
-    constexpr int NKC = (KCH + 255) / 256, NVC = DV * (BKV / 8) / 256;        // chunks per thread
-    __shared__ __attribute__((aligned(16))) bf16_t sK[2][BKV * KLD];
-    __shared__ __attribute__((aligned(16))) bf16_t sV[2][DV * VLD];
+    constexpr int KCPR = DK / 8;                        // 16-byte chunks per K row; a K tile is KCPR copy instructions
+    constexpr int NKI = (KCPR + 3) / 4, NVI = DV / 32;  // copy instructions per wavefront and tile (K, V^T)
+    static_assert(KCPR == 8 || KCPR == 10 || KCPR == 12 || KCPR == 16, "swizzle defined for these row lengths");
+    // two stages as separate arrays: the compiler can tell the stage being filled from the one being read
+    __shared__ __attribute__((aligned(1024))) bf16_t sK0[BKV * DK];
+    __shared__ __attribute__((aligned(1024))) bf16_t sK1[BKV * DK];
+    __shared__ __attribute__((aligned(1024))) bf16_t sV0[DV * BKV];
+    __shared__ __attribute__((aligned(1024))) bf16_t sV1[DV * BKV];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lq = lane & 31, g2 = lane >> 5;
@@ -104,42 +120,42 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     const int t_begin = SPLIT ? int(blockIdx.z) * tps : 0;
     const int nt = SPLIT ? min(nt_all, t_begin + tps) : nt_all;      // tiles t_begin .. nt - 1
 
-    // Loads are unconditional with clamped addresses (no branches, nothing waits on a load before the stash):
+    // Copies are unconditional with clamped addresses:
     //  * K rows past S repeat row S-1; those keys are masked to -inf (a tile that contains them is always masked);
     //  * feature chunks past dh (zero padding of the head dimension) re-read chunk 0: they meet zero Q features;
     //  * V^T rows past dh repeat row dh-1 (they produce output features nobody stores); V^T position chunks that
     //    start past S re-read the chunk at 0, and a chunk that straddles S brings along up to 7 stale positions:
     //    their probabilities are exact zeros and the buffers hold finite numbers everywhere (zeroed when the
     //    module is finalised, rows padded to a multiple of 64 positions);
-    //  * ONES: the last V^T row of the tile (a padding row) is replaced by ones when it is stashed.
-    u32x4 rk[NKC], rv[NVC];
-    auto fetch = [&](int j0) {
+    //  * ONES: the last V^T row of a stage (a padding row) holds ones, written once below; the copies skip it.
+    // Copy instruction ii of a K tile lands chunks 64 ii .. 64 ii + 63 of the row-major tile (row = id / KCPR); of a
+    // V^T tile rows 8 ii .. 8 ii + 7.  A lane fetches the LOGICAL chunk that belongs at its physical position.
+    auto copy_tile = [&](int j0, bf16_t* sKd, bf16_t* sVd) {
 #pragma unroll
-        for (int i = 0; i < NKC; ++i) {
-            const int c = min(tid + 256 * i, KCH - 1), row = c / (DK / 8), kc = (c % (DK / 8)) * 8;
-            rk[i] = *reinterpret_cast<const u32x4*>(kbase + size_t(min(j0 + row, p.S - 1)) * p.ldk + (kc < p.dh ? kc : 0));
+        for (int i = 0; i < NKI; ++i) {
+            const int ii = wave + 4 * i;
+            if (KCPR % 4 != 0 && ii >= KCPR) continue;           // wavefront-uniform
+            const int id = 64 * ii + lane, row = id / KCPR, c = (id % KCPR) ^ chunk_swizzle<KCPR>(row);
+            DL_ATT_GLL16(kbase + size_t(min(j0 + row, p.S - 1)) * p.ldk + (8 * c < p.dh ? 8 * c : 0), sKd + 512 * ii);
         }
 #pragma unroll
-        for (int i = 0; i < NVC; ++i) {
-            const int c = tid + 256 * i, e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
-            rv[i] = *reinterpret_cast<const u32x4*>(vbase + size_t(min(e, p.dh - 1)) * p.ldv + (j0 + jc < p.S ? j0 + jc : 0));
-        }
-    };
-    auto stash = [&](int s) {
-#pragma unroll
-        for (int i = 0; i < NKC; ++i) {
-            const int c = tid + 256 * i, row = c / (DK / 8), kc = (c % (DK / 8)) * 8;
-            if (KCH % 256 == 0 || c < KCH) *reinterpret_cast<u32x4*>(&sK[s][row * KLD + kc]) = rk[i];
-        }
-#pragma unroll
-        for (int i = 0; i < NVC; ++i) {
-            const int c = tid + 256 * i, e = c / (BKV / 8), jc = (c % (BKV / 8)) * 8;
-            const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};        // bf16 1.0 pairs
-            *reinterpret_cast<u32x4*>(&sV[s][e * VLD + jc]) = (ONES && e == DV - 1) ? ones : rv[i];
+        for (int i = 0; i < NVI; ++i) {
+            const int ii = wave + 4 * i;
+            const int row = 8 * ii + (lane >> 3), c = (lane & 7) ^ chunk_swizzle<8>(row);
+            const bf16_t* src = vbase + size_t(min(row, p.dh - 1)) * p.ldv + (j0 + 8 * c < p.S ? j0 + 8 * c : 0);
+            if (ONES && ii == DV / 8 - 1) {                      // the last row of the tile keeps its ones
+                if (lane < 56) DL_ATT_GLL16(src, sVd + 512 * ii);
+            } else {
+                DL_ATT_GLL16(src, sVd + 512 * ii);
+            }
         }
     };
+    if (ONES && tid < 16) {
+        const u32x4 ones = {0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};            // bf16 1.0 pairs
+        *reinterpret_cast<u32x4*>((tid < 8 ? sV0 : sV1) + (DV - 1) * BKV + 8 * (tid & 7)) = ones;
+    }
 
-    fetch(t_begin * BKV);                              // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
+    copy_tile(t_begin * BKV, sK0, sV0);                // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
     bf16x8 qf[DK / 16];
 #pragma unroll
     for (int kk = 0; kk < DK / 16; ++kk) {
@@ -147,7 +163,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         const u32x4 z = {0u, 0u, 0u, 0u};
         u32x4 v = (tq < p.T && e < p.dh) ? qv[kk] : z;      // queries past T and padding features are zero
         // pass the words through a register move: inside the tile loop the fragments are then results of vector
-        // instructions, and the compiler does not put a wait for ALL outstanding loads (the prefetch of the next
+        // instructions, and the compiler does not put a wait for ALL outstanding loads (the copy of the next
         // K/V tile included) in front of the first MFMA that reads them
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
@@ -157,11 +173,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         }
         qf[kk] = *reinterpret_cast<bf16x8*>(&v);
     }
-    stash(0);
-    __syncthreads();
-    for (int t = t_begin; t < nt; ++t) {
-        const int j0 = t * BKV, s = (t - t_begin) & 1;
-        if (t + 1 < nt) fetch(j0 + BKV);
+    __builtin_amdgcn_s_waitcnt(0);                     // the first tile and the ones rows are in place
+    __builtin_amdgcn_s_barrier();
+    // one K/V tile: cK / cV the stage it is read from, nK / nV the stage the next tile is copied into meanwhile
+    auto tile_step = [&](int t, const bf16_t* cK, const bf16_t* cV, bf16_t* nK, bf16_t* nV) {
+        const int j0 = t * BKV;
+        if (t + 1 < nt) copy_tile(j0 + BKV, nK, nV);
         // a wavefront whose queries all lie before this tile has nothing to add (causal)
         const bool active = !p.causal || j0 <= wave_last;
         if (active) {
@@ -173,7 +190,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 bf16x8 fr[NS];
                 auto kfrag = [&](int n) {
                     const int i = n / (DK / 16), kk = n % (DK / 16);
-                    return *reinterpret_cast<const bf16x8*>(&sK[s][(32 * i + krow) * KLD + 16 * kk + 8 * g2]);
+                    const int row = 32 * i + krow, pc = (2 * kk + g2) ^ chunk_swizzle<KCPR>(row);
+                    return *reinterpret_cast<const bf16x8*>(cK + row * DK + 8 * pc);
                 };
 #pragma unroll
                 for (int n = 0; n < AHEAD; ++n) fr[n] = kfrag(n);
@@ -254,7 +272,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 bf16x8 fr[NP];
                 auto vfrag = [&](int n) {
                     const int dt = n / 4, i = (n / 2) % 2, t2 = n % 2;
-                    return *reinterpret_cast<const bf16x8*>(&sV[s][(32 * dt + lq) * VLD + 32 * i + 16 * t2 + 8 * g2]);
+                    const int row = 32 * dt + lq, pc = (4 * i + 2 * t2 + g2) ^ chunk_swizzle<8>(row);
+                    return *reinterpret_cast<const bf16x8*>(cV + row * BKV + 8 * pc);
                 };
 #pragma unroll
                 for (int n = 0; n < AHEAD; ++n) fr[n] = vfrag(n);
@@ -273,8 +292,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        if (t + 1 < nt) stash(s ^ 1);
-        __syncthreads();
+        // this wavefront's copies of the next tile have landed and its fragment reads are done; past the barrier that
+        // holds for the whole workgroup
+        __builtin_amdgcn_s_waitcnt(0);
+        __builtin_amdgcn_s_barrier();
+    };
+    for (int t = t_begin; t < nt; t += 2) {
+        tile_step(t, sK0, sV0, sK1, sV1);
+        if (t + 1 < nt) tile_step(t + 1, sK1, sV1, sK0, sV0);
     }
 
     // ONES: output row DV - 1 (tile DV/32 - 1, register 15 of the lanes 32..63) holds the sum of the probabilities
