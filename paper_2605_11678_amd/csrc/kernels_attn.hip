@@ -10,8 +10,8 @@
 // MFMA rows with bits 2 and 3 of the row index swapped, which makes those 8 k-values 8 consecutive keys.
 // V is kept transposed in memory ([feature][position]) so V^T tiles are plain row loads.
 //
-// Block: 4 wavefronts, K/V tiles of 64 positions in LDS, double-buffered; the next tile is fetched into
-// registers while the current one is multiplied.  Two work splits:
+// Block: 4 wavefronts, K/V tiles of 64 positions in LDS, two stages; the next tile is copied global -> LDS
+// directly (no staging registers) while the current one is multiplied.  Two work splits:
 //   HEADS = true  (grouped-query attention, group size a multiple of 4): the four wavefronts are four
 //                  query heads of ONE KV head on the same 32 query positions, so a K/V tile is loaded once
 //                  for four heads;
