@@ -292,13 +292,18 @@ int32_t dl_vla_infer(dl_ctx* ctx, const dl_vla_desc* desc, const dl_vla_buffers*
 /* ---- measurement ------------------------------------------------------------------------ */
 
 typedef struct {
-    double c_dma_ms;      /* un-overlapped host-to-device copy time of the layer */
+    double c_dma_ms;      /* un-overlapped host-to-device copy time of the layer: an isolated copy, the copy queue
+                             idle before and after it */
+    double c_dma_cont_ms; /* copy time of the layer inside an uninterrupted train of copies (the next one already
+                             queued when this one ends): what a copy costs while the copy queue never runs dry */
     double c_exe_ms;      /* un-overlapped execution time of the layer, run right after its copy (the GPU was idle) */
     double c_exe_hot_ms;  /* execution time of the layer inside an uninterrupted run of all layers (no copies, no
                              idle gaps): what a layer costs when compute is continuous, e.g. between resident layers */
     double c_fence_ms;    /* the two cross-stream hand-offs of a streamed layer (copy end -> its first kernel, its last
-                             kernel -> next copy start) as the sequential run shows them; charged to the compute
-                             stream per streamed layer by dl_timeline */
+                             kernel -> next copy start) as the sequential run shows them, less what the timing events
+                             themselves cost (a sequential pass without them is timed too, and the hand-offs are
+                             reduced so that copies + executions + hand-offs add up to that pass); charged to the
+                             compute stream per streamed layer by dl_timeline */
     uint64_t bytes;       /* bytes one copy moves */
 } dl_layer_profile;
 
@@ -401,6 +406,8 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * The n layer invocations of all passes are flattened: c_dma_ms[j], c_exe_ms[j] = times of
  * invocation j; streamed[j] != 0 if its parameters are copied; pass_start[j] != 0 marks the first
  * layer of a pass; module_id[j] (NULL = all the same) tells passes over different stacks apart.
+ * c_dma_cont_ms (NULL = same as c_dma_ms): copy time of invocation j when its copy starts at the very
+ * instant the previous copy ended, i.e. the copy queue did not wait in between (dl_profile measures both).
  * c_exe_idle_ms (NULL = same as c_exe_ms): time of invocation j when the compute queue sat idle
  * waiting for its copy right before it (a GPU that idled runs the next kernels slower than one
  * kept busy; dl_profile measures both).  c_fence_ms (NULL = zeros): time added on the compute queue to
@@ -408,8 +415,8 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * mode, wrap_prefetch: as dl_set_mode; n_slots: as dl_set_slot_count (1 .. 4).  overhead_ms is added to every
  * execution (fixed host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
  * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
-int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
-                    const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+int32_t dl_timeline(const double* c_dma_ms, const double* c_dma_cont_ms, const double* c_exe_ms,
+                    const double* c_exe_idle_ms, const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
                     int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms);
 

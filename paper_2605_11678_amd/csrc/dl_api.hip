@@ -1328,6 +1328,9 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     c->book.n_slots = c->n_slots;
     const int32_t Ln = M->d.n_layers;
     std::vector<double> dma(size_t(Ln), 0.0), exe(size_t(Ln), 0.0), hot(size_t(Ln), 0.0), fence(size_t(Ln), 0.0);
+    double timed_span = 0.0;         // first copy start -> last kernel end of the passes with timing events, summed
+    double fence_excess = 0.0;       // per layer: what the timing events added to a sequential pass
+    double cont_scale = 1.0;         // copy time inside a train of copies / isolated copy time
     for (int32_t it = 0; it < iters && rc == DL_OK; ++it) {
         rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
         if (rc) break;
@@ -1345,6 +1348,71 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
             const double in = double(recs[size_t(i)].exe_start_ms) - recs[size_t(i)].dma_end_ms;
             const double outw = i + 1 < Ln ? double(recs[size_t(i + 1)].dma_start_ms) - recs[size_t(i)].exe_end_ms : in;
             fence[size_t(i)] += std::max(0.0, in) + std::max(0.0, outw);
+        }
+        timed_span += double(recs[size_t(Ln - 1)].exe_end_ms) - recs[0].dma_start_ms;
+    }
+    // The event pair around every copy and every layer costs a few microseconds each, and in a sequential pass all
+    // of it lands in the gaps between the operations, i.e. in the hand-off figure.  Passes that are timed
+    // in one piece (first copy enqueued -> last kernel done) show what a pass costs without those events; the
+    // difference, spread over the layers, is taken off the hand-offs.
+    // Copies are also faster when the next one is already queued as one ends (pipelined runs that are bound by
+    // the copies keep the copy queue full) than each one is with an idle queue on both sides: a train of all
+    // layers' copies into the slots, timed in one piece, gives the ratio.
+    if (rc == DL_OK) {
+        constexpr int32_t kReps = 3;
+        double whole[kReps] = {0, 0, 0}, train[kReps] = {0, 0, 0};
+        c->timing = false;
+        for (int32_t rep = 0; rep < kReps && rc == DL_OK; ++rep) {
+            hipEvent_t e0 = nullptr, e1 = nullptr;
+            rc = timing_event(c, &e0);
+            if (rc == DL_OK) rc = timing_event(c, &e1);
+            if (rc) break;
+            c->book = dl::SlotBook();
+            c->book.n_slots = c->n_slots;
+            if (hipEventRecord(e0, c->s_copy) != hipSuccess) { rc = fail(c, DL_ERR_DEVICE, "event record failed"); break; }
+            rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
+            if (rc) break;
+            float ms = 0.0f;
+            if (hipEventRecord(e1, c->s_compute) != hipSuccess || hipStreamSynchronize(c->s_compute) != hipSuccess ||
+                hipStreamSynchronize(c->s_copy) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess) {
+                rc = fail(c, DL_ERR_DEVICE, "timing the sequential pass in one piece failed");
+                break;
+            }
+            whole[rep] = double(ms);
+        }
+        for (int32_t rep = 0; rep < kReps && rc == DL_OK; ++rep) {
+            hipEvent_t e0 = nullptr, e1 = nullptr;
+            rc = timing_event(c, &e0);
+            if (rc == DL_OK) rc = timing_event(c, &e1);
+            if (rc) break;
+            // every copy sits between a wait on a (long completed) event of the compute stream and a record, as the
+            // copies of a pass do: the packets these put into the copy queue are part of what a copy in a train costs
+            hipEvent_t released = nullptr, copied = nullptr;
+            rc = timing_event(c, &released);
+            if (rc == DL_OK) rc = timing_event(c, &copied);
+            if (rc) break;
+            bool ok = hipEventRecord(released, c->s_compute) == hipSuccess && hipStreamSynchronize(c->s_compute) == hipSuccess &&
+                      hipEventRecord(e0, c->s_copy) == hipSuccess;
+            for (int32_t i = 0; i < Ln && ok; ++i)
+                ok = hipStreamWaitEvent(c->s_copy, released, 0) == hipSuccess &&
+                     hipMemcpyAsync(c->base + c->slot_off[i % c->slots_held], M->store + size_t(i) * M->L.bytes, M->L.bytes,
+                                    hipMemcpyHostToDevice, c->s_copy) == hipSuccess &&
+                     hipEventRecord(copied, c->s_copy) == hipSuccess;
+            float ms = 0.0f;
+            ok = ok && hipEventRecord(e1, c->s_copy) == hipSuccess && hipStreamSynchronize(c->s_copy) == hipSuccess &&
+                 hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+            if (!ok) { rc = fail(c, DL_ERR_DEVICE, "timing the train of copies failed"); break; }
+            train[rep] = double(ms);
+        }
+        c->timing = true;
+        if (rc == DL_OK) {
+            std::sort(whole, whole + kReps);
+            std::sort(train, train + kReps);
+            double dma_sum = 0.0;
+            for (int32_t i = 0; i < Ln; ++i) dma_sum += dma[size_t(i)];
+            dma_sum /= double(iters - 1);
+            fence_excess = std::max(0.0, timed_span / double(iters - 1) - whole[kReps / 2]) / double(Ln);
+            if (dma_sum > 0.0 && train[kReps / 2] > 0.0) cont_scale = std::min(1.0, train[kReps / 2] / dma_sum);
         }
     }
     // all layers back to back, no copies: execution time under continuous load.  The last of kHotReps runs counts:
@@ -1446,9 +1514,10 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     if (rc) return rc;
     for (int32_t i = 0; i < Ln; ++i) {
         out[i].c_dma_ms = dma[size_t(i)] / (iters - 1);
+        out[i].c_dma_cont_ms = out[i].c_dma_ms * cont_scale;
         out[i].c_exe_ms = exe[size_t(i)] / (iters - 1);
         out[i].c_exe_hot_ms = hot[size_t(i)];
-        out[i].c_fence_ms = fence[size_t(i)] / (iters - 1);
+        out[i].c_fence_ms = std::max(0.0, fence[size_t(i)] / (iters - 1) - fence_excess);
         out[i].bytes = M->L.bytes;
     }
     return DL_OK;

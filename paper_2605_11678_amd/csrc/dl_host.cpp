@@ -482,8 +482,8 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
     return DL_OK;
 }
 
-int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double* c_exe_idle_ms,
-                    const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+int32_t dl_timeline(const double* c_dma_ms, const double* c_dma_cont_ms, const double* c_exe_ms,
+                    const double* c_exe_idle_ms, const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
                     int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms) {
     if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
@@ -505,6 +505,7 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
     double ev_dma[dl::kMaxSlots] = {0, 0, 0, 0}, ev_comp[dl::kMaxSlots] = {0, 0, 0, 0}, ev_pass = 0;
     double copy_start[dl::kMaxSlots] = {0, 0, 0, 0}, copy_dur[dl::kMaxSlots] = {0, 0, 0, 0};
     double exposed = 0, dma_sum = 0;
+    double last_copy_end = -1.0;                 // copy-queue clock when its latest copy ended (no copy yet: none)
     bool idled = false;                          // the compute queue waited for the copy of the next layer
     std::vector<dl_trace_op> ops;
     std::vector<uint8_t> resident;
@@ -543,9 +544,12 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_exe_ms, const double
                         if (pp < passes.size() && passes[pp].module == P.module && o.layer < passes[pp].j1 - passes[pp].j0)
                             jj = passes[pp].j0 + o.layer;
                     }
+                    // a copy that starts the instant the previous one ended runs at the rate of a train of copies
+                    const double dur = (c_dma_cont_ms && t[q] == last_copy_end) ? c_dma_cont_ms[jj] : c_dma_ms[jj];
                     copy_start[o.slot] = t[q];
-                    copy_dur[o.slot] = c_dma_ms[jj];
-                    t[q] += c_dma_ms[jj];
+                    copy_dur[o.slot] = dur;
+                    t[q] += dur;
+                    last_copy_end = t[q];
                     break;
                 }
                 case DL_OP_EXEC:

@@ -39,6 +39,8 @@ def test_profile_returns_table3_quantities():
             assert packed / 63e9 * 1e3 * 0.95 <= r["c_dma_ms"] <= packed / 2e9 * 1e3
             # execution under continuous load is not slower than right after an idle spell (beyond noise)
             assert r["c_exe_hot_ms"] <= r["c_exe_ms"] * 1.25
+            # a copy inside a train of copies is not slower than an isolated one, and still bounded by the link
+            assert packed / 63e9 * 1e3 * 0.95 <= r["c_dma_cont_ms"] <= r["c_dma_ms"]
         # layers of one module are identical in structure and timing (Sec. II-C)
         exe = np.array([r["c_exe_ms"] for r in prof])
         assert exe.max() <= 1.5 * exe.min()
@@ -199,7 +201,8 @@ def test_pipelined_mode_overlaps_copies_with_execution():
         # and the timeline predictor, fed with this profile, agrees with both measurements
         rows = [(r["c_dma_ms"], r["c_exe_hot_ms"]) for r in prof]
         args = ([r[0] for r in rows], [r[1] for r in rows], [True] * L, [i == 0 for i in range(L)])
-        kw = dict(c_exe_idle_ms=[r["c_exe_ms"] for r in prof], c_fence_ms=[r["c_fence_ms"] for r in prof])
+        kw = dict(c_exe_idle_ms=[r["c_exe_ms"] for r in prof], c_fence_ms=[r["c_fence_ms"] for r in prof],
+                  c_dma_cont_ms=[r["c_dma_cont_ms"] for r in prof])
         pred_pipe = B.timeline(*args, **kw)["total"]
         pred_seq = B.timeline(*args, mode=B.DL_MODE_SEQUENTIAL, **kw)["total"]
         assert abs(pred_pipe - pipe) <= 0.15 * pipe and abs(pred_seq - seq) <= 0.15 * seq, (pred_pipe, pipe, pred_seq, seq)

@@ -150,6 +150,49 @@ def test_timeline_with_measured_corrections_matches_oracle(wrap):
         assert seq["total"] == pytest.approx(P.sequential_time(inv, overhead=ov), rel=1e-12)
 
 
+def test_timeline_copy_trains_take_the_continuous_copy_time():
+    """c_dma_cont_ms applies to a copy exactly when the copy queue did not wait since the previous copy ended:
+    closed forms for the two regimes of Sec. IV-C, and NULL / equal arrays change nothing"""
+    L = 9
+    st, ps = [True] * L, [i == 0 for i in range(L)]
+    # copy-bound (C_DMA > C_EXE, two slots): every copy after the first follows its predecessor at once
+    d, dc, e = 4.0, 3.5, 1.0
+    got = B.timeline([d] * L, [e] * L, st, ps, c_dma_cont_ms=[dc] * L)
+    assert got["total"] == pytest.approx(d + (L - 1) * dc + e)
+    # execution-bound: the first two copies form a train, every later one waits for its slot to be released
+    d, dc, e = 1.0, 0.6, 5.0
+    got = B.timeline([d] * L, [e] * L, st, ps, c_dma_cont_ms=[dc] * L)
+    assert got["total"] == pytest.approx(d + L * e)
+    assert got["exposed"] == pytest.approx(d)
+    # one slot: a copy always waits for the execution before it, so no copy is part of a train
+    got = B.timeline([4.0] * L, [1.0] * L, st, ps, c_dma_cont_ms=[3.5] * L, n_slots=1)
+    assert got["total"] == pytest.approx(L * 5.0)
+    # sequential mode never forms trains either
+    got = B.timeline([4.0] * L, [1.0] * L, st, ps, c_dma_cont_ms=[3.5] * L, mode=B.DL_MODE_SEQUENTIAL)
+    assert got["total"] == pytest.approx(L * 5.0)
+    # per-invocation values: the train time used is the one of the copy that runs, not of its predecessor
+    dma = [4.0, 5.0, 6.0]
+    cont = [0.1, 4.5, 5.5]
+    got = B.timeline(dma, [1.0] * 3, [True] * 3, [True, False, False], c_dma_cont_ms=cont)
+    assert got["total"] == pytest.approx(4.0 + 4.5 + 5.5 + 1.0)
+    # a resident layer between streamed ones does not break a train on the copy queue
+    got = B.timeline([4.0] * 4, [1.0] * 4, [True, False, True, True], [True, False, False, False], c_dma_cont_ms=[3.0] * 4)
+    assert got["total"] == pytest.approx(4.0 + 3.0 + 3.0 + 1.0)
+    rnd = random.Random(5)
+    for trial in range(100):
+        n = rnd.randint(1, 8)
+        dma = [rnd.uniform(0.1, 5) for _ in range(n)]
+        exe = [rnd.uniform(0.1, 5) for _ in range(n)]
+        mask = [rnd.random() < 0.7 for _ in range(n)]
+        ps = [i == 0 for i in range(n)]
+        base = B.timeline(dma, exe, mask, ps, wrap_prefetch=trial % 2)
+        same = B.timeline(dma, exe, mask, ps, wrap_prefetch=trial % 2, c_dma_cont_ms=list(dma))
+        assert base == same
+        faster = B.timeline(dma, exe, mask, ps, wrap_prefetch=trial % 2, c_dma_cont_ms=[0.8 * v for v in dma])
+        assert faster["total"] <= base["total"] + 1e-12
+        assert faster["total"] >= B.timeline([0.8 * v for v in dma], exe, mask, ps, wrap_prefetch=trial % 2)["total"] - 1e-12
+
+
 def test_timeline_closed_forms_eq5_eq6_eq7():
     L, R = 36, 21
     uni = lambda d, e: [(d, e, True)] * L
