@@ -309,7 +309,8 @@ typedef struct {
 
 /* Sec. II-C / Table III: runs the module in sequential mode `iters` times at (n_tokens, pos0),
  * discards the first iteration, writes per-layer means.  Every layer is copied (into a slot)
- * and timed regardless of residency.  Then all layers are run back to back without copies (on
+ * and timed regardless of residency.  Three more sequential passes without per-layer events and three
+ * trains of all the layers' copies are each timed in one piece (c_fence_ms, c_dma_cont_ms).  Then all layers are run back to back without copies (on
  * whatever parameters the slot holds: same shapes, same cost) to time them under continuous load.  out: host array
  * [n_layers].  A last sequential pass with every layer's own parameters leaves the KV-cache rows pos0 .. pos0+n_tokens-1
  * as a real pass over x_dev writes them.  The call's temporaries (an activation block, weight copies for the continuous

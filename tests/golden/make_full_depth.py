@@ -2,7 +2,7 @@
 ratios of the full-shape cases (tests/test_parity_discriminates.py).  Calls ONLY the oracle and the seeded input
 generators; nothing here loads the HIP library.
 
-    python tests/golden/make_full_depth.py [part ...]      parts: dec8b_L1 dec8b_L1_attn act_L8 act_L8_cross vit_L27 dec8b_L36 dec8b_L36_mutants (default: all)
+    python tests/golden/make_full_depth.py [part ...]      parts: dec8b_L1 dec8b_L1_attn act_L8 act_L8_cross vit_L27 dec8b_L36 dec8b_L36_mutants vla_full (default: all)
 
 The 36-layer decoder at 3072 tokens costs the float64 oracle ~10 minutes on 8 cores, each mutant as much again, and a
 single-token step needs all 13.9 GB of weights once more: too slow to repeat inside the GPU test run, so the values
@@ -173,13 +173,36 @@ def part_dec8b_L36(arrays, meta):
     raise SystemExit("no head seed gave a margin above %.2f at every step" % MIN_MARGIN)
 
 
+def part_vla_full(arrays, meta):
+    """The five-stage pipeline at its full shape (27-layer encoder on 4096 patches, merger, 36-layer decoder over
+    1024 visual + 2048 text positions, 8-layer action head, 10 Euler steps, 64 x 3 trajectory), stated N(0, 0.02)
+    recipe, no decode steps: the generated tokens feed neither the action head nor the trajectory (Sec. II-A), and
+    the full-size single-token steps are what part dec8b_L36 stores."""
+    from oracle import pipeline as PL
+    vit, dec, act = CFG.vit_encoder(), CFG.decoder_8b(), CFG.action_head()
+    n_patches, n_text, n_actions = 4096, 2048, 64
+    inp = CFG.make_pipeline_inputs(vit, dec, act, n_patches, n_text, n_actions)
+    gen = (lambda c: (lambda l: CFG.make_layer_weights(c, l, 0.0)))
+    out = PL.vla_pipeline(vit.as_dict(), gen(vit), inp["proj_w"], dec.as_dict(), gen(dec), CFG.make_head(dec),
+                          act.as_dict(), gen(act), (inp["out_w"][2], inp["out_w"][3]),
+                          inp["patches"], inp["text"], inp["a0"], 0)
+    store_output(arrays, meta, "vla_full_hidden_ctx", out["hidden_ctx"], np.zeros_like(out["hidden_ctx"]), 61)
+    arrays["vla_full_actions"] = out["actions"].astype(np.float32)
+    arrays["vla_full_trajectory"] = out["trajectory"].astype(np.float64)
+    a0 = np.asarray(inp["a0"], np.float64)
+    meta["vla_full"] = dict(n_patches=n_patches, n_text=n_text, n_actions=n_actions, n_decode=0, n_euler=10,
+                            actions_max_abs=float(np.max(np.abs(out["actions"]))),
+                            actions_max_abs_contrib=float(np.max(np.abs(out["actions"] - a0))),
+                            trajectory_max_abs=float(np.max(np.abs(out["trajectory"]))))
+
+
 def main():
-    parts = sys.argv[1:] or ["dec8b_L1", "dec8b_L1_attn", "act_L8", "act_L8_cross", "vit_L27", "dec8b_L36", "dec8b_L36_mutants"]
+    parts = sys.argv[1:] or ["dec8b_L1", "dec8b_L1_attn", "act_L8", "act_L8_cross", "vit_L27", "dec8b_L36", "dec8b_L36_mutants", "vla_full"]
     arrays, meta = load()
     for p in parts:
         t = time.time()
         {"dec8b_L1": part_dec8b_L1, "dec8b_L1_attn": part_dec8b_L1_attn, "act_L8": part_act_L8, "act_L8_cross": part_act_L8_cross, "vit_L27": part_vit_L27, "dec8b_L36": part_dec8b_L36,
-         "dec8b_L36_mutants": part_dec8b_L36_mutants}[p](arrays, meta)
+         "dec8b_L36_mutants": part_dec8b_L36_mutants, "vla_full": part_vla_full}[p](arrays, meta)
         meta.setdefault("seconds", {})[p] = round(time.time() - t)
         save(arrays, meta)
         log("part", p, "done")

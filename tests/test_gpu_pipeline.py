@@ -51,3 +51,51 @@ def test_vla_pipeline_small_vs_oracle_and_residency_invariance():
             assert out["tokens"] == ref_tok
     finally:
         eng.close()
+
+
+def test_vla_pipeline_full_shape_vs_stored_oracle():
+    """The five-stage pipeline at the shape bench.py times (27-layer encoder on 4096 patches, merger, 36-layer decoder
+    over 1024 + 2048 positions, 8-layer action head cross-attending to the 3072 final-normed states, 10 Euler steps,
+    64 x 3 trajectory) under the 16e9-byte arena, everything streamed, against oracle values stored by
+    tests/golden/make_full_depth.py (part vla_full; the float64 oracle needs a quarter of an hour for it).  No decode
+    steps: the generated tokens feed neither the action head nor the trajectory, and full-size single-token steps
+    are compared in tests/test_gpu_fullsize.py.  Every measure is held to the stated 2e-2 (observed: final-normed
+    decoder states 1.2e-2, action tokens 1.4e-3, trajectory 2.3e-3).  Which sub-block each measure can see is shown
+    on the reduced pipeline and on the full-shape action head (tests/test_parity_discriminates.py); the oracle is
+    too slow at this size to be run once more per removed sub-block.  A partially resident plan reproduces the
+    bits (Table IX)."""
+    import json
+    import os
+    gold = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    with open(os.path.join(gold, "full_depth_meta.json")) as f:
+        meta = json.load(f)
+    arrays = np.load(os.path.join(gold, "full_depth.npz"))
+    m = meta["vla_full"]
+    vit, dec, act = CFG.vit_encoder(), CFG.decoder_8b(), CFG.action_head()
+    eng = Engine(16_000_000_000, device=0)
+    try:
+        pipe = VlaPipeline(eng, vit, dec, act, n_patches=m["n_patches"], n_text=m["n_text"], n_actions=m["n_actions"])
+        pipe.run(0, m["n_euler"])
+        got = pipe.results(0)
+        rows = arrays["vla_full_hidden_ctx_rows"]
+        e_ctx = float(np.max(np.abs(got["hidden_ctx"][rows].astype(np.float64) - arrays["vla_full_hidden_ctx_want"])))
+        e_act = float(np.max(np.abs(got["actions"].astype(np.float64) - arrays["vla_full_actions"])))
+        e_traj = float(np.max(np.abs(got["trajectory"].astype(np.float64) - arrays["vla_full_trajectory"])))
+        measures = {
+            "hidden_ctx": e_ctx / meta["vla_full_hidden_ctx"]["max_abs"] / TOL,
+            "actions": e_act / m["actions_max_abs"] / TOL,
+            "actions_contrib": e_act / m["actions_max_abs_contrib"] / PC.TOL_CONTRIB,
+            "trajectory": e_traj / m["trajectory_max_abs"] / TOL,
+        }
+        print("full-shape pipeline, measures / bound:", {k: "%.3f" % v for k, v in measures.items()}, flush=True)
+        assert max(measures.values()) <= 1.0, measures
+        ref = got["trajectory"].view(np.uint32).copy()
+        ref_act = got["actions"].view(np.uint32).copy()
+        eng.ctx.set_residency(pipe.m_act, list(range(act.n_layers)))
+        eng.ctx.set_residency(pipe.m_dec, B.place_interleaved(dec.n_layers, 18))
+        pipe.run(0, m["n_euler"])
+        out = pipe.results(0)
+        assert np.array_equal(out["trajectory"].view(np.uint32), ref)
+        assert np.array_equal(out["actions"].view(np.uint32), ref_act)
+    finally:
+        eng.close()
