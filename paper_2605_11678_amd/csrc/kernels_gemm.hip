@@ -1,23 +1,24 @@
 // BF16 GEMM on gfx950 matrix cores: C[M,N] = A[M,K] * B[N,K]^T with fused epilogues.
 //
 // Both operands are K-contiguous, which is the layout v_mfma_f32_32x32x16_bf16 wants for A and
-// for B alike (a lane supplies 8 consecutive k of one row / one column), so tiles go
-// global -> registers -> LDS -> MFMA without any transposition.  Weights are stored [N,K]
-// by the packer for exactly this reason.
+// for B alike (a lane supplies 8 consecutive k of one row / one column), so no tile is ever
+// transposed on its way to the matrix core.  Weights are stored [N,K] by the packer for exactly this reason.
 //
-// Two kernels share the epilogues:
+// Three kernels share the epilogues:
 //
-//  * gemm_fast<BM,BN,EPI> — the production path for K % 128 == 0.  One workgroup per CU (256 threads =
-//    4 wavefronts in a 2x2 grid, each owning a (BM/2)x(BN/2) tile, i.e. up to 4x4 MFMA tiles = 256 fp32
-//    accumulators per lane).  k-tile 64: a row of a tile is one 128-byte cache line.  Tiles go global -> LDS
-//    directly (global_load_lds_dwordx4, no staging registers) into two LDS stages that are separate arrays, so
-//    the compiler can tell the stage being filled from the one being read; the wait for a copy is an explicit
-//    s_waitcnt.  LDS rows are 128 bytes, unpadded (a wavefront's copy fills 1 KB = 8 rows contiguously); the
-//    16-byte chunk index is XOR-swizzled with (row/2)%8 on both sides, which keeps the b128 fragment reads
-//    conflict-free.  Per k-tile four phases of up to 16 MFMAs, each interleaved with the fragment reads of the
-//    next phase through sched_group_barrier, ONE bare s_barrier, and the copy of the k-tile after the next
-//    spread over the two phases that follow the barrier (a whole k-tile of time to land).
-//  * gemm_generic<EPI> — any shape (K % 8 == 0): 128x128 tile, 64x64 per wavefront, register-staged.
+//  * gemm_fast<BM,BN,EPI,WM,BNR,NS> — the production path for K % 128 == 0.  256 threads = 4 wavefronts, 2x2 (WM = 2:
+//    each owns a (BM/2)x(BN/2) tile, up to 4x4 MFMA tiles = 256 fp32 accumulators per lane) or stacked 4x1 (WM = 4);
+//    one workgroup per CU for the 192- and 256-row tiles, two for 128x192 and 128x128.  BNR <= BN columns are stored
+//    (128x144 of a 128x160 tile puts exactly one workgroup on every CU for N = 1152).  k-tile 64: a row of a tile is
+//    one 128-byte cache line.  Tiles go global -> LDS directly (global_load_lds_dwordx4, no staging registers) into
+//    NS = 2 (4 for the small tile with long reductions) LDS stages that are separate arrays, so the compiler can tell
+//    the stage being filled from the one being read; the wait for a copy is an explicit s_waitcnt.  LDS rows are
+//    128 bytes, unpadded (a wavefront's copy fills 1 KB = 8 rows contiguously); the 16-byte chunk index is
+//    XOR-swizzled with (row/2)%8 on both sides, which keeps the b128 fragment reads conflict-free.  Per k-tile four
+//    phases of up to 16 MFMAs, each interleaved with the fragment reads of the next phase through
+//    sched_group_barrier, ONE bare s_barrier, and the copy of the k-tile NS ahead spread over the two phases that
+//    follow the barrier (a whole k-tile of time to land).
+//  * gemm_generic<EPI> — any shape (K % 8 == 0): 128x128 tile, 64x64 per wavefront, staged through registers.
 //  * gemm_few_rows<EPI> — M <= 64: 64x32 output per workgroup, reduction split over its 8 wavefronts.
 //
 // Accumulator layout of a 32x32 tile: lane l, register r -> column l%32, row 8*(r/4) + 4*(l/32) + r%4.
