@@ -379,6 +379,92 @@ def vit_leg(B, CFG, Engine, torch, log):
     eng.close()
     return out
 
+def long_prefill_leg(B, CFG, Engine, torch, log, cap, T=16384):
+    """The execution-intensive regime of Sec. IV-C (Eq. 5, Table IV) on this part: the same 36-layer 8B-class decoder
+    over a 16384-token prompt, where a layer executes for longer than its copy takes (at 3072 tokens the copy takes
+    5.7x the execution, so most of it CANNOT be hidden).  Everything streamed, pipelined against sequential, and the
+    largest residency the arena holds; hidden fraction from the per-layer event records; predictor from one
+    profiling run; streamed and partially resident outputs compared bit for bit on the device."""
+    import numpy as np
+    c = CFG.decoder_8b(max_seq=T, vocab=0)
+    L = c.n_layers
+    eng = Engine(int(cap), device=0)
+    try:
+        mid = eng.add_module(c, max_tokens=T)
+        ctx = eng.ctx
+        packed, _ = ctx.module_layer_bytes(mid)
+        xp, xv = eng.alloc_f32(T * c.d_model)
+        yp, yv = eng.alloc_f32(T * c.d_model)
+        eng.upload(xv, CFG.make_tokens(T, c.d_model, seed=7))
+        tried = eng.pick_copy_stream(mid, T, xp, yp, passes=1)
+        log("long prefill copy-stream candidates (ms per fully streamed pass): " + ", ".join("%.1f" % t for _, t in tried))
+        prof = ctx.profile(mid, L, T, 0, xp, iters=2)
+        col = lambda key: [p_[key] for p_ in prof]
+        c_dma, c_cont, c_exe, c_hot, c_fence = (col(k_) for k_ in ("c_dma_ms", "c_dma_cont_ms", "c_exe_ms", "c_exe_hot_ms", "c_fence_ms"))
+        flops_layer = 2.0 * T * c.d_model * (c.n_q_heads * c.d_head + 2 * c.n_kv_heads * c.d_head) \
+            + 2.0 * T * c.d_model * c.n_q_heads * c.d_head + 6.0 * T * c.d_model * c.d_ff \
+            + 4.0 * c.d_head * c.n_q_heads * (T * (T + 1) / 2.0)
+        roof_layer_ms = max(packed / (LINK_GBPS_THEORY * 1e6), flops_layer / (PEAK_BF16_TFLOPS * 1e9))
+
+        def measure(k, mode):
+            ctx.set_mode(mode, 0)
+            ctx.set_residency(mid, B.place_interleaved(L, k))
+            ctx.forward(mid, xp, yp, T, 0)
+            ctx.sync()
+            samples = []
+            for _ in range(3):
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                ctx.forward(mid, xp, yp, T, 0)
+                ctx.sync()
+                samples.append((time.perf_counter() - t) * 1e3)
+            ctx.set_timing(True)
+            ctx.forward(mid, xp, yp, T, 0)
+            st = ctx.collect_stats()
+            ctx.set_timing(False)
+            rs = set(B.place_interleaved(L, k))
+            pred = B.timeline(c_dma, c_hot, [i not in rs for i in range(L)], [i == 0 for i in range(L)], mode=mode,
+                              c_exe_idle_ms=c_exe, c_fence_ms=c_fence, c_dma_cont_ms=c_cont)["total"]
+            ms = float(np.median(samples))
+            return {"k": k, "mode": "sequential" if mode == B.DL_MODE_SEQUENTIAL else "pipelined",
+                    "measured_ms": round(ms, 2), "predicted_ms": round(pred, 2), "pred_err_pct": round((pred - ms) / ms * 100, 2),
+                    "hidden_frac": round(st["hidden_frac"], 4), "h2d_gbps": round(st["h2d_gbps"], 2),
+                    "roofline_frac": round(roof_layer_ms * L / ms, 4), "arena_gb": round(ctx.arena_stats()["used"] / 1e9, 3)}
+
+        rows = [measure(0, B.DL_MODE_SEQUENTIAL), measure(0, B.DL_MODE_PIPELINED)]
+        ctx.sync()
+        torch.cuda.synchronize()
+        ref = yv.clone()
+        k_fit = 0
+        for k in range(L, 0, -1):
+            try:
+                ctx.set_residency(mid, B.place_interleaved(L, k))
+                k_fit = k
+                break
+            except B.DLError as e:
+                if e.code != B.DL_ERR_BUDGET_EXCEEDED:
+                    raise
+        identical = None
+        if k_fit:
+            rows.append(measure(k_fit, B.DL_MODE_PIPELINED))
+            ctx.sync()
+            torch.cuda.synchronize()
+            identical = bool(torch.equal(yv.view(torch.int32), ref.view(torch.int32)))
+        del ref
+        for r in rows:
+            log("long prefill T=%d k=%2d %-10s %.1f ms (predicted %.1f, %+.2f%%) hidden %.3f H2D %.1f GB/s roofline frac %.3f" %
+                (T, r["k"], r["mode"], r["measured_ms"], r["predicted_ms"], r["pred_err_pct"], r["hidden_frac"], r["h2d_gbps"],
+                 r["roofline_frac"]))
+        return {"workload": "8B-class decoder prefill, 36 layers, T=%d, cap %.3g B" % (T, cap), "layer_bytes": packed,
+                "layer_flop": flops_layer,
+                "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_dma_cont_ms": round(float(np.mean(c_cont)), 4),
+                            "c_exe_ms": round(float(np.mean(c_exe)), 4), "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
+                            "c_fence_ms": round(float(np.mean(c_fence)), 4), "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 3)},
+                "runs": rows, "streamed_vs_partially_resident_bit_identical": identical}
+    finally:
+        eng.close()
+
+
 def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     """configs[4]: vision encoder -> merger -> 8B decoder prefill + 64 decode steps -> action head (10 Euler
     steps, 64 tokens cross-attending to the decoder's hidden states), all under one arena; one slot pair shared
@@ -533,8 +619,8 @@ def main():
     ap.add_argument("--sweep", type=str, default="0,9,18,27,33,35,36")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the decode, ViT and pipeline legs")
-    ap.add_argument("--extras", default="decode,vit,vla", help="which of the extra legs to run (comma list)")
-    ap.add_argument("--only", default="", help="profiling aid: run just one of the extra legs (vit | vla) and print its "
+    ap.add_argument("--extras", default="decode,vit,vla,long", help="which of the extra legs to run (comma list)")
+    ap.add_argument("--only", default="", help="profiling aid: run just one of the extra legs (vit | vla | long) and print its "
                                                 "record instead of the contract line")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: one 1 GiB device copy (calibrates FETCH_SIZE / WRITE_SIZE), then "
@@ -556,7 +642,8 @@ def main():
 
     if args.only:
         leg = {"vit": lambda: vit_leg(B, CFG, Engine, torch, log),
-               "vla": lambda: vla_leg(B, CFG, Engine, torch, log, int(args.cap))}[args.only]
+               "vla": lambda: vla_leg(B, CFG, Engine, torch, log, int(args.cap)),
+               "long": lambda: long_prefill_leg(B, CFG, Engine, torch, log, int(args.cap))}[args.only]
         print(json.dumps({"only": args.only, "record": leg()}), flush=True)
         return
 
@@ -887,6 +974,11 @@ def main():
             out["extras"]["vla"] = vla_leg(B, CFG, Engine, torch, log, cap)
         except B.DLError as e:
             out["extras"]["vla"] = {"error": str(e)}
+    if "long" in legs:
+        try:
+            out["extras"]["long_prefill"] = long_prefill_leg(B, CFG, Engine, torch, log, cap)
+        except B.DLError as e:
+            out["extras"]["long_prefill"] = {"error": str(e)}
     # the residency sweep of the headline workload once more, last on stderr (what a truncated log keeps)
     log("---- summary: 8B decoder prefill T=%d under %.3g B ----" % (T, cap))
     for r in sweep:

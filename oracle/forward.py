@@ -157,6 +157,21 @@ def layer_forward(cfg, W, x, pos0=0, kv=None, ctx=None):
     return h + mid @ W[T_W_DOWN].T + _w(W, T_B_DOWN)
 
 
+def project_kv(cfg, W, x, pos0=0):
+    """The keys and values layer_forward derives from rows x at positions pos0.. (the same definition, on its
+    own): k, v = Norm1(x) Wk^T (+ bk), Norm1(x) Wv^T (+ bv), keys rotated when the module uses RoPE.  Lets a test
+    fill a KV cache for a long prefix without paying for that prefix's attention and feed-forward, and then ask
+    layer_forward for a few chunks of rows only.  Pinned against the cache rows layer_forward itself writes."""
+    T = x.shape[0]
+    Hkv, dh = cfg["n_kv_heads"], cfg["d_head"]
+    n1 = norm(cfg, x, W[T_NORM1_G], _w(W, T_NORM1_B))
+    k = (n1 @ W[T_WK].T + _w(W, T_BK)).reshape(T, Hkv, dh)
+    v = (n1 @ W[T_WV].T + _w(W, T_BV)).reshape(T, Hkv, dh)
+    if cfg["rope_theta"] > 0:
+        k = rope(k, pos0 + np.arange(T), cfg["rope_theta"])
+    return k, v
+
+
 def new_kv_cache(cfg, n_layers=None):
     n = cfg["n_layers"] if n_layers is None else n_layers
     shape = (cfg["max_seq"], cfg["n_kv_heads"], cfg["d_head"])

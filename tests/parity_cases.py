@@ -245,6 +245,37 @@ def pipeline_measures(got, want):
     }
 
 
+# ---- a 16384-token prompt through one 8B-class layer: the oracle computes three chunks of rows on their own -------
+LONG_T = 16384
+LONG_CHUNKS = [(0, 64), (8192 - 39, 77), (LONG_T - 128, 128)]      # first rows, a ragged chunk across the middle, last rows
+
+
+def long_prompt_case(attention_alone):
+    """attention_alone: the feed-forward's output projection zeroed, so that y - x is the attention sub-block only (next
+    to the feed-forward, an average over thousands of keys is a tenth of the contribution)."""
+    return Case("dec8b_L1_T%d%s" % (LONG_T, "_attn" if attention_alone else ""),
+                CFG.decoder_8b(n_layers=1, max_seq=LONG_T, vocab=0), [(0, LONG_T)], 7, gain=0.0,
+                zero=(CFG.T_W_DOWN,) if attention_alone else ())
+
+
+def long_prompt_oracle(case, weights=None, cfg_over=None, x=None):
+    """(rows, oracle output at those rows).  The whole pass would cost the oracle minutes (its attention alone one):
+    the keys and values of all positions come from oracle.forward.project_kv, and layer_forward then computes
+    LONG_CHUNKS at their positions over that cache, which tests/test_oracle_forward.py shows to equal those rows of the
+    full pass."""
+    cfg = case.cfg.as_dict()
+    if cfg_over:
+        cfg.update(cfg_over)
+    gen = weights or case.weights()
+    W = {t: (F.widen(a) if a.dtype == np.uint16 else np.asarray(a, np.float64)) for t, a in gen(0).items()}
+    x64 = (case.x() if x is None else x).astype(np.float64)
+    kv = F.new_kv_cache(cfg, 1)[0]
+    kv["k"][:LONG_T], kv["v"][:LONG_T] = F.project_kv(cfg, W, x64, 0)
+    want = np.concatenate([F.layer_forward(cfg, W, x64[p:p + t], p, kv) for p, t in LONG_CHUNKS])
+    rows = np.concatenate([np.arange(p, p + t) for p, t in LONG_CHUNKS])
+    return rows, want
+
+
 # ---- full-shape cases: expected values and mutation ratios come from tests/golden/make_full_depth.py ---------
 def full_cases():
     return {

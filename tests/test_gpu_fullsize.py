@@ -7,7 +7,10 @@
     script that calls only the oracle: the float64 oracle needs ~10 minutes per 36-layer pass), at sampled rows (every
     61st / 83rd and the last, all columns), the maxima the error measures divide by taken over the whole output;
 (c) properties that hold at any size: streamed, partially resident and fully resident passes agree bit for bit
-    (Table IX), and so do repeated passes."""
+    (Table IX), and so do repeated passes;
+(d) a 16384-token prompt (the length at which a layer of this part executes longer than its copy takes, the regime
+    of Sec. IV-C / Table IV that bench.py's long-prefill leg measures) through one 8B-class layer, against the oracle
+    on three chunks of rows that it computes on their own."""
 import json
 import os
 
@@ -68,6 +71,27 @@ def test_full_shape_case_vs_oracle_live(name):
         g.eng.ctx.set_residency(g.mid, [0])
         p0, t0 = case.passes[0]
         assert np.array_equal(g.forward_bits(x[:t0], ctx=ctx), bits)
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("attention_alone", [False, True])
+def test_long_prompt_one_layer_sampled_chunks_vs_oracle(attention_alone):
+    """16384 tokens through one 8B-class layer (64 x 96 GEMM tiles of 256 x 256 in the gate/up product, 512 query
+    blocks per head, causal jobs of up to 256 K/V tiles), against the oracle on three chunks of rows (the first rows,
+    a ragged chunk across the middle, the last rows: tests/parity_cases.py says how the oracle gets them without
+    running the whole pass).  Both measures divide by maxima over the sampled rows only (smaller than over the whole
+    output: stricter).  tests/test_parity_discriminates.py shows which sub-block each variant can see."""
+    case = PC.long_prompt_case(attention_alone)
+    x = case.x()
+    g = GpuStack(case.cfg, max_tokens=PC.LONG_T, cap_bytes=6 << 30, weights=case.weights())
+    try:
+        got = g.forward(x)
+        rows, want = PC.long_prompt_oracle(case, x=x)
+        PC.check(got[rows], want, x[rows], "%s, %d sampled rows" % (case.name, len(rows)))
+        bits = got.view(np.uint32).copy()
+        g.eng.ctx.set_residency(g.mid, [0])
+        assert np.array_equal(g.forward_bits(x), bits)
     finally:
         g.close()
 

@@ -261,6 +261,31 @@ def test_decode_over_cache_vs_brute_force_and_prefill_consistency():
     assert a == pytest.approx(b, rel=1e-14)
 
 
+def test_project_kv_is_what_layer_forward_caches_and_chunks_reproduce_the_full_pass():
+    """project_kv against the cache rows layer_forward writes (RMSNorm + RoPE decoder, LayerNorm + bias module), and
+    the use the long-prompt GPU test makes of it: a cache filled by project_kv for the whole prompt, then
+    layer_forward on a chunk of rows at its position, reproduces those rows of the full causal pass."""
+    rng = np.random.default_rng(41)
+    for c in (cfg_decoder(), cfg_decoder(norm=F.NORM_LN, has_bias=1, n_kv_heads=4, act=F.ACT_GELU)):
+        W = rand_weights(c, rng)
+        T = 11
+        x = rng.standard_normal((T, c["d_model"]))
+        kv = F.new_kv_cache(c, 1)[0]
+        full = F.layer_forward(c, W, x, 0, kv)
+        k, v = F.project_kv(c, W, x, 0)
+        assert np.array_equal(k, kv["k"][:T]) and np.array_equal(v, kv["v"][:T])
+        # positions matter for the keys of a module with rotary embedding
+        k3, v3 = F.project_kv(c, W, x[3:7], 3)
+        assert np.array_equal(k3, kv["k"][3:7]) and np.array_equal(v3, kv["v"][3:7])
+        if c["rope_theta"] > 0:
+            assert not np.allclose(F.project_kv(c, W, x[3:7], 0)[0], k3)
+        kv2 = F.new_kv_cache(c, 1)[0]
+        kv2["k"][:T], kv2["v"][:T] = k, v
+        for p0, t in ((0, 2), (4, 3), (9, 2)):
+            got = F.layer_forward(c, W, x[p0:p0 + t], p0, kv2)
+            assert got == pytest.approx(full[p0:p0 + t], rel=1e-12, abs=1e-14)
+
+
 def test_structure_invariants():
     rng = np.random.default_rng(5)
     c = cfg_decoder()

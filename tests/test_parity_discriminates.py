@@ -71,3 +71,20 @@ def test_full_shape_cases_detect_mutations():
             seen = set(want[name].get(m, []))
             if len(seen) < n_pass:
                 assert (name, m) in companions and m in want[companions[(name, m)]], (name, m)
+
+
+def test_long_prompt_chunks_detect_mutations():
+    """The 16384-token case of tests/test_gpu_fullsize.py, mutated live on its three chunks of rows: the plain variant
+    must see the feed-forward go, the attention-alone variant the attention, the rotary embedding and the causal mask."""
+    for attention_alone, mutations in ((False, ["ffn"]), (True, ["self_attention", "rope", "causal_mask"])):
+        case = PC.long_prompt_case(attention_alone)
+        x = case.x()
+        rows, base = PC.long_prompt_oracle(case, x=x)
+        for m in mutations:
+            applies, make = PC.MUTATIONS[m]
+            assert applies(case)
+            w, over = make(case)
+            _, mut = PC.long_prompt_oracle(case, w, over, x=x)
+            r = max(PC.stated_err(mut, base) / PC.TOL, PC.contrib_err(mut, base, x[rows]) / PC.TOL_CONTRIB)
+            print("long prompt%s: %s removed -> %.1f x the bound" % (" (attention alone)" if attention_alone else "", m, r))
+            assert r >= PC.DISCRIMINATION, (case.name, m, r)
