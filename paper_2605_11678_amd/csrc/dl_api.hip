@@ -1468,13 +1468,17 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         }
     }
     // The event pairs between the layers drain the queue (a few microseconds per layer, which is percents for short
-    // layers): one more run with events only around the whole stack gives the true total, and the per-layer figures
-    // are scaled to it.
+    // layers): runs with events only around the whole stack give the true total, and the per-layer figures are scaled
+    // to it.  Three such runs, the median counts: the part's clock under load wanders by a percent or two from one
+    // pass to the next, and a single slow pass would put that into every prediction made from this profile.
     if (rc == DL_OK) {
-        hipEvent_t e0 = nullptr, e1 = nullptr;
-        rc = timing_event(c, &e0);
-        if (rc == DL_OK) rc = timing_event(c, &e1);
-        if (rc == DL_OK) {
+        constexpr int32_t kWhole = 3;
+        double totals[kWhole] = {0, 0, 0};
+        for (int32_t rep = 0; rep < kWhole && rc == DL_OK; ++rep) {
+            hipEvent_t e0 = nullptr, e1 = nullptr;
+            rc = timing_event(c, &e0);
+            if (rc == DL_OK) rc = timing_event(c, &e1);
+            if (rc) break;
             (void)hipEventRecord(e0, c->s_compute);
             for (int32_t i = 0; i < Ln; ++i)
                 run_layer(c, *M, i, c->base + rot[size_t(i) % rot.size()], i == 0 ? static_cast<const float*>(x) : scratch,
@@ -1483,10 +1487,15 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
             float total = 0.0f;
             if (hipStreamSynchronize(c->s_compute) != hipSuccess || hipEventElapsedTime(&total, e0, e1) != hipSuccess)
                 rc = fail(c, DL_ERR_DEVICE, "timing the uninterrupted run failed");
+            totals[rep] = double(total);
+        }
+        if (rc == DL_OK) {
+            std::sort(totals, totals + kWhole);
+            const double total = totals[kWhole / 2];
             double sum = 0.0;
             for (int32_t i = 0; i < Ln; ++i) sum += hot[size_t(i)];
-            if (rc == DL_OK && sum > 0.0 && total > 0.0f)
-                for (int32_t i = 0; i < Ln; ++i) hot[size_t(i)] *= double(total) / sum;
+            if (sum > 0.0 && total > 0.0)
+                for (int32_t i = 0; i < Ln; ++i) hot[size_t(i)] *= total / sum;
         }
     }
     // The continuous runs executed every layer on rotated parameters and appended THOSE keys and values at pos0..:
