@@ -379,14 +379,22 @@ def vit_leg(B, CFG, Engine, torch, log):
     eng.close()
     return out
 
-def long_prefill_leg(B, CFG, Engine, torch, log, cap, T=16384):
-    """The execution-intensive regime of Sec. IV-C (Eq. 5, Table IV) on this part: the same 36-layer 8B-class decoder
-    over a 16384-token prompt, where a layer executes for longer than its copy takes (at 3072 tokens the copy takes
-    5.7x the execution, so most of it CANNOT be hidden).  Everything streamed, pipelined against sequential, and the
-    largest residency the arena holds; hidden fraction from the per-layer event records; predictor from one
-    profiling run; streamed and partially resident outputs compared bit for bit on the device."""
+def long_prefill_leg(B, CFG, Engine, torch, log, cap, which="decoder"):
+    """The execution-intensive regime of Sec. IV-C (Eq. 5, Table IV) on this part: the 36-layer 8B-class decoder over
+    a 16384-token prompt, or the 27-layer encoder over 8192 patches, where a layer executes for longer than its copy
+    takes (at the paper's 3072 / 4096 tokens the copy takes 5.7x / 1.8x the execution, so most of it CANNOT be
+    hidden).  Everything streamed, pipelined against sequential, the first layer resident, and the largest residency
+    the arena holds; hidden fraction from the per-layer event records; predictor from one profiling run; streamed
+    and partially resident outputs compared bit for bit on the device."""
     import numpy as np
-    c = CFG.decoder_8b(max_seq=T, vocab=0)
+    if which == "decoder":
+        T = 16384
+        c = CFG.decoder_8b(max_seq=T, vocab=0)
+        name = "8B-class decoder prefill, 36 layers"
+    else:
+        T, cap = 8192, 2e9
+        c = CFG.vit_encoder()
+        name = "27-layer encoder"
     L = c.n_layers
     eng = Engine(int(cap), device=0)
     try:
@@ -396,14 +404,16 @@ def long_prefill_leg(B, CFG, Engine, torch, log, cap, T=16384):
         xp, xv = eng.alloc_f32(T * c.d_model)
         yp, yv = eng.alloc_f32(T * c.d_model)
         eng.upload(xv, CFG.make_tokens(T, c.d_model, seed=7))
-        tried = eng.pick_copy_stream(mid, T, xp, yp, passes=1)
-        log("long prefill copy-stream candidates (ms per fully streamed pass): " + ", ".join("%.1f" % t for _, t in tried))
-        prof = ctx.profile(mid, L, T, 0, xp, iters=2)
+        tried = eng.pick_copy_stream(mid, T, xp, yp, passes=1 if which == "decoder" else 3)
+        log("long %s copy-stream candidates (ms per fully streamed pass): " % which + ", ".join("%.1f" % t for _, t in tried))
+        prof = ctx.profile(mid, L, T, 0, xp, iters=2 if which == "decoder" else 4)
         col = lambda key: [p_[key] for p_ in prof]
         c_dma, c_cont, c_exe, c_hot, c_fence = (col(k_) for k_ in ("c_dma_ms", "c_dma_cont_ms", "c_exe_ms", "c_exe_hot_ms", "c_fence_ms"))
+        pairs = T * (T + 1) / 2.0 if c.causal else float(T) * T
+        ff = 6.0 if c.act == CFG.ACT_SWIGLU else 4.0
         flops_layer = 2.0 * T * c.d_model * (c.n_q_heads * c.d_head + 2 * c.n_kv_heads * c.d_head) \
-            + 2.0 * T * c.d_model * c.n_q_heads * c.d_head + 6.0 * T * c.d_model * c.d_ff \
-            + 4.0 * c.d_head * c.n_q_heads * (T * (T + 1) / 2.0)
+            + 2.0 * T * c.d_model * c.n_q_heads * c.d_head + ff * T * c.d_model * c.d_ff \
+            + 4.0 * c.d_head * c.n_q_heads * pairs
         roof_layer_ms = max(packed / (LINK_GBPS_THEORY * 1e6), flops_layer / (PEAK_BF16_TFLOPS * 1e9))
 
         def measure(k, mode):
@@ -412,12 +422,14 @@ def long_prefill_leg(B, CFG, Engine, torch, log, cap, T=16384):
             ctx.forward(mid, xp, yp, T, 0)
             ctx.sync()
             samples = []
+            n_rep = 1 if which == "decoder" else 4
             for _ in range(5):
                 torch.cuda.synchronize()
                 t = time.perf_counter()
-                ctx.forward(mid, xp, yp, T, 0)
+                for _ in range(n_rep):
+                    ctx.forward(mid, xp, yp, T, 0)
                 ctx.sync()
-                samples.append((time.perf_counter() - t) * 1e3)
+                samples.append((time.perf_counter() - t) * 1e3 / n_rep)
             ctx.set_timing(True)
             ctx.forward(mid, xp, yp, T, 0)
             st = ctx.collect_stats()
@@ -459,10 +471,10 @@ def long_prefill_leg(B, CFG, Engine, torch, log, cap, T=16384):
             identical = bool(torch.equal(yv.view(torch.int32), ref.view(torch.int32)))
         del ref
         for r in rows:
-            log("long prefill T=%d k=%2d %-10s %.1f ms (predicted %.1f, %+.2f%%) hidden %.3f H2D %.1f GB/s roofline frac %.3f" %
-                (T, r["k"], r["mode"], r["measured_ms"], r["predicted_ms"], r["pred_err_pct"], r["hidden_frac"], r["h2d_gbps"],
+            log("long %s T=%d k=%2d %-10s %.2f ms (predicted %.2f, %+.2f%%) hidden %.3f H2D %.1f GB/s roofline frac %.3f" %
+                (which, T, r["k"], r["mode"], r["measured_ms"], r["predicted_ms"], r["pred_err_pct"], r["hidden_frac"], r["h2d_gbps"],
                  r["roofline_frac"]))
-        return {"workload": "8B-class decoder prefill, 36 layers, T=%d, cap %.3g B" % (T, cap), "layer_bytes": packed,
+        return {"workload": "%s, T=%d, cap %.3g B" % (name, T, cap), "layer_bytes": packed,
                 "layer_flop": flops_layer,
                 "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_dma_cont_ms": round(float(np.mean(c_cont)), 4),
                             "c_exe_ms": round(float(np.mean(c_exe)), 4), "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
@@ -650,7 +662,8 @@ def main():
     if args.only:
         leg = {"vit": lambda: vit_leg(B, CFG, Engine, torch, log),
                "vla": lambda: vla_leg(B, CFG, Engine, torch, log, int(args.cap)),
-               "long": lambda: long_prefill_leg(B, CFG, Engine, torch, log, int(args.cap))}[args.only]
+               "long": lambda: long_prefill_leg(B, CFG, Engine, torch, log, int(args.cap)),
+               "long_encoder": lambda: long_prefill_leg(B, CFG, Engine, torch, log, int(args.cap), which="encoder")}[args.only]
         print(json.dumps({"only": args.only, "record": leg()}), flush=True)
         return
 
@@ -984,6 +997,7 @@ def main():
     if "long" in legs:
         try:
             out["extras"]["long_prefill"] = long_prefill_leg(B, CFG, Engine, torch, log, cap)
+            out["extras"]["long_encoder"] = long_prefill_leg(B, CFG, Engine, torch, log, cap, which="encoder")
             # the execution-intensive regime next to the streamed headline figures (what a record of the line's
             # top-level objects keeps)
             lp = [r for r in out["extras"]["long_prefill"]["runs"] if r["k"] == 0 and r["mode"] == "pipelined"]
