@@ -211,7 +211,7 @@ int32_t dl_sync(dl_ctx* ctx);
  * hipMalloc, or callers that hold the head's tensors in device memory of their own and have no context or arena.
  * The greedy step of dl_greedy_step on plain device pointers: logits = FinalNorm(h) * W_head^T in fp32, token = lowest
  * index of the maximum, x_dev = E[token]; the same two kernels, enqueued on `stream` (a hipStream_t of `device`, which
- * is made current), no host synchronisation, no context touched.  The logits of the step live in a static device
+ * is current while the call runs; the caller's current device is restored on return), no host synchronisation, no context touched.  The logits of the step live in a static device
  * array of the library (one per GPU, 131072 floats + 256 bytes, held until the process ends); the call allocates
  * nothing, creates no event, and records nothing a graph capture could not hold.
  * h_dev: device fp32 [d_model]; head_dev, embed_dev: device BF16 [vocab, d_model] (embed_dev and x_dev may both be

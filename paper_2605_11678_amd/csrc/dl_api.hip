@@ -1042,7 +1042,17 @@ int32_t dl_greedy_step_static(int32_t device, void* stream, const void* h_dev, c
     if (!h_dev || !head_dev || !norm_g_dev || !token_dev || (norm == DL_NORM_LN && !norm_b_dev))
         return bad(DL_ERR_INVALID_ARG, "null device pointer");
     if ((x_dev == nullptr) != (embed_dev == nullptr)) return bad(DL_ERR_INVALID_ARG, "x_dev and embed_dev go together");
-    hipError_t e = hipSetDevice(device);
+    // the call runs with `device` current and leaves the caller's current device as it found it
+    struct DeviceGuard {
+        int prev = -1;
+        ~DeviceGuard() { if (prev >= 0) (void)hipSetDevice(prev); }
+    } guard;
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e == hipSuccess && cur != device) {
+        e = hipSetDevice(device);
+        if (e == hipSuccess) guard.prev = cur;
+    }
     void* sp = nullptr;
     if (e == hipSuccess) e = static_scratch_ptr(device, &sp);
     if (e != hipSuccess) return bad(DL_ERR_DEVICE, std::string("static scratch of the device: ") + hipGetErrorString(e));
