@@ -121,7 +121,8 @@ int32_t dl_arena_stats(const dl_ctx* ctx, uint64_t* used, uint64_t* peak, uint64
 int32_t dl_residency_budget(const dl_ctx* ctx, uint64_t* bytes);
 
 /* compute_stream / copy_stream: hipStream_t handles owned by the caller; distinct; default priority.
- * Sec. IV-C: one queue executes layers, the other prefetches parameters. */
+ * Sec. IV-C: one queue executes layers, the other prefetches parameters.  Every call of a device context that
+ * enqueues work returns DL_ERR_BAD_STATE until the streams are set. */
 int32_t dl_set_streams(dl_ctx* ctx, void* compute_stream, void* copy_stream);
 
 /* ---- registering a layer stack (one-time, untimed) ------------------------------------- */

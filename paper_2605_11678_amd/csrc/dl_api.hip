@@ -947,6 +947,7 @@ int32_t dl_embed_token(dl_ctx* c, int32_t module, int32_t token, void* x_dev) {
     if (token < 0 || token >= M->d.vocab) return fail(c, DL_ERR_INVALID_ARG, "token out of range");
     if (!on_gpu(c)) return DL_OK;
     if (!x_dev) return fail(c, DL_ERR_INVALID_ARG, "null output");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
     dlk::embed_row(reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_EMBED]), M->d.d_model, nullptr, token,
                    static_cast<float*>(x_dev), c->s_compute);
     DL_HIP(c, hipGetLastError());
@@ -963,6 +964,7 @@ int32_t dl_final_norm(dl_ctx* c, int32_t module, const void* h, void* out, int32
     if (T < 1) return fail(c, DL_ERR_INVALID_ARG, "n_tokens < 1");
     if (!on_gpu(c)) return DL_OK;
     if (!h || !out) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
     dlk::norm_rows(M->d.norm, static_cast<const float*>(h),
                    reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_G]),
                    M->rt_set[DL_R_FINAL_NORM_B] ? reinterpret_cast<const bf16_t*>(c->base + M->rt_off[DL_R_FINAL_NORM_B]) : nullptr,
@@ -981,6 +983,7 @@ static int32_t head_common(dl_ctx* c, Module* M, const void* h, int32_t* token_c
     if (x_next && !M->rt_set[DL_R_EMBED]) return fail(c, DL_ERR_BAD_STATE, "embedding table not set");
     if (!on_gpu(c)) return DL_OK;
     if (!h) return fail(c, DL_ERR_INVALID_ARG, "null hidden state");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
     uint8_t* ws = c->base + M->ws_off;
     float* logits = reinterpret_cast<float*>(ws + M->W.logits);
     int32_t* tok = reinterpret_cast<int32_t*>(ws + M->W.token);
@@ -1144,6 +1147,7 @@ int32_t dl_mean_pool(dl_ctx* c, const void* x, void* y, int32_t n_out, int32_t g
     if (n_out < 1 || group < 1 || d < 1) return fail(c, DL_ERR_INVALID_ARG, "bad sizes");
     if (!on_gpu(c)) return DL_OK;
     if (!x || !y || x == y) return fail(c, DL_ERR_INVALID_ARG, "null or aliasing pointers");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
     dlk::mean_pool_rows(static_cast<const float*>(x), static_cast<float*>(y), n_out, group, d, c->s_compute);
     DL_HIP(c, hipGetLastError());
     return DL_OK;
@@ -1152,8 +1156,9 @@ int32_t dl_mean_pool(dl_ctx* c, const void* x, void* y, int32_t n_out, int32_t g
 int32_t dl_axpy(dl_ctx* c, void* y, float alpha, const void* x, uint64_t n) {
     int32_t rc = enter(c);
     if (rc) return rc;
-    if (!on_gpu(c)) return DL_OK;
+    if (!on_gpu(c) || n == 0) return DL_OK;
     if (!x || !y) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
     dlk::axpy_f32(static_cast<float*>(y), alpha, static_cast<const float*>(x), n, c->s_compute);
     DL_HIP(c, hipGetLastError());
     return DL_OK;
@@ -1165,6 +1170,7 @@ int32_t dl_add_time_embedding(dl_ctx* c, const void* x, void* y, float tval, int
     if (T < 1 || d < 2 || d % 2) return fail(c, DL_ERR_INVALID_ARG, "bad sizes");
     if (!on_gpu(c)) return DL_OK;
     if (!x || !y) return fail(c, DL_ERR_INVALID_ARG, "null pointer");
+    if (!c->streams_set) return fail(c, DL_ERR_BAD_STATE, "streams not set");
     dlk::add_time_embedding(static_cast<const float*>(x), static_cast<float*>(y), tval, T, d, c->s_compute);
     DL_HIP(c, hipGetLastError());
     return DL_OK;
