@@ -164,3 +164,23 @@ def test_identity_layer_is_exact():
         assert np.array_equal(g.forward(x), x)
     finally:
         g.close()
+
+
+def test_enqueuing_calls_are_refused_before_the_streams_are_set():
+    """A device context without streams must return DL_ERR_BAD_STATE from every call that would launch a kernel,
+    not fall back to the null stream."""
+    import torch
+    ctx = B.Context(0)
+    try:
+        arena = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+        ctx.set_arena(arena.data_ptr(), arena.numel(), keep=arena)
+        a = ctx.arena_alloc(4096)
+        b = ctx.arena_alloc(4096)
+        for call in (lambda: ctx.axpy(a, 0.5, b, 16),
+                     lambda: ctx.mean_pool(a, b, 4, 2, 8),
+                     lambda: ctx.add_time_embedding(a, b, 0.3, 4, 8)):
+            with pytest.raises(B.DLError) as e:
+                call()
+            assert e.value.code == B.DL_ERR_BAD_STATE
+    finally:
+        ctx.destroy()
