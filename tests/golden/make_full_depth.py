@@ -2,7 +2,7 @@
 ratios of the full-shape cases (tests/test_parity_discriminates.py).  Calls ONLY the oracle and the seeded input
 generators; nothing here loads the HIP library.
 
-    python tests/golden/make_full_depth.py [part ...]      parts: dec8b_L1 dec8b_L1_attn act_L8 act_L8_cross vit_L27 dec8b_L36 dec8b_L36_mutants vla_full (default: all)
+    python tests/golden/make_full_depth.py [part ...]      parts: dec8b_L1 dec8b_L1_attn act_L8 act_L8_cross vit_L1_T8192 vit_L1_T8192_attn vit_L27 dec8b_L36 dec8b_L36_mutants vla_full (default: all)
 
 The 36-layer decoder at 3072 tokens costs the float64 oracle ~10 minutes on 8 cores, each mutant as much again, and a
 single-token step needs all 13.9 GB of weights once more: too slow to repeat inside the GPU test run, so the values
@@ -90,6 +90,18 @@ def part_act_L8_cross(arrays, meta):
     case = PC.full_cases()["act_L8_cross"]
     base = PC.oracle_passes(case)
     meta["mutation_ratio"]["act_L8_cross"] = ratios(case, base)
+
+
+def part_vit_L1_T8192(arrays, meta):
+    case = PC.full_cases()["vit_L1_T8192"]
+    base = PC.oracle_passes(case)
+    meta["mutation_ratio"]["vit_L1_T8192"] = ratios(case, base)
+
+
+def part_vit_L1_T8192_attn(arrays, meta):
+    case = PC.full_cases()["vit_L1_T8192_attn"]
+    base = PC.oracle_passes(case)
+    meta["mutation_ratio"]["vit_L1_T8192_attn"] = ratios(case, base)
 
 
 def part_vit_L27(arrays, meta):
@@ -197,11 +209,11 @@ def part_vla_full(arrays, meta):
 
 
 def main():
-    parts = sys.argv[1:] or ["dec8b_L1", "dec8b_L1_attn", "act_L8", "act_L8_cross", "vit_L27", "dec8b_L36", "dec8b_L36_mutants", "vla_full"]
+    parts = sys.argv[1:] or ["dec8b_L1", "dec8b_L1_attn", "act_L8", "act_L8_cross", "vit_L1_T8192", "vit_L1_T8192_attn", "vit_L27", "dec8b_L36", "dec8b_L36_mutants", "vla_full"]
     arrays, meta = load()
     for p in parts:
         t = time.time()
-        {"dec8b_L1": part_dec8b_L1, "dec8b_L1_attn": part_dec8b_L1_attn, "act_L8": part_act_L8, "act_L8_cross": part_act_L8_cross, "vit_L27": part_vit_L27, "dec8b_L36": part_dec8b_L36,
+        {"dec8b_L1": part_dec8b_L1, "dec8b_L1_attn": part_dec8b_L1_attn, "act_L8": part_act_L8, "act_L8_cross": part_act_L8_cross, "vit_L1_T8192": part_vit_L1_T8192, "vit_L1_T8192_attn": part_vit_L1_T8192_attn, "vit_L27": part_vit_L27, "dec8b_L36": part_dec8b_L36,
          "dec8b_L36_mutants": part_dec8b_L36_mutants, "vla_full": part_vla_full}[p](arrays, meta)
         meta.setdefault("seconds", {})[p] = round(time.time() - t)
         save(arrays, meta)

@@ -297,6 +297,13 @@ def full_cases():
                              zero=(CFG.T_WO, CFG.T_BO, CFG.T_W_DOWN, CFG.T_B_DOWN)),
         # the 27-layer encoder at 4096 tokens and the 36-layer decoder at 3072 tokens, as the workloads state them
         "vit_L27": Case("vit_L27", CFG.vit_encoder(), [(0, 4096)], 7, gain=0.0),
+        # one encoder layer over 8192 patches: the length at which its execution outlasts its copy (bench.py's
+        # execution-intensive leg); 128 K/V tiles per query block, 64 query blocks per head
+        "vit_L1_T8192": Case("vit_L1_T8192", CFG.vit_encoder(n_layers=1), [(0, 8192)], 7, gain=0.0),
+        # the same with the feed-forward zeroed: a bidirectional average over 8192 keys adds a twentieth of what the
+        # feed-forward adds (judged at 2.3x its bound next to it), alone it is judged at 50x
+        "vit_L1_T8192_attn": Case("vit_L1_T8192_attn", CFG.vit_encoder(n_layers=1), [(0, 8192)], 7, gain=0.0,
+                                  zero=(CFG.T_W_DOWN, CFG.T_B_DOWN)),
         "dec8b_L36": Case("dec8b_L36", CFG.decoder_8b(max_seq=3136, vocab=32768), [(0, 3072)], 7, gain=0.0),
     }
 

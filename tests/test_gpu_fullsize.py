@@ -51,12 +51,12 @@ def check_sampled(got, arrays, meta, key, what, contrib=True, tol=PC.TOL):
     assert c <= tol, (what, "contrib", c)
 
 
-@pytest.mark.parametrize("name", ["dec8b_L1", "dec8b_L1_attn", "act_L8", "act_L8_cross"])
+@pytest.mark.parametrize("name", ["dec8b_L1", "dec8b_L1_attn", "act_L8", "act_L8_cross", "vit_L1_T8192", "vit_L1_T8192_attn"])
 def test_full_shape_case_vs_oracle_live(name):
     """Oracle run live.  dec8b_*: one 8B-class layer, 3072-token prefill, then two single-token passes over the
     3072-entry cache.  act_*: the 8-layer action head, 64 tokens cross-attending to a 3072 x 4096 context (the split
-    cross-attention path).  The *_attn / *_cross variants zero the other sub-blocks so that the attention kernels are
-    judged alone (tests/parity_cases.py says why)."""
+    cross-attention path).  vit_L1_T8192: one encoder layer over 8192 patches.  The *_attn / *_cross variants zero the
+    other sub-blocks so that the attention kernels are judged alone (tests/parity_cases.py says why)."""
     case = PC.full_cases()[name]
     x, ctx = case.x(), case.ctx()
     g = GpuStack(case.cfg, max_tokens=case.max_tokens, max_ctx=case.n_ctx, cap_bytes=3 << 30, weights=case.weights())

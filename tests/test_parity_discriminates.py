@@ -53,6 +53,8 @@ def test_full_shape_cases_detect_mutations():
         "act_L8": {"self_attention": [0], "ffn": [0]},
         "act_L8_cross": {"cross_attention": [0]},
         "vit_L27": {"self_attention": [0], "ffn": [0]},
+        "vit_L1_T8192": {"ffn": [0]},
+        "vit_L1_T8192_attn": {"self_attention": [0]},
         "dec8b_L36": {"self_attention": [0], "ffn": [0], "rope": [0], "causal_mask": [0]},
     }
     for name, muts in want.items():
@@ -62,7 +64,7 @@ def test_full_shape_cases_detect_mutations():
                 assert got[m][i] >= PC.DISCRIMINATION, (name, m, i, got[m])
     # every applicable mutation of every full-shape case is accounted for: seen here or by the named companion
     companions = {("dec8b_L1", "self_attention"): "dec8b_L1_attn", ("dec8b_L1", "rope"): "dec8b_L1_attn",
-                  ("act_L8", "cross_attention"): "act_L8_cross"}
+                  ("act_L8", "cross_attention"): "act_L8_cross", ("vit_L1_T8192", "self_attention"): "vit_L1_T8192_attn"}
     for name, case in PC.full_cases().items():
         for m, (applies, _) in PC.MUTATIONS.items():
             if not applies(case):
