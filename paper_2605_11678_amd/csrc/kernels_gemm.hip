@@ -478,9 +478,16 @@ __device__ __forceinline__ bool tile_of(int bid, int tiles_m, int tiles_n, int* 
     return true;
 }
 
-#define DL_GLL16(g, l)                                                                                   \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
-                                     (__attribute__((address_space(3))) void*)(l), 16, 0, 0)
+// 16 bytes per lane from a buffer straight into LDS (buffer_load_dwordx4 ... offen lds): the address is the buffer's
+// base (four scalar registers, set up once) + a per-lane 32-bit offset that never changes + a scalar offset that
+// advances with the k-tile, so a copy costs the vector unit nothing (a flat 64-bit address per lane cost 1.5 vector
+// additions per copy instruction, which a wavefront cannot overlap with its own MFMAs).  Offsets past the buffer's
+// size read zeros.
+#define DL_BLL16(rsrc, voff, soff, l)                                                                    \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds((rsrc), (__attribute__((address_space(3))) void*)(l), 16,  \
+                                             int(voff), int(soff), 0, 0)
+// third dword of a raw buffer resource on gfx9: 32-bit data format, no swizzle, offsets checked against the size
+constexpr int kBufferFlags = 0x00020000;
 
 // s_waitcnt with an explicit vector-memory count (6 bits, split 4 + 2 in the gfx9 encoding); expcnt is left
 // unconstrained, lgkmcnt is either unconstrained or zero
@@ -516,7 +523,9 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
     constexpr int JA = BM / 32, JB = BN / 32;            // 1 KB copy blocks (8 rows x 128 B) per wavefront and k-tile
     constexpr int RT = TM * TN / 4;
     static_assert(BM % (32 * WM) == 0 && BN % (32 * WN) == 0, "whole MFMA tiles per wavefront");
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wavefront index is the same in every lane: as a scalar it keeps the LDS addresses of the copies (M0) and
+    // everything else derived from it out of the vector unit
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
     f32x16 acc[TM][TN];
@@ -543,8 +552,11 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
         const int row = 8 * (wave + 4 * j) + (lane >> 3), lc = (lane & 7) ^ ((row >> 1) & 7);
         offB[j] = uint32_t((size_t(min(n0 + row, p.N - 1)) * p.ldb + lc * 8) * 2);
     }
-    const char* gA = reinterpret_cast<const char*>(p.A);
-    const char* gB = reinterpret_cast<const char*>(p.B);
+    // the host only takes this path for operands below 4 GB
+    const __amdgpu_buffer_rsrc_t gA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(p.A), 0, int(uint32_t(size_t(p.M) * p.lda * 2)), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t gB = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(p.B), 0, int(uint32_t(size_t(p.N) * p.ldb * 2)), kBufferFlags);
     // fragment read offsets (elements) inside a stage, one per 16-wide k step
     const int lr = lane & 31, g2 = lane >> 5;
     int rdA[4], rdB[4];
@@ -558,11 +570,11 @@ __device__ __forceinline__ void fast_tile(const GemmArgs& p, int m0, int n0, bf1
     bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
     auto copyA = [&](bf16_t* S, int kt) {
 #pragma unroll
-        for (int j = 0; j < JA; ++j) DL_GLL16(gA + size_t(kt) * (BK * 2) + offA[j], S + (wave + 4 * j) * 512);
+        for (int j = 0; j < JA; ++j) DL_BLL16(gA, offA[j], kt * (BK * 2), S + (wave + 4 * j) * 512);
     };
     auto copyB = [&](bf16_t* S, int kt) {
 #pragma unroll
-        for (int j = 0; j < JB; ++j) DL_GLL16(gB + size_t(kt) * (BK * 2) + offB[j], S + BM * BK + (wave + 4 * j) * 512);
+        for (int j = 0; j < JB; ++j) DL_BLL16(gB, offB[j], kt * (BK * 2), S + BM * BK + (wave + 4 * j) * 512);
     };
     auto ldfrag = [&](bf16x8* a, bf16x8* b, const bf16_t* S, int kk) {
 #pragma unroll
