@@ -108,6 +108,13 @@ bool validate_desc(const dl_module_desc& d, std::string* why) {
     // the single-token attention kernel maps the query heads of one KV head onto the 32 columns of one MFMA tile
     if (d.max_seq > 0 && d.n_q_heads / d.n_kv_heads > 32)
         return bad("with a KV cache at most 32 query heads may share one KV head");
+    // the kernels address an operand (an activation matrix, the keys or values of one head) with 32-bit byte offsets
+    {
+        const uint64_t positions = uint64_t(std::max(std::max(d.max_seq, d.max_tokens), d.max_ctx));
+        const uint64_t widest = std::max(uint64_t(d.n_q_heads + 2 * d.n_kv_heads) * uint64_t(d.d_head),
+                                         std::max(uint64_t(d.d_ff) * (d.act == DL_ACT_SWIGLU ? 2u : 1u), uint64_t(std::max(d.d_model, d.d_ctx))));
+        if (positions * widest * 4 >= (1ull << 32)) return bad("max_seq / max_tokens / max_ctx times the widest row exceeds 4 GB");
+    }
     if (d.vocab < 0) return bad("vocab < 0");
     if (!(d.norm_eps >= 0)) return bad("norm_eps < 0");
     return true;

@@ -42,9 +42,13 @@ __device__ __forceinline__ bf16_t f_to_bf16_attn(float f) {
     return *reinterpret_cast<bf16_t*>(&b);
 }
 
-#define DL_ATT_GLL16(g, l)                                                                               \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
-                                     (__attribute__((address_space(3))) void*)(l), 16, 0, 0)
+// 16 bytes per lane from a buffer straight into LDS (buffer_load_dwordx4 ... offen lds): buffer base in four scalar
+// registers, a per-lane 32-bit offset that is the same for every tile, a scalar offset that advances with the tile.
+// Offsets past the buffer's size read zeros.
+#define DL_ATT_BLL16(rsrc, voff, soff, l)                                                                \
+    __builtin_amdgcn_raw_ptr_buffer_load_lds((rsrc), (__attribute__((address_space(3))) void*)(l), 16,  \
+                                             int(voff), int(soff), 0, 0)
+constexpr int kAttnBufferFlags = 0x00020000;   // raw buffer, 32-bit data format, offsets checked against the size
 
 // K / V^T tiles sit in LDS without padding, filled by global -> LDS copies (a wavefront instruction lands 64 chunks of
 // 16 bytes contiguously).  A b128 fragment read serves 16 lanes = 16 rows of one logical chunk per cycle across 64
@@ -72,7 +76,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     __shared__ __attribute__((aligned(1024))) bf16_t sV0[DV * BKV];
     __shared__ __attribute__((aligned(1024))) bf16_t sV1[DV * BKV];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // the wavefront index as a scalar: the head, the K / V^T base and the LDS addresses of the copies stay out of
+    // the vector unit
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lq = lane & 31, g2 = lane >> 5;
     // MFMA row lq of a score tile holds key krow: bits 2 and 3 swapped.  With that order the 8 accumulator
     // registers a lane turns into one B-operand fragment of P^T belong to 8 CONSECUTIVE keys
@@ -111,8 +117,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         for (int r = 0; r < 16; ++r) accO[dt][r] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;             // running maximum (raw score units) and sum
 
-    const bf16_t* kbase = p.k + size_t(kvh) * p.k_head_stride;
-    const bf16_t* vbase = p.vt + size_t(kvh) * p.v_head_stride;
+    // K of this KV head: S rows of ldk elements (what lies behind row S - 1 is out of range and reads zeros);
+    // V^T: dh rows of ldv positions.  The host keeps both below 4 GB.
+    const __amdgpu_buffer_rsrc_t kbuf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(p.k + size_t(kvh) * p.k_head_stride), 0, int(uint32_t(size_t(p.S) * p.ldk * 2)), kAttnBufferFlags);
+    const __amdgpu_buffer_rsrc_t vbuf = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<bf16_t*>(p.vt + size_t(kvh) * p.v_head_stride), 0, int(uint32_t(size_t(p.dh) * p.ldv * 2)), kAttnBufferFlags);
     int kv_end = p.S;                                  // block-uniform: keys any query of the block may see
     if (p.causal) kv_end = min(p.S, p.q_pos0 + min(q0 + QB, p.T));
     const int wave_last = p.q_pos0 + min(wq0 + 31, p.T - 1);   // last query position of this wavefront
@@ -120,33 +130,44 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     const int t_begin = SPLIT ? int(blockIdx.z) * tps : 0;
     const int nt = SPLIT ? min(nt_all, t_begin + tps) : nt_all;      // tiles t_begin .. nt - 1
 
-    // Copies are unconditional with clamped addresses:
-    //  * K rows past S repeat row S-1; those keys are masked to -inf (a tile that contains them is always masked);
+    // Copies are unconditional; a lane's offset inside its buffer is the same for every tile (computed once here)
+    // plus the tile's scalar offset:
+    //  * K rows past S lie outside the buffer and read zeros; those keys are masked to -inf (a tile that contains
+    //    them is always masked);
     //  * feature chunks past dh (zero padding of the head dimension) re-read chunk 0: they meet zero Q features;
-    //  * V^T rows past dh repeat row dh-1 (they produce output features nobody stores); V^T position chunks that
-    //    start past S re-read the chunk at 0, and a chunk that straddles S brings along up to 7 stale positions:
-    //    their probabilities are exact zeros and the buffers hold finite numbers everywhere (zeroed when the
-    //    module is finalised, rows padded to a multiple of 64 positions);
+    //  * V^T rows past dh repeat row dh-1 (they produce output features nobody stores); V^T positions past S are
+    //    read as they are (rows are padded to a multiple of 64 positions): their probabilities are exact zeros and
+    //    the buffers hold finite numbers everywhere (zeroed when the module is finalised), what would lie past the
+    //    last row's end reads zeros;
     //  * ONES: the last V^T row of a stage (a padding row) holds ones, written once below; the copies skip it.
     // Copy instruction ii of a K tile lands chunks 64 ii .. 64 ii + 63 of the row-major tile (row = id / KCPR); of a
     // V^T tile rows 8 ii .. 8 ii + 7.  A lane fetches the LOGICAL chunk that belongs at its physical position.
-    auto copy_tile = [&](int j0, bf16_t* sKd, bf16_t* sVd) {
+    uint32_t koff[NKI], voff[NVI];
+#pragma unroll
+    for (int i = 0; i < NKI; ++i) {
+        const int id = 64 * (wave + 4 * i) + lane, row = id / KCPR, c = (id % KCPR) ^ chunk_swizzle<KCPR>(row);
+        koff[i] = uint32_t((size_t(row) * p.ldk + (8 * c < p.dh ? 8 * c : 0)) * 2);
+    }
+#pragma unroll
+    for (int i = 0; i < NVI; ++i) {
+        const int row = 8 * (wave + 4 * i) + (lane >> 3), c = (lane & 7) ^ chunk_swizzle<8>(row);
+        voff[i] = uint32_t((size_t(min(row, p.dh - 1)) * p.ldv + 8 * c) * 2);
+    }
+    const int k_tile_bytes = BKV * p.ldk * 2;
+    auto copy_tile = [&](int t, bf16_t* sKd, bf16_t* sVd) {
 #pragma unroll
         for (int i = 0; i < NKI; ++i) {
             const int ii = wave + 4 * i;
             if (KCPR % 4 != 0 && ii >= KCPR) continue;           // wavefront-uniform
-            const int id = 64 * ii + lane, row = id / KCPR, c = (id % KCPR) ^ chunk_swizzle<KCPR>(row);
-            DL_ATT_GLL16(kbase + size_t(min(j0 + row, p.S - 1)) * p.ldk + (8 * c < p.dh ? 8 * c : 0), sKd + 512 * ii);
+            DL_ATT_BLL16(kbuf, koff[i], t * k_tile_bytes, sKd + 512 * ii);
         }
 #pragma unroll
         for (int i = 0; i < NVI; ++i) {
             const int ii = wave + 4 * i;
-            const int row = 8 * ii + (lane >> 3), c = (lane & 7) ^ chunk_swizzle<8>(row);
-            const bf16_t* src = vbase + size_t(min(row, p.dh - 1)) * p.ldv + (j0 + 8 * c < p.S ? j0 + 8 * c : 0);
             if (ONES && ii == DV / 8 - 1) {                      // the last row of the tile keeps its ones
-                if (lane < 56) DL_ATT_GLL16(src, sVd + 512 * ii);
+                if (lane < 56) DL_ATT_BLL16(vbuf, voff[i], t * (BKV * 2), sVd + 512 * ii);
             } else {
-                DL_ATT_GLL16(src, sVd + 512 * ii);
+                DL_ATT_BLL16(vbuf, voff[i], t * (BKV * 2), sVd + 512 * ii);
             }
         }
     };
@@ -155,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
         *reinterpret_cast<u32x4*>((tid < 8 ? sV0 : sV1) + (DV - 1) * BKV + 8 * (tid & 7)) = ones;
     }
 
-    copy_tile(t_begin * BKV, sK0, sV0);                // clamped addresses: safe for any S >= 1 (the host rejects S <= 0)
+    copy_tile(t_begin, sK0, sV0);                      // range-checked by the buffers: safe for any S >= 1 (the host rejects S <= 0)
     bf16x8 qf[DK / 16];
 #pragma unroll
     for (int kk = 0; kk < DK / 16; ++kk) {
@@ -178,7 +199,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(AttnArgs p, float scale_lo
     // one K/V tile: cK / cV the stage it is read from, nK / nV the stage the next tile is copied into meanwhile
     auto tile_step = [&](int t, const bf16_t* cK, const bf16_t* cV, bf16_t* nK, bf16_t* nV) {
         const int j0 = t * BKV;
-        if (t + 1 < nt) copy_tile(j0 + BKV, nK, nV);
+        if (t + 1 < nt) copy_tile(t + 1, nK, nV);
         // a wavefront whose queries all lie before this tile has nothing to add (causal)
         const bool active = !p.causal || j0 <= wave_last;
         if (active) {
