@@ -119,6 +119,8 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
     c_exe = [p["c_exe_ms"] for p in prof]
     c_hot = [p["c_exe_hot_ms"] for p in prof]
     c_fence = [p["c_fence_ms"] for p in prof]
+    c_fhot = [p["c_fence_hot_ms"] for p in prof]
+    c_load = [p["c_exe_loaded_ms"] for p in prof]
     res = {"profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_dma_cont_ms": round(float(np.mean(c_cont)), 4),
                        "c_exe_ms": round(float(np.mean(c_exe)), 4),
                        "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
@@ -185,7 +187,7 @@ def decode_leg(eng, ctx, mid, c, T, L, xp, yp, packed, B, torch, log):
         starts = [i == 0 for i in range(L)] * steps
         return B.timeline(c_dma * steps, c_hot * steps, streamed, starts, wrap_prefetch=wrap, n_slots=n_slots,
                           c_exe_idle_ms=c_exe * steps, c_fence_ms=c_fence * steps,
-                          c_dma_cont_ms=c_cont * steps)["total"] / steps + head_ms
+                          c_dma_cont_ms=c_cont * steps, c_fence_hot_ms=c_fhot * steps, c_exe_loaded_ms=c_load * steps)["total"] / steps + head_ms
 
     def fit_count():
         for k in range(L, -1, -1):
@@ -294,6 +296,8 @@ def vit_leg(B, CFG, Engine, torch, log):
     c_exe = [p["c_exe_ms"] for p in prof]
     c_hot = [p["c_exe_hot_ms"] for p in prof]
     c_fence = [p["c_fence_ms"] for p in prof]
+    c_fhot = [p["c_fence_hot_ms"] for p in prof]
+    c_load = [p["c_exe_loaded_ms"] for p in prof]
     rows = []
     for k in (0, 7, 14, 20, 24, 27):
         res = B.place_interleaved(L, k)
@@ -315,7 +319,7 @@ def vit_leg(B, CFG, Engine, torch, log):
         ctx.set_timing(False)
         rs = set(res)
         pred = B.timeline(c_dma, c_hot, [i not in rs for i in range(L)], [i == 0 for i in range(L)],
-                          c_exe_idle_ms=c_exe, c_fence_ms=c_fence, c_dma_cont_ms=c_cont)["total"]
+                          c_exe_idle_ms=c_exe, c_fence_ms=c_fence, c_dma_cont_ms=c_cont, c_fence_hot_ms=c_fhot, c_exe_loaded_ms=c_load)["total"]
         rows.append({"k": k, "measured_ms": round(ms, 3), "predicted_ms": round(pred, 3),
                      "pred_err_pct": round((pred - ms) / ms * 100, 2), "hidden_frac": round(st["hidden_frac"], 4),
                      "h2d_gbps": round(st["h2d_gbps"], 2)})
@@ -347,7 +351,7 @@ def vit_leg(B, CFG, Engine, torch, log):
                 ms = float(np.median(samples))
                 rs = set(res)
                 pred = B.timeline(c_dma, c_hot, [i not in rs for i in range(L)], [i == 0 for i in range(L)],
-                                  c_exe_idle_ms=c_exe, c_fence_ms=c_fence, n_slots=n_slots, c_dma_cont_ms=c_cont)["total"]
+                                  c_exe_idle_ms=c_exe, c_fence_ms=c_fence, n_slots=n_slots, c_dma_cont_ms=c_cont, c_fence_hot_ms=c_fhot, c_exe_loaded_ms=c_load)["total"]
                 slot_rows.append({"k": k, "placement": name, "slots": n_slots, "measured_ms": round(ms, 3),
                                   "predicted_ms": round(pred, 3), "pred_err_pct": round((pred - ms) / ms * 100, 2)})
                 log("vit k=%2d %-20s slots=%d measured %.3f ms predicted %.3f ms" % (k, name, n_slots, ms, pred))
@@ -372,7 +376,8 @@ def vit_leg(B, CFG, Engine, torch, log):
            "roofline_frac_streamed_k0": round(L * packed / (LINK_GBPS_THEORY * 1e6) / rows[0]["measured_ms"], 4),
            "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_dma_cont_ms": round(float(np.mean(c_cont)), 4),
                        "c_exe_ms": round(float(np.mean(c_exe)), 4),
-                       "c_exe_hot_ms": round(float(np.mean(c_hot)), 4), "c_fence_ms": round(float(np.mean(c_fence)), 4),
+                       "c_exe_hot_ms": round(float(np.mean(c_hot)), 4), "c_exe_loaded_ms": round(float(np.mean(c_load)), 4),
+                       "c_fence_ms": round(float(np.mean(c_fence)), 4), "c_fence_hot_ms": round(float(np.mean(c_fhot)), 4),
                        "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 2)},
            "sweep": rows, "layer_flop": flops_layer,
            "resident_tflops": round(flops_layer * L / (rows[-1]["measured_ms"] * 1e-3) / 1e12, 1)}
@@ -408,7 +413,8 @@ def long_prefill_leg(B, CFG, Engine, torch, log, cap, which="decoder"):
         log("long %s copy-stream candidates (ms per fully streamed pass): " % which + ", ".join("%.1f" % t for _, t in tried))
         prof = ctx.profile(mid, L, T, 0, xp, iters=2 if which == "decoder" else 4)
         col = lambda key: [p_[key] for p_ in prof]
-        c_dma, c_cont, c_exe, c_hot, c_fence = (col(k_) for k_ in ("c_dma_ms", "c_dma_cont_ms", "c_exe_ms", "c_exe_hot_ms", "c_fence_ms"))
+        c_dma, c_cont, c_exe, c_hot, c_fence, c_fhot, c_load = (col(k_) for k_ in ("c_dma_ms", "c_dma_cont_ms", "c_exe_ms", "c_exe_hot_ms",
+                                                                                  "c_fence_ms", "c_fence_hot_ms", "c_exe_loaded_ms"))
         pairs = T * (T + 1) / 2.0 if c.causal else float(T) * T
         ff = 6.0 if c.act == CFG.ACT_SWIGLU else 4.0
         flops_layer = 2.0 * T * c.d_model * (c.n_q_heads * c.d_head + 2 * c.n_kv_heads * c.d_head) \
@@ -436,7 +442,7 @@ def long_prefill_leg(B, CFG, Engine, torch, log, cap, which="decoder"):
             ctx.set_timing(False)
             rs = set(B.place_interleaved(L, k))
             pred = B.timeline(c_dma, c_hot, [i not in rs for i in range(L)], [i == 0 for i in range(L)], mode=mode,
-                              c_exe_idle_ms=c_exe, c_fence_ms=c_fence, c_dma_cont_ms=c_cont)["total"]
+                              c_exe_idle_ms=c_exe, c_fence_ms=c_fence, c_dma_cont_ms=c_cont, c_fence_hot_ms=c_fhot, c_exe_loaded_ms=c_load)["total"]
             ms = float(np.median(samples))
             return {"k": k, "mode": "sequential" if mode == B.DL_MODE_SEQUENTIAL else "pipelined",
                     "measured_ms": round(ms, 2), "predicted_ms": round(pred, 2), "pred_err_pct": round((pred - ms) / ms * 100, 2),
@@ -478,7 +484,8 @@ def long_prefill_leg(B, CFG, Engine, torch, log, cap, which="decoder"):
                 "layer_flop": flops_layer,
                 "profile": {"c_dma_ms": round(float(np.mean(c_dma)), 4), "c_dma_cont_ms": round(float(np.mean(c_cont)), 4),
                             "c_exe_ms": round(float(np.mean(c_exe)), 4), "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
-                            "c_fence_ms": round(float(np.mean(c_fence)), 4), "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 3)},
+                            "c_fence_ms": round(float(np.mean(c_fence)), 4), "c_fence_hot_ms": round(float(np.mean(c_fhot)), 4),
+                            "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 3)},
                 "runs": rows, "table4_check": table4, "streamed_vs_partially_resident_bit_identical": identical}
     finally:
         eng.close()
@@ -562,10 +569,10 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
     glue_ms = (time.perf_counter() - t) * 1e3 / 10
 
     def predict(ks, wrap):
-        dma, cont, hot, idle, fence, streamed, starts, mids = [], [], [], [], [], [], [], []
+        dma, cont, hot, idle, fence, fhot, load, streamed, starts, mids = [], [], [], [], [], [], [], [], [], []
         def add_pass(mi, rows, res):
             for i, r in enumerate(rows):
-                dma.append(r["c_dma_ms"]); cont.append(r["c_dma_cont_ms"]); hot.append(r["c_exe_hot_ms"]); idle.append(r["c_exe_ms"]); fence.append(r["c_fence_ms"])
+                dma.append(r["c_dma_ms"]); cont.append(r["c_dma_cont_ms"]); hot.append(r["c_exe_hot_ms"]); idle.append(r["c_exe_ms"]); fence.append(r["c_fence_ms"]); fhot.append(r["c_fence_hot_ms"]); load.append(r["c_exe_loaded_ms"])
                 streamed.append(i not in res); starts.append(i == 0); mids.append(mi)
         rs = [set(B.place_interleaved(Ls[m], ks[m])) for m in range(3)]
         add_pass(0, P["vit"], rs[0])
@@ -575,7 +582,7 @@ def vla_leg(B, CFG, Engine, torch, log, cap, n_decode=64):
         for _ in range(10):
             add_pass(2, P["action"], rs[2])
         return B.timeline(dma, hot, streamed, starts, module_id=mids, wrap_prefetch=wrap, c_exe_idle_ms=idle,
-                          c_fence_ms=fence, c_dma_cont_ms=cont)["total"] \
+                          c_fence_ms=fence, c_dma_cont_ms=cont, c_fence_hot_ms=fhot, c_exe_loaded_ms=load)["total"] \
             + head_ms * n_decode + glue_ms
 
     def measure(ks, wrap, reps):
@@ -691,6 +698,8 @@ def main():
     c_exe = [p["c_exe_ms"] for p in prof]              # right after the copy (GPU was idle): the paper's C_EXE
     c_hot = [p["c_exe_hot_ms"] for p in prof]          # the same layer re-run at once (GPU busy)
     c_fence = [p["c_fence_ms"] for p in prof]          # cross-stream hand-offs of a streamed layer
+    c_fhot = [p["c_fence_hot_ms"] for p in prof]       # the same when the copy is long done as the layer starts
+    c_load = [p["c_exe_loaded_ms"] for p in prof]      # c_hot while copies run the whole time
     log("profile: C_DMA %.3f ms  C_EXE %.3f ms (%.3f ms when compute is continuous) per layer (means), r = %.2f" %
         (np.mean(c_dma), np.mean(c_exe), np.mean(c_hot), np.mean(c_dma) / np.mean(c_exe)))
 
@@ -713,7 +722,7 @@ def main():
         res = set(B.place_interleaved(L, k))
         streamed = [i not in res for i in range(L)]
         return B.timeline(c_dma, c_hot, streamed, [i == 0 for i in range(L)], mode=mode, c_exe_idle_ms=c_exe,
-                          c_fence_ms=c_fence, c_dma_cont_ms=c_cont)
+                          c_fence_ms=c_fence, c_dma_cont_ms=c_cont, c_fence_hot_ms=c_fhot, c_exe_loaded_ms=c_load)
 
     # ---- largest resident count the arena holds ----
     k_best = None
@@ -975,6 +984,7 @@ def main():
                     "c_exe_ms": round(float(np.mean(c_exe)), 4),
                     "c_exe_hot_ms": round(float(np.mean(c_hot)), 4),
                     "c_fence_ms": round(float(np.mean(c_fence)), 4),
+                    "c_fence_hot_ms": round(float(np.mean(c_fhot)), 4),
                     "r": round(float(np.mean(c_dma) / np.mean(c_exe)), 3),
                     "h2d_gbps": round(packed / (float(np.mean(c_dma)) * 1e6), 2),
                     "h2d_frac_of_63GBps": round(packed / (float(np.mean(c_dma)) * 1e6) / LINK_GBPS_THEORY, 3)},

@@ -179,14 +179,16 @@ int32_t dl_module_set_max_tokens(dl_ctx* ctx, int32_t module, int32_t max_tokens
 
 /* How many streaming passes (passes that copy at least one layer) may be unfinished when the next one is
  * enqueued (1..8; 0 = no limit).  Default 1: each further pass of short streamed layers in flight slowed copies and
- * kernels on MI355X (+4 % with two, +25 % with four).  Passes of resident layers only are never held back. */
+ * kernels on MI355X (+4 % with two, +25 % with four).  A pass counts as finished for this purpose when its last
+ * layer has started (the head of the next pass is then queued while that layer runs).  Passes of resident layers only
+ * are never held back. */
 int32_t dl_set_run_ahead(dl_ctx* ctx, int32_t passes);
 
 /* ---- the hot path (Sec. IV-C) ------------------------------------------------------------ */
 
 /* One pass over all layers of `module`; enqueues only, returns before the GPU finishes, except that a pass
  * which streams at least one layer first waits until the streaming pass dl_set_run_ahead (default one) passes
- * back has finished.
+ * back has reached its last layer.
  * x_dev: device fp32 [n_tokens, d_model] input;  y_dev: device fp32 [n_tokens, d_model] output
  * (may equal x_dev).  Token t sits at absolute position pos0 + t; with a KV cache the pass appends
  * its keys/values at those positions and attends over 0 .. pos0+t.  pos0 must be 0 without a cache.
@@ -300,11 +302,17 @@ typedef struct {
     double c_exe_ms;      /* un-overlapped execution time of the layer, run right after its copy (the GPU was idle) */
     double c_exe_hot_ms;  /* execution time of the layer inside an uninterrupted run of all layers (no copies, no
                              idle gaps): what a layer costs when compute is continuous, e.g. between resident layers */
+    double c_exe_loaded_ms; /* c_exe_hot_ms as it is while host-to-device copies run the whole time (the copies share HBM
+                             and the fabric with the kernels): the uninterrupted run once more next to a train of copies */
     double c_fence_ms;    /* the two cross-stream hand-offs of a streamed layer (copy end -> its first kernel, its last
                              kernel -> next copy start) as the sequential run shows them, less what the timing events
                              themselves cost (a sequential pass without them is timed too, and the hand-offs are
                              reduced so that copies + executions + hand-offs add up to that pass); charged to the
                              compute stream per streamed layer by dl_timeline */
+    double c_fence_hot_ms;/* what a streamed layer adds to the compute stream when its copy finished long before (the
+                             wait on the already completed DMA-done event and the compute-done record drain the queue
+                             between kernels): the uninterrupted run of all layers once more with those two operations
+                             around every layer, minus the run without them */
     uint64_t bytes;       /* bytes one copy moves */
 } dl_layer_profile;
 
@@ -312,7 +320,9 @@ typedef struct {
  * discards the first iteration, writes per-layer means.  Every layer is copied (into a slot)
  * and timed regardless of residency.  Three more sequential passes without per-layer events and three
  * trains of all the layers' copies are each timed in one piece (c_fence_ms, c_dma_cont_ms).  Then all layers are run back to back without copies (on
- * whatever parameters the slot holds: same shapes, same cost) to time them under continuous load.  out: host array
+ * whatever parameters the slot holds: same shapes, same cost) to time them under continuous load, and again with the
+ * event protocol of a streamed layer around every layer (c_fence_hot_ms) and next to a train of copies
+ * (c_exe_loaded_ms), each in turn with a plain run.  out: host array
  * [n_layers].  A last sequential pass with every layer's own parameters leaves the KV-cache rows pos0 .. pos0+n_tokens-1
  * as a real pass over x_dev writes them.  The call's temporaries (an activation block, weight copies for the continuous
  * run) come out of the arena and are returned before it ends; dl_arena_stats' peak does not include them. */
@@ -413,12 +423,18 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
  * c_exe_idle_ms (NULL = same as c_exe_ms): time of invocation j when the compute queue sat idle
  * waiting for its copy right before it (a GPU that idled runs the next kernels slower than one
  * kept busy; dl_profile measures both).  c_fence_ms (NULL = zeros): time added on the compute queue to
- * every streamed invocation for its two cross-stream hand-offs (dl_profile's c_fence_ms).
+ * every streamed invocation for its two cross-stream hand-offs (dl_profile's c_fence_ms).  c_fence_hot_ms (NULL =
+ * same as c_fence_ms): that time for a streamed invocation whose copy was complete when the compute queue reached
+ * it (the queue did not idle: dl_profile's c_fence_hot_ms).  c_exe_loaded_ms (NULL = no slow-down): time of
+ * invocation j if a copy ran throughout; an execution then advances at the rate c_exe / c_exe_loaded during the parts
+ * of it that overlap a copy already placed on the copy queue (with more than two slots a copy enqueued behind the
+ * execution can still start under it: that overlap is not counted).
  * mode, wrap_prefetch: as dl_set_mode; n_slots: as dl_set_slot_count (1 .. 4).  overhead_ms is added to every
  * execution (fixed host/launch cost).  Outputs (any may be NULL): total_ms; exposed_ms = time the compute queue
  * idled on DMA-done while that copy was in flight; hidden_frac = 1 - exposed / summed copy time. */
 int32_t dl_timeline(const double* c_dma_ms, const double* c_dma_cont_ms, const double* c_exe_ms,
-                    const double* c_exe_idle_ms, const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+                    const double* c_exe_idle_ms, const double* c_exe_loaded_ms, const double* c_fence_ms,
+                    const double* c_fence_hot_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
                     int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms);
 

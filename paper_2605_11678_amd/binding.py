@@ -33,8 +33,8 @@ class dl_module_desc(C.Structure):
 
 
 class dl_layer_profile(C.Structure):
-    _fields_ = [("c_dma_ms", C.c_double), ("c_dma_cont_ms", C.c_double), ("c_exe_ms", C.c_double), ("c_exe_hot_ms", C.c_double),
-                ("c_fence_ms", C.c_double), ("bytes", C.c_uint64)]
+    _fields_ = [("c_dma_ms", C.c_double), ("c_dma_cont_ms", C.c_double), ("c_exe_ms", C.c_double), ("c_exe_hot_ms", C.c_double), ("c_exe_loaded_ms", C.c_double),
+                ("c_fence_ms", C.c_double), ("c_fence_hot_ms", C.c_double), ("bytes", C.c_uint64)]
 
 
 class dl_run_stats(C.Structure):
@@ -123,7 +123,7 @@ SIGNATURES = {
     "dl_benefit": (_i32, [_f64, _f64, _i32, _PF64, _PI32, _PF64]),
     "dl_consecutive_limit": (_i32, [_f64, _f64, _PI32]),
     "dl_predict_linear": (_i32, [_f64, _f64, _i32, _PF64]),
-    "dl_timeline": (_i32, [_PF64, _PF64, _PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
+    "dl_timeline": (_i32, [_PF64, _PF64, _PF64, _PF64, _PF64, _PF64, _PF64, C.POINTER(C.c_uint8), C.POINTER(C.c_uint8), _PI32, _i32, _i32, _i32,
                            _i32, _f64, _PF64, _PF64, _PF64]),
     "dl_set_slot_count": (_i32, [_p, _i32]),
     "dl_module_set_max_tokens": (_i32, [_p, _i32, _i32]),
@@ -314,7 +314,7 @@ class Context:
     def profile(self, module, n_layers, n_tokens, pos0, x_ptr, iters=4, ctx_ptr=None, n_ctx=0):
         out = (dl_layer_profile * n_layers)()
         self._ck(lib().dl_profile(self._h, module, n_tokens, pos0, _p(x_ptr), _p(ctx_ptr), n_ctx, iters, out))
-        return [dict(c_dma_ms=o.c_dma_ms, c_dma_cont_ms=o.c_dma_cont_ms, c_exe_ms=o.c_exe_ms, c_exe_hot_ms=o.c_exe_hot_ms, c_fence_ms=o.c_fence_ms,
+        return [dict(c_dma_ms=o.c_dma_ms, c_dma_cont_ms=o.c_dma_cont_ms, c_exe_ms=o.c_exe_ms, c_exe_hot_ms=o.c_exe_hot_ms, c_exe_loaded_ms=o.c_exe_loaded_ms, c_fence_ms=o.c_fence_ms, c_fence_hot_ms=o.c_fence_hot_ms,
                      bytes=o.bytes) for o in out]
 
     def set_timing(self, on):
@@ -416,13 +416,15 @@ def predict_linear(c_total0_ms, slope_ms_per_layer, k):
 
 
 def timeline(c_dma_ms, c_exe_ms, streamed, pass_start, module_id=None, mode=DL_MODE_PIPELINED, wrap_prefetch=0,
-             overhead_ms=0.0, c_exe_idle_ms=None, c_fence_ms=None, n_slots=2, c_dma_cont_ms=None):
+             overhead_ms=0.0, c_exe_idle_ms=None, c_fence_ms=None, n_slots=2, c_dma_cont_ms=None, c_fence_hot_ms=None, c_exe_loaded_ms=None):
     n = len(c_dma_ms)
     tot, hid, exp_ = _f64(), _f64(), _f64()
     rc = lib().dl_timeline(_arr(_f64, c_dma_ms), None if c_dma_cont_ms is None else _arr(_f64, c_dma_cont_ms),
                            _arr(_f64, c_exe_ms),
                            None if c_exe_idle_ms is None else _arr(_f64, c_exe_idle_ms),
+                           None if c_exe_loaded_ms is None else _arr(_f64, c_exe_loaded_ms),
                            None if c_fence_ms is None else _arr(_f64, c_fence_ms),
+                           None if c_fence_hot_ms is None else _arr(_f64, c_fence_hot_ms),
                            _arr(C.c_uint8, [1 if s else 0 for s in streamed]),
                            _arr(C.c_uint8, [1 if s else 0 for s in pass_start]),
                            None if module_id is None else _arr(_i32, module_id), n, mode, int(wrap_prefetch),

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -96,7 +97,7 @@ struct dl_ctx {
     hipEvent_t ev_dma[dl::kMaxSlots] = {}, ev_comp[dl::kMaxSlots] = {}, ev_pass = nullptr;
     bool events_made = false;
     static constexpr int kMaxRunAhead = 8;
-    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // end of the most recent streaming passes on the compute stream (host throttle)
+    hipEvent_t ev_inflight[kMaxRunAhead] = {};   // start of the last layer of the most recent streaming passes (host throttle)
     uint64_t n_passes = 0;                       // streaming passes enqueued so far
     int32_t run_ahead = 1;                        // streaming passes that may be unfinished; 0 = unlimited
     int32_t mode = DL_MODE_PIPELINED, wrap = 0;
@@ -581,8 +582,16 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
     for (const dl_trace_op& o : ops) has_copy = has_copy || o.op == DL_OP_COPY;
     if (has_copy && c->run_ahead > 0 && c->n_passes >= uint64_t(c->run_ahead))
         DL_HIP(c, hipEventSynchronize(c->ev_inflight[(c->n_passes - uint64_t(c->run_ahead)) % dl_ctx::kMaxRunAhead]));
+    // The throttle's event goes in front of the pass's last layer, not behind it: the host then has that layer's
+    // execution time to enqueue the head of the next pass, and the GPU does not sit idle between two streaming passes
+    // while the host wakes up and launches (70 us per pass of the 27-layer encoder).
+    const dl_trace_op* last_exec = nullptr;
+    for (const dl_trace_op& o : ops)
+        if (o.op == DL_OP_EXEC) last_exec = &o;
     for (const dl_trace_op& o : ops) {
         hipStream_t st = o.queue == 0 ? c->s_compute : c->s_copy;
+        if (has_copy && &o == last_exec)
+            DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_compute));
         switch (o.op) {
             case DL_OP_WAIT:
                 DL_HIP(c, hipStreamWaitEvent(st, event_of(c, o), 0));
@@ -630,10 +639,7 @@ int32_t run_pass(dl_ctx* c, int32_t mi, const float* x, float* y, int32_t T, int
             default: break;
         }
     }
-    if (has_copy) {
-        DL_HIP(c, hipEventRecord(c->ev_inflight[c->n_passes % dl_ctx::kMaxRunAhead], c->s_compute));
-        ++c->n_passes;
-    }
+    if (has_copy) ++c->n_passes;
     return DL_OK;
 }
 
@@ -1347,6 +1353,9 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     double timed_span = 0.0;         // first copy start -> last kernel end of the passes with timing events, summed
     double fence_excess = 0.0;       // per layer: what the timing events added to a sequential pass
     double cont_scale = 1.0;         // copy time inside a train of copies / isolated copy time
+    double hot_total = 0.0;          // the uninterrupted run of all layers, median
+    double fence_hot = 0.0;          // per layer: what the event protocol of a streamed layer adds to that run
+    double load_scale = 1.0;         // that run next to a train of copies / that run alone
     for (int32_t it = 0; it < iters && rc == DL_OK; ++it) {
         rc = run_pass(c, module, static_cast<const float*>(x), scratch, T, pos0, static_cast<const float*>(ctx), n_ctx, true);
         if (rc) break;
@@ -1485,33 +1494,90 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
     }
     // The event pairs between the layers drain the queue (a few microseconds per layer, which is percents for short
     // layers): runs with events only around the whole stack give the true total, and the per-layer figures are scaled
-    // to it.  Three such runs, the median counts: the part's clock under load wanders by a percent or two from one
-    // pass to the next, and a single slow pass would put that into every prediction made from this profile.
+    // to it.  Three variants of that run, each taken in turn with a plain one (three rounds,
+    // medians) because the part's clock under sustained load drifts by a percent or two over the tens of passes of a
+    // profile, which is as much as the two effects the variants are there to measure:
+    //  * plain: all layers back to back;
+    //  * with what a streamed layer puts on the compute stream when its copy is done before the layer's turn: in
+    //    front of the layer a wait on an event that the copy stream records behind a (tiny) copy of its own - a fresh
+    //    event per layer, so that the wait is a real one with its acquire of what the copy wrote, not one the runtime
+    //    can drop because the event is known to be complete - and behind the layer an event record that the copy
+    //    stream waits for (a record nobody waits for costs a third: 7 against 24 us per 27-layer-encoder layer).  The
+    //    difference to the plain run, per layer, is the hand-off cost of a streamed layer in a pass that is bound by
+    //    execution;
+    //  * next to a train of copies that lasts at least as long as the run: host-to-device copies write to HBM
+    //    through the same fabric the kernels read through, and a pass that streams some layers while it is bound by
+    //    execution runs its kernels a few percent slower than this profile's copy-free runs.  The layers read the
+    //    temporary weight copies only (the train overwrites the slots); without any they share the slots, which
+    //    changes values, not times.
     if (rc == DL_OK) {
-        constexpr int32_t kWhole = 3;
-        double totals[kWhole] = {0, 0, 0};
-        for (int32_t rep = 0; rep < kWhole && rc == DL_OK; ++rep) {
+        constexpr int32_t kRounds = 3;
+        double plain[kRounds] = {0, 0, 0}, with_ops[kRounds] = {0, 0, 0}, loaded[kRounds] = {0, 0, 0};
+        std::vector<hipEvent_t> fresh(size_t(Ln), nullptr);
+        std::vector<hipEvent_t> released(size_t(Ln), nullptr);
+        for (int32_t i = 0; i < Ln && rc == DL_OK; ++i) rc = timing_event(c, &fresh[size_t(i)]);
+        for (int32_t i = 0; i < Ln && rc == DL_OK; ++i) rc = timing_event(c, &released[size_t(i)]);
+        double dma_mean = 0.0, hot_sum = 0.0;
+        for (int32_t i = 0; i < Ln; ++i) { dma_mean += dma[size_t(i)]; hot_sum += hot[size_t(i)]; }
+        dma_mean = dma_mean / double(iters - 1) / double(Ln) * cont_scale;
+        const int32_t n_train = dma_mean > 0.0 ? int32_t(std::min(4096.0, std::ceil(1.15 * hot_sum / dma_mean) + 1.0)) : 0;
+        std::vector<uint64_t> rot2(rot_tmp.begin(), rot_tmp.end());
+        if (rot2.empty()) rot2 = rot;
+        // variant 0 plain, 1 with the event protocol, 2 next to the train of copies
+        auto whole_run = [&](int32_t variant, double* ms_out) -> int32_t {
             hipEvent_t e0 = nullptr, e1 = nullptr;
-            rc = timing_event(c, &e0);
-            if (rc == DL_OK) rc = timing_event(c, &e1);
-            if (rc) break;
-            (void)hipEventRecord(e0, c->s_compute);
-            for (int32_t i = 0; i < Ln; ++i)
-                run_layer(c, *M, i, c->base + rot[size_t(i) % rot.size()], i == 0 ? static_cast<const float*>(x) : scratch,
+            int32_t r = timing_event(c, &e0);
+            if (r == DL_OK) r = timing_event(c, &e1);
+            if (r) return r;
+            bool ok = true;
+            if (variant == 2)
+                for (int32_t i = 0; i < n_train && ok; ++i)
+                    ok = hipMemcpyAsync(c->base + c->slot_off[i % c->slots_held], M->store + size_t(i % Ln) * M->L.bytes,
+                                        M->L.bytes, hipMemcpyHostToDevice, c->s_copy) == hipSuccess;
+            const std::vector<uint64_t>& from = variant == 2 ? rot2 : rot;
+            ok = ok && hipEventRecord(e0, c->s_compute) == hipSuccess;
+            for (int32_t i = 0; i < Ln && ok; ++i) {
+                if (variant == 1)
+                    ok = hipMemcpyAsync(c->base + c->slot_off[0], M->store + size_t(i) * M->L.bytes, 256, hipMemcpyHostToDevice,
+                                        c->s_copy) == hipSuccess &&
+                         hipEventRecord(fresh[size_t(i)], c->s_copy) == hipSuccess &&
+                         hipStreamWaitEvent(c->s_compute, fresh[size_t(i)], 0) == hipSuccess;
+                run_layer(c, *M, i, c->base + from[size_t(i) % from.size()], i == 0 ? static_cast<const float*>(x) : scratch,
                           scratch, T, pos0, static_cast<const float*>(ctx), n_ctx);
-            (void)hipEventRecord(e1, c->s_compute);
+                if (variant == 1)
+                    ok = ok && hipEventRecord(released[size_t(i)], c->s_compute) == hipSuccess &&
+                         hipStreamWaitEvent(c->s_copy, released[size_t(i)], 0) == hipSuccess;
+            }
             float total = 0.0f;
-            if (hipStreamSynchronize(c->s_compute) != hipSuccess || hipEventElapsedTime(&total, e0, e1) != hipSuccess)
-                rc = fail(c, DL_ERR_DEVICE, "timing the uninterrupted run failed");
-            totals[rep] = double(total);
+            ok = ok && hipEventRecord(e1, c->s_compute) == hipSuccess;
+            if (hipStreamSynchronize(c->s_compute) != hipSuccess || hipStreamSynchronize(c->s_copy) != hipSuccess || !ok ||
+                hipEventElapsedTime(&total, e0, e1) != hipSuccess)
+                return fail(c, DL_ERR_DEVICE, "timing an uninterrupted run failed");
+            *ms_out = double(total);
+            return DL_OK;
+        };
+        // the runs next to copies come last and have plain runs of their own to be compared with: the copy engines add
+        // to the board's power, and the plain run right behind such a run is 2-4 % slower than one in a copy-free
+        // sequence (which is what a pass over resident layers is)
+        double plain_b[kRounds] = {0, 0, 0};
+        for (int32_t round = 0; round < kRounds && rc == DL_OK; ++round) {
+            rc = whole_run(0, &plain[round]);
+            if (rc == DL_OK) rc = whole_run(1, &with_ops[round]);
+        }
+        for (int32_t round = 0; round < kRounds && rc == DL_OK && n_train > 0; ++round) {
+            rc = whole_run(0, &plain_b[round]);
+            if (rc == DL_OK) rc = whole_run(2, &loaded[round]);
         }
         if (rc == DL_OK) {
-            std::sort(totals, totals + kWhole);
-            const double total = totals[kWhole / 2];
-            double sum = 0.0;
-            for (int32_t i = 0; i < Ln; ++i) sum += hot[size_t(i)];
-            if (sum > 0.0 && total > 0.0)
-                for (int32_t i = 0; i < Ln; ++i) hot[size_t(i)] *= total / sum;
+            std::sort(plain, plain + kRounds);
+            std::sort(with_ops, with_ops + kRounds);
+            std::sort(plain_b, plain_b + kRounds);
+            std::sort(loaded, loaded + kRounds);
+            hot_total = plain[kRounds / 2];
+            if (hot_sum > 0.0 && hot_total > 0.0)
+                for (int32_t i = 0; i < Ln; ++i) hot[size_t(i)] *= hot_total / hot_sum;
+            if (hot_total > 0.0) fence_hot = std::max(0.0, with_ops[kRounds / 2] - hot_total) / double(Ln);
+            if (n_train > 0 && plain_b[kRounds / 2] > 0.0) load_scale = std::max(1.0, loaded[kRounds / 2] / plain_b[kRounds / 2]);
         }
     }
     // The continuous runs executed every layer on rotated parameters and appended THOSE keys and values at pos0..:
@@ -1542,7 +1608,9 @@ int32_t dl_profile(dl_ctx* c, int32_t module, int32_t T, int32_t pos0, const voi
         out[i].c_dma_cont_ms = out[i].c_dma_ms * cont_scale;
         out[i].c_exe_ms = exe[size_t(i)] / (iters - 1);
         out[i].c_exe_hot_ms = hot[size_t(i)];
+        out[i].c_exe_loaded_ms = hot[size_t(i)] * load_scale;
         out[i].c_fence_ms = std::max(0.0, fence[size_t(i)] / (iters - 1) - fence_excess);
+        out[i].c_fence_hot_ms = fence_hot;
         out[i].bytes = M->L.bytes;
     }
     return DL_OK;

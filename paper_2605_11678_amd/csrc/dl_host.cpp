@@ -4,6 +4,7 @@
 #include "dl_internal.hpp"
 
 #include <algorithm>
+#include <utility>
 #include <cmath>
 #include <cstring>
 
@@ -490,7 +491,8 @@ int32_t dl_predict_linear(double c_total0_ms, double slope_ms_per_layer, int32_t
 }
 
 int32_t dl_timeline(const double* c_dma_ms, const double* c_dma_cont_ms, const double* c_exe_ms,
-                    const double* c_exe_idle_ms, const double* c_fence_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
+                    const double* c_exe_idle_ms, const double* c_exe_loaded_ms, const double* c_fence_ms,
+                    const double* c_fence_hot_ms, const uint8_t* streamed, const uint8_t* pass_start, const int32_t* module_id, int32_t n,
                     int32_t mode, int32_t wrap_prefetch, int32_t n_slots, double overhead_ms,
                     double* total_ms, double* hidden_frac, double* exposed_ms) {
     if (n < 0 || (n > 0 && (!c_dma_ms || !c_exe_ms || !streamed || !pass_start))) return DL_ERR_INVALID_ARG;
@@ -512,6 +514,8 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_dma_cont_ms, const d
     double ev_dma[dl::kMaxSlots] = {0, 0, 0, 0}, ev_comp[dl::kMaxSlots] = {0, 0, 0, 0}, ev_pass = 0;
     double copy_start[dl::kMaxSlots] = {0, 0, 0, 0}, copy_dur[dl::kMaxSlots] = {0, 0, 0, 0};
     double exposed = 0, dma_sum = 0;
+    std::vector<std::pair<double, double>> copy_busy;   // [start, end) of every copy placed so far, in queue order
+    size_t first_live = 0;                               // copies before this index ended before the compute queue's clock
     double last_copy_end = -1.0;                 // copy-queue clock when its latest copy ended (no copy yet: none)
     bool idled = false;                          // the compute queue waited for the copy of the next layer
     std::vector<dl_trace_op> ops;
@@ -555,15 +559,38 @@ int32_t dl_timeline(const double* c_dma_ms, const double* c_dma_cont_ms, const d
                     const double dur = (c_dma_cont_ms && t[q] == last_copy_end) ? c_dma_cont_ms[jj] : c_dma_ms[jj];
                     copy_start[o.slot] = t[q];
                     copy_dur[o.slot] = dur;
+                    copy_busy.emplace_back(t[q], t[q] + dur);
                     t[q] += dur;
                     last_copy_end = t[q];
                     break;
                 }
-                case DL_OP_EXEC:
-                    t[q] += ((idled && c_exe_idle_ms) ? c_exe_idle_ms[j] : c_exe_ms[j]) + overhead_ms +
-                            ((o.slot >= 0 && c_fence_ms) ? c_fence_ms[j] : 0.0);
+                case DL_OP_EXEC: {
+                    const double exe = (idled && c_exe_idle_ms) ? c_exe_idle_ms[j] : c_exe_ms[j];
+                    const double rest = overhead_ms +
+                        ((o.slot >= 0 && c_fence_ms) ? ((!idled && c_fence_hot_ms) ? c_fence_hot_ms[j] : c_fence_ms[j]) : 0.0);
+                    const double slow = (c_exe_loaded_ms && c_exe_ms[j] > 0.0) ? std::max(1.0, c_exe_loaded_ms[j] / c_exe_ms[j]) : 1.0;
+                    double now = t[q], left = exe;
+                    if (slow > 1.0) {
+                        // the execution advances at 1 / slow while a copy is in flight
+                        while (first_live < copy_busy.size() && copy_busy[first_live].second <= now) ++first_live;
+                        for (size_t ci = first_live; ci < copy_busy.size() && left > 0.0; ++ci) {
+                            const double cs = copy_busy[ci].first, ce = copy_busy[ci].second;
+                            if (ce <= now) continue;
+                            if (cs > now) {
+                                const double free_run = std::min(left, cs - now);
+                                now += free_run;
+                                left -= free_run;
+                                if (left <= 0.0) break;
+                            }
+                            const double under = (ce - now) / slow;        // work done until this copy ends
+                            if (under >= left) { now += left * slow; left = 0.0; }
+                            else { now = ce; left -= under; }
+                        }
+                    }
+                    t[q] = now + left + rest;
                     idled = false;
                     break;
+                }
                 default: break;
             }
         }

@@ -41,6 +41,10 @@ def test_profile_returns_table3_quantities():
             assert r["c_exe_hot_ms"] <= r["c_exe_ms"] * 1.25
             # a copy inside a train of copies is not slower than an isolated one, and still bounded by the link
             assert packed / 63e9 * 1e3 * 0.95 <= r["c_dma_cont_ms"] <= r["c_dma_ms"]
+            # the event protocol of a streamed layer costs the compute stream something, but not a layer's time
+            assert 0.0 <= r["c_fence_hot_ms"] <= 0.5 * r["c_exe_hot_ms"]
+            # kernels next to a train of copies are not faster than alone, and not slower by more than half
+            assert r["c_exe_hot_ms"] <= r["c_exe_loaded_ms"] <= 1.5 * r["c_exe_hot_ms"]
         # layers of one module are identical in structure and timing (Sec. II-C)
         exe = np.array([r["c_exe_ms"] for r in prof])
         assert exe.max() <= 1.5 * exe.min()
@@ -202,7 +206,8 @@ def test_pipelined_mode_overlaps_copies_with_execution():
         rows = [(r["c_dma_ms"], r["c_exe_hot_ms"]) for r in prof]
         args = ([r[0] for r in rows], [r[1] for r in rows], [True] * L, [i == 0 for i in range(L)])
         kw = dict(c_exe_idle_ms=[r["c_exe_ms"] for r in prof], c_fence_ms=[r["c_fence_ms"] for r in prof],
-                  c_dma_cont_ms=[r["c_dma_cont_ms"] for r in prof])
+                  c_dma_cont_ms=[r["c_dma_cont_ms"] for r in prof], c_fence_hot_ms=[r["c_fence_hot_ms"] for r in prof],
+                  c_exe_loaded_ms=[r["c_exe_loaded_ms"] for r in prof])
         pred_pipe = B.timeline(*args, **kw)["total"]
         pred_seq = B.timeline(*args, mode=B.DL_MODE_SEQUENTIAL, **kw)["total"]
         assert abs(pred_pipe - pipe) <= 0.15 * pipe and abs(pred_seq - seq) <= 0.15 * seq, (pred_pipe, pipe, pred_seq, seq)

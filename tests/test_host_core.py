@@ -193,6 +193,66 @@ def test_timeline_copy_trains_take_the_continuous_copy_time():
         assert faster["total"] >= B.timeline([0.8 * v for v in dma], exe, mask, ps, wrap_prefetch=trial % 2)["total"] - 1e-12
 
 
+def test_timeline_hand_off_cost_depends_on_whether_the_copy_was_exposed():
+    """c_fence_hot_ms is charged to a streamed layer whose copy was complete when the compute queue reached it,
+    c_fence_ms to one the queue had to wait for; NULL keeps one figure for both."""
+    L = 8
+    st, ps = [True] * L, [i == 0 for i in range(L)]
+    f, fh = 0.3, 0.1
+    # execution-bound (two slots): only the first layer waits for its copy
+    d, e = 1.0, 5.0
+    got = B.timeline([d] * L, [e] * L, st, ps, c_fence_ms=[f] * L, c_fence_hot_ms=[fh] * L)
+    assert got["total"] == pytest.approx(d + L * e + f + (L - 1) * fh)
+    # copy-bound: every layer waits for its copy
+    d, e = 4.0, 1.0
+    got = B.timeline([d] * L, [e] * L, st, ps, c_fence_ms=[f] * L, c_fence_hot_ms=[fh] * L)
+    assert got["total"] == pytest.approx(L * d + e + f)
+    # resident layers carry neither
+    got = B.timeline([d] * L, [e] * L, [False] * L, ps, c_fence_ms=[f] * L, c_fence_hot_ms=[fh] * L)
+    assert got["total"] == pytest.approx(L * e)
+    # without the second array the first one is used throughout (the oracle's recurrence)
+    a = B.timeline([1.0] * L, [5.0] * L, st, ps, c_fence_ms=[f] * L)
+    b = B.timeline([1.0] * L, [5.0] * L, st, ps, c_fence_ms=[f] * L, c_fence_hot_ms=[f] * L)
+    assert a == b and a["total"] == pytest.approx(1.0 + L * 5.0 + L * f)
+
+
+def test_timeline_execution_slows_down_under_a_copy():
+    """c_exe_loaded_ms: an execution advances at c_exe / c_exe_loaded while a copy is in flight.  Closed forms for
+    the execution-bound and the copy-bound pass, partial overlap, and no effect without copies or with equal arrays."""
+    L = 6
+    st, ps = [True] * L, [i == 0 for i in range(L)]
+    # execution-bound, two slots: every layer but the last runs next to the whole copy of its successor (1.0 of wall
+    # time does 1 / 1.2 of work), the last one next to none
+    d, e, k = 1.0, 5.0, 1.2
+    got = B.timeline([d] * L, [e] * L, st, ps, c_exe_loaded_ms=[k * e] * L)
+    assert got["total"] == pytest.approx(d + (L - 1) * (e + d * (1 - 1 / k)) + e)
+    # copy-bound: a layer runs entirely under the next copy (e * k < d), the last one alone
+    d, e = 4.0, 1.0
+    got = B.timeline([d] * L, [e] * L, st, ps, c_exe_loaded_ms=[k * e] * L)
+    assert got["total"] == pytest.approx(L * d + e)
+    assert B.timeline([d] * 1, [e] * 1, [True], [True], c_exe_loaded_ms=[k * e])["total"] == pytest.approx(d + e)
+    # a resident layer behind a streamed one runs under the copy of the streamed layer after it:
+    # copies [0,2) and [2,4); layer 0 runs 2 -> 3.2 (1 of work under a copy), layer 1 (resident, 3 of work): 0.8 of wall
+    # under the copy does 2/3 of work, the other 7/3 alone -> 6.3333; layer 2 alone
+    got = B.timeline([2.0, 9.9, 2.0], [1.0, 3.0, 1.0], [True, False, True], [True, False, False],
+                     c_exe_loaded_ms=[1.2, 3.6, 1.2])
+    assert got["total"] == pytest.approx(3.2 + 0.8 + (3.0 - 0.8 / 1.2) + 1.0)
+    # no copies: nothing changes; equal arrays: nothing changes
+    a = B.timeline([d] * L, [e] * L, [False] * L, ps, c_exe_loaded_ms=[k * e] * L)
+    assert a["total"] == pytest.approx(L * e)
+    rnd = random.Random(9)
+    for trial in range(60):
+        n = rnd.randint(1, 8)
+        dma = [rnd.uniform(0.1, 5) for _ in range(n)]
+        exe = [rnd.uniform(0.1, 5) for _ in range(n)]
+        mask = [rnd.random() < 0.7 for _ in range(n)]
+        p2 = [i == 0 for i in range(n)]
+        base = B.timeline(dma, exe, mask, p2)
+        assert B.timeline(dma, exe, mask, p2, c_exe_loaded_ms=list(exe)) == base
+        slower = B.timeline(dma, exe, mask, p2, c_exe_loaded_ms=[1.3 * v for v in exe])
+        assert base["total"] - 1e-12 <= slower["total"] <= B.timeline(dma, [1.3 * v for v in exe], mask, p2)["total"] + 1e-12
+
+
 def test_timeline_closed_forms_eq5_eq6_eq7():
     L, R = 36, 21
     uni = lambda d, e: [(d, e, True)] * L
