@@ -10,7 +10,7 @@
 //    each owns a (BM/2)x(BN/2) tile, up to 4x4 MFMA tiles = 256 fp32 accumulators per lane) or stacked 4x1 (WM = 4);
 //    one workgroup per CU for the 192- and 256-row tiles, two for 128x192 and 128x128.  BNR <= BN columns are stored
 //    (128x144 of a 128x160 tile puts exactly one workgroup on every CU for N = 1152).  k-tile 64: a row of a tile is
-//    one 128-byte cache line.  Tiles go global -> LDS directly (global_load_lds_dwordx4, no staging registers) into
+//    one 128-byte cache line.  Tiles go global -> LDS directly (buffer_load_dwordx4 ... lds, no staging registers) into
 //    NS = 2 (4 for the small tile with long reductions) LDS stages that are separate arrays, so the compiler can tell
 //    the stage being filled from the one being read; the wait for a copy is an explicit s_waitcnt.  LDS rows are
 //    128 bytes, unpadded (a wavefront's copy fills 1 KB = 8 rows contiguously); the 16-byte chunk index is
