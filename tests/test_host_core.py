@@ -704,6 +704,22 @@ def test_kv_cache_module_limits_query_heads_per_kv_head():
     eng.close()
 
 
+def test_module_whose_operands_would_pass_4_gb_is_refused():
+    """The kernels address an operand (an activation matrix, one head's keys) with 32-bit byte offsets; a descriptor
+    whose longest pass times its widest row does not fit them is refused when the module is created."""
+    eng = Engine(1 << 26, device=-1)
+    c = CFG.decoder_8b(n_layers=1, vocab=0)
+    ok = desc_fields(c, 16384)
+    ok["max_seq"] = 16384
+    eng.ctx.module_create(**ok)                        # 16384 x 24576 x 4 B = 1.6 GB: fine
+    too_long = dict(ok)
+    too_long["max_seq"] = too_long["max_tokens"] = 65536
+    with pytest.raises(B.DLError) as e:
+        eng.ctx.module_create(**too_long)
+    assert e.value.code == B.DL_ERR_INVALID_ARG and "4 GB" in str(e.value)
+    eng.close()
+
+
 def test_vla_infer_records_the_five_stages_and_checks_shapes():
     """dl_vla_infer on a host-only context: the recorded schedule is one encoder pass, one prefill pass, n_decode
     single-token passes and n_euler action passes, in that order; mismatching shapes are refused before anything is
