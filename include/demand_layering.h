@@ -128,7 +128,10 @@ int32_t dl_set_streams(dl_ctx* ctx, void* compute_stream, void* copy_stream);
 /* ---- registering a layer stack (one-time, untimed) ------------------------------------- */
 
 /* Allocates the module's pinned host parameter store (Sec. IV-C(iii)), one contiguous
- * kernel-ready blob per layer so that a layer is ONE host-to-device copy. */
+ * kernel-ready blob per layer so that a layer is ONE host-to-device copy.  DL_ERR_INVALID_ARG for a description outside
+ * the limits noted in dl_module_desc, for more than 32 query heads per KV head on a module with a KV cache, and when
+ * max(max_seq, max_tokens, max_ctx) times the widest row of the module (2 * d_ff for SwiGLU) times 4 bytes reaches
+ * 4 GB (the kernels address one operand with 32-bit byte offsets). */
 int32_t dl_module_create(dl_ctx* ctx, const dl_module_desc* desc, int32_t* module_out);
 /* host_bf16: host pointer, n_elems BF16 values, shape fixed by the descriptor (see DL_T_*).
  * The data is COPIED into the packed blob (fused / interleaved as the kernels read it). */
